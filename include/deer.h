@@ -1,0 +1,181 @@
+/* deer.h - C ABI of libdeer: DEER's draft-verify step on one AMD MI355X (gfx950).
+ *
+ * One iteration of the paper's inference loop (Algorithm 1, body of the while):
+ *     deer_draft_block        y^_{j+1:j+k} ~ q_theta(. | x_{1:j})        (Sec. 3.2, first display)
+ *     deer_verify_block       p_AR(. | x_{1:j+i-1}), i = 1..k, one pass  (Sec. 3.2, Eq. "accept")
+ *     deer_accept_and_commit  accept / residual-resample, append, j <- length(x)
+ *                                                     (Sec. 3.2 Eq. "accept", "resample"; Alg. 1)
+ * preceded once per batch of sequences by deer_init_models, deer_load_tensor (weights) and
+ * deer_prefill (build both KV caches for the prefix x_{1:j}; Alg. 1 "Input").
+ *
+ * Conventions
+ *  - Plain C.  No exceptions cross the boundary.  Every call returns a deer_status; on failure
+ *    nothing observable has changed except for DEER_EHIP (a HIP call failed mid-way; destroy the
+ *    context).  deer_last_error() gives a human-readable string for the last failure.
+ *  - "dev" pointers are device (HBM) addresses on the context's device, "host" pointers are
+ *    ordinary host memory.  The library NEVER allocates or frees device memory: the caller
+ *    allocates the buffers whose sizes deer_query_sizes reports (e.g. as torch tensors), passes
+ *    them to deer_init_models, and keeps them alive until deer_destroy.
+ *  - All device work is enqueued on the hipStream_t given at init.  deer_draft_block and
+ *    deer_verify_block return without waiting; deer_accept_and_commit and deer_prefill wait for
+ *    the stream before they return (they hand results to the host).
+ *  - Call order per batch:  init -> load_tensor* -> prefill -> { draft -> verify -> accept }*.
+ *    A call out of order returns DEER_ESTATE.
+ *  - Token positions are 0-indexed: committed token x_t (1-indexed in the paper) sits at position
+ *    and cache slot t-1.  The target cache holds x_{1:j-1}; x_j is "pending" and is the first row
+ *    of the next verify pass, so verify sees exactly k rows [x_j, y^_1 .. y^_{k-1}] and yields
+ *    p_1 .. p_k (no bonus token: the largest accepted length is k, as in the paper's Table 4).
+ *  - Acceptance stops at the first rejected draft; that position receives the residual sample
+ *    (T > 0) or the target's argmax (T = 0) and the rest of the block is discarded.
+ */
+#ifndef DEER_H
+#define DEER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DEER_ABI_VERSION 1u
+
+typedef enum {
+    DEER_OK = 0,
+    DEER_EINVAL = -1,    /* null pointer, k < 1, k > max_k, T < 0, batch > max_batch, bad shape      */
+    DEER_ESTATE = -2,    /* call out of order                                                       */
+    DEER_ECAPACITY = -3, /* a sequence would exceed max_seq, or a caller buffer is too small        */
+    DEER_EHIP = -4,      /* a HIP runtime call failed; see deer_last_error                          */
+    DEER_EVERSION = -5   /* struct_size / abi_version mismatch                                      */
+} deer_status;
+
+enum { DEER_TARGET = 0, DEER_DRAFTER = 1 };
+enum { DEER_F32 = 0, DEER_BF16 = 1 };
+
+/* Tensor ids for deer_load_tensor.  Every projection is given in [in][out] row-major order
+ * (y = x W); the embedding table is [vocab][d_model]. */
+enum {
+    DEER_T_EMBED = 1, DEER_T_LM_HEAD = 2, DEER_T_WQ = 3, DEER_T_WK = 4, DEER_T_WV = 5, DEER_T_WO = 6,
+    DEER_T_WG = 7, DEER_T_WU = 8, DEER_T_WD = 9, DEER_T_ROUTER = 10
+};
+
+/* Decoder shape (pre-norm, RMSNorm with unit gains, GQA attention with rotate-half RoPE, SwiGLU
+ * FFN, untied LM head, no biases).  n_experts = 0 selects a dense FFN of width d_ff; otherwise
+ * a top_k-of-n_experts mixture (softmax over all experts, top_k kept, renormalised) with expert
+ * width d_ff_expert. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+    int32_t n_experts, top_k, d_ff_expert;
+    float rope_base, rms_eps;
+} deer_model_cfg;
+
+typedef struct {
+    uint32_t struct_size;   /* sizeof(deer_init_params) */
+    uint32_t abi_version;   /* DEER_ABI_VERSION */
+    deer_model_cfg target, drafter;
+    int32_t max_batch;      /* sequences decoded together                                         */
+    int32_t max_seq;        /* cache slots per sequence (prefix + generated + one block)          */
+    int32_t max_k;          /* largest block size, 1..32                                          */
+    int32_t mask_token_id;  /* the drafter's [MASK] id                                            */
+    int32_t eos_token_id;   /* -1: none.  A commit is cut after the first EOS (Alg. 1, break)     */
+    int32_t keep_logits;    /* 1: materialise [B][k][vocab] fp32 logits at T = 0 too (parity)     */
+    int32_t device;         /* HIP device ordinal                                                 */
+    void *hip_stream;       /* hipStream_t, default priority; NULL = the default stream          */
+} deer_init_params;
+
+/* Bytes the caller must provide.  All buffers 256-byte aligned. */
+typedef struct {
+    size_t weights[2];   /* per model: projections in the library's tiled layout + embedding     */
+    size_t kv[2];        /* per model: K and V caches, bf16, max_batch * max_seq slots           */
+    size_t workspace;    /* activations, split-K partials, logits, per-sequence state            */
+    size_t staging;      /* scratch that deer_load_tensor needs beyond the source tensor: 0      */
+} deer_sizes;
+
+typedef struct {
+    void *weights[2];    /* dev */
+    void *kv[2];         /* dev */
+    void *workspace;     /* dev */
+} deer_buffers;
+
+typedef struct deer_ctx deer_ctx;
+
+/* Host-only: fills *out from *p.  DEER_EINVAL on unsupported shapes (head_dim not in
+ * {32,64,128}, widths not multiples of the 128-column tile, max_k > 32, ...). */
+int deer_query_sizes(const deer_init_params *p, deer_sizes *out);
+
+/* Creates a context over caller-owned device buffers (each at least as large as
+ * deer_query_sizes reported; sizes are passed for checking).  *out is NULL on failure. */
+int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const deer_sizes *buf_sizes,
+                     deer_ctx **out);
+
+/* Copies one canonical tensor (device pointer `src_dev`, dtype DEER_F32 or DEER_BF16, `rows` x
+ * `cols` row-major) into the library's layout, converting to bf16 (round to nearest even).
+ * layer = -1 for embedding / LM head; expert = -1 unless the model is a mixture and the tensor is
+ * WG/WU/WD.  Enqueued on the stream; `src_dev` may be reused after the stream has passed it. */
+int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int expert,
+                     const void *src_dev, int src_dtype, int64_t rows, int64_t cols);
+
+/* Prefix x_{1:j} for `batch` sequences (Alg. 1, Input).  prompt_ids_host: concatenated ids;
+ * prompt_lens_host[b] >= 1.  Builds the target cache for x_{1:j-1} and the drafter cache for
+ * x_{1:j} with causal attention, in chunks of 64 rows.  Waits for completion. */
+int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *prompt_ids_host, const int32_t *prompt_lens_host);
+
+/* Sets the state as if `lens_host[b]` tokens had been prefilled, WITHOUT running the models:
+ * the caller has written cache contents itself (see deer_kv_layout) - used where a real prefill
+ * is too costly (32k-token prefixes).  last_token_host[b] = x_j, the pending token.  The drafter
+ * cache is taken to hold all lens_host[b] tokens. */
+int deer_set_prefilled(deer_ctx *c, int32_t batch, const int32_t *lens_host, const int32_t *last_token_host);
+
+/* Drafter pass (Sec. 3.2: one pass proposes the whole block; position i's law does not depend
+ * on the other drafted tokens).  Rows per sequence: the committed tokens the drafter has not
+ * cached yet (causal, appended to its cache) followed by k MASK rows at positions j..j+k-1 that
+ * see the whole cache and each other.  T = 0: y^_i = argmax (lowest index on ties); T > 0:
+ * y^_i ~ softmax(z_i / T) by Gumbel-max with the counter generator keyed by (seed, sequence,
+ * position).  Writes draft tokens to draft_tokens_dev[batch][k] (int32). */
+int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *draft_tokens_dev);
+
+/* Target pass over rows [x_j, y^_1 .. y^_{k-1}] (block-causal over the cache), reading the
+ * drafts from draft_tokens_dev[batch][k] - normally the buffer deer_draft_block filled; tests
+ * may inject blocks.  Leaves per-row argmax / log-normaliser (and logits at T > 0) on device. */
+int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_tokens_dev);
+
+/* Acceptance (Sec. 3.2 Eq. "accept"/"resample"; Alg. 1 inner loop, stopped at the first
+ * rejection) and commit: appends the accepted drafts and the correction, cuts at EOS, rolls the
+ * target cache back to (new length - 1).  Host outputs, per sequence b:
+ *   accept_len[b] in [0,k];  n_committed[b] = min(accept_len+1, k) (less after EOS);
+ *   committed[b*k .. b*k+n_committed[b]).   Waits for the stream. */
+int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed,
+                           int32_t *accept_len_host, int32_t *committed_host, int32_t *n_committed_host);
+
+int deer_destroy(deer_ctx *c);
+const char *deer_last_error(const deer_ctx *c); /* c may be NULL: last init-time error */
+
+/* ---- inspection surface used by tests and the benchmark (not part of the timed path) -------- */
+
+/* Copies the last pass's logits [batch][k][vocab] (fp32) of `model` to host; needs keep_logits
+ * or T > 0 in that pass.  Waits for the stream. */
+int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_floats);
+
+/* Replaces the commit decided by the last deer_accept_and_commit... not needed: instead, a test
+ * that must follow the oracle after a low-margin split re-prefills.  Reserved. */
+
+/* Current committed length j per sequence (host mirror). */
+int deer_get_lengths(const deer_ctx *c, int32_t *len_host);
+
+/* Where cache rows live, so that a caller can inspect or pre-fill them:
+ *   K[layer][seq][kv_head][slot][head_dim]  and  V stored transposed  Vt[layer][seq][kv_head][head_dim][slot],
+ * bf16, slot < max_seq.  Offsets are in elements from the start of the model's kv buffer. */
+typedef struct {
+    size_t k_base, v_base;            /* element offsets of K and Vt blocks                        */
+    size_t layer_stride, seq_stride, head_stride; /* same for both                                 */
+    int32_t max_seq, head_dim;
+} deer_kv_layout;
+int deer_get_kv_layout(const deer_ctx *c, int model, deer_kv_layout *out);
+
+/* Runs the weight-streaming GEMM of the verify pass alone, `iters` times, on the given layer's
+ * gate/up projection (benchmark aid; results are discarded). Reserved for profiling. */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEER_H */

@@ -86,6 +86,18 @@ def rope(x, pos, base):
     return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
 
 
+def round_to_bf16(x):
+    """Nearest bfloat16 (8 significand bits, ties to even), returned in x's dtype.  Storage
+    format only; finite inputs."""
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    keep = u >> np.uint64(16)
+    rest = u & np.uint64(0xFFFF)
+    up = (rest > 0x8000) | ((rest == 0x8000) & ((keep & np.uint64(1)) == 1))
+    keep = (keep + up.astype(np.uint64)) << np.uint64(16)
+    return keep.astype(np.uint32).view(np.float32).reshape(f.shape).astype(x.dtype)
+
+
 def gqa_attention(q, keys, vals, allowed):
     """Softmax attention with grouped K/V heads.
 
@@ -128,10 +140,14 @@ class Decoder:
     `weights(name, layer, expert)` returns the tensor in [in][out] orientation (embedding
     [vocab][d]) as exact values of the stored model; it may generate them on demand."""
 
-    def __init__(self, shape, weights, dtype=np.float64):
+    def __init__(self, shape, weights, dtype=np.float64, kv_storage=None):
+        """kv_storage: None (K,V rows kept in the compute dtype) or "bf16": every K,V row is
+        rounded to bfloat16 when it is produced, the way a bf16 KV cache stores it (the
+        workloads with bf16 weights also state a bf16 cache); arithmetic stays in `dtype`."""
         self.s = shape
         self.w = weights
         self.dtype = dtype
+        self.kv_storage = kv_storage
 
     def _w(self, name, layer=-1, expert=-1):
         return np.asarray(self.w(name, layer, expert), dtype=self.dtype)
@@ -182,6 +198,8 @@ class Decoder:
             v = (a @ self._w("wv", l)).reshape(R, s.n_kv_heads, s.head_dim)
             q = rope(q, pos, s.rope_base)
             k = rope(k, pos, s.rope_base)
+            if self.kv_storage == "bf16":
+                k, v = round_to_bf16(k), round_to_bf16(v)
             keys = np.concatenate([cache.K[l, :n_old], k], axis=0)
             vals = np.concatenate([cache.V[l, :n_old], v], axis=0)
             o = gqa_attention(q, keys, vals, allowed)

@@ -1,0 +1,585 @@
+// Host side of libdeer: context, buffer carving, call-order state machine, kernel launches.
+// The C ABI is declared in include/deer.h.  Nothing here allocates device memory.
+#include "deer_kernels.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "deer.h"
+
+using namespace deer;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+constexpr int MAX_NS = 16;          // key-range splits of block attention
+constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+struct ModelRT {
+    deer_model_cfg c{};
+    int n_qkv = 0, kattn = 0, F = 0;   // fused QKV width, Hq*hd, FFN width used by GEMMs
+    // weights (device)
+    char *w = nullptr;
+    size_t off_embed = 0, off_lm = 0, off_layers = 0, layer_bytes = 0;
+    size_t lo_qkv = 0, lo_o = 0, lo_gu = 0, lo_d = 0;   // offsets inside a layer
+    size_t weight_bytes = 0;
+    // kv (device, elements of bf16)
+    uint16_t *kv = nullptr;
+    size_t kv_k_base = 0, kv_v_base = 0, kv_layer_stride = 0, kv_seq_stride = 0, kv_head_stride = 0;
+    size_t kv_bytes = 0;
+    double *theta = nullptr;           // device [hd/2]
+};
+
+struct Work {   // carved from the workspace
+    SeqState st{};
+    RowMeta rm{};
+    float2 *cs = nullptr;
+    float *h = nullptr, *ssq = nullptr, *part = nullptr, *lmpart = nullptr;
+    uint4 *xa_hi = nullptr, *xa_lo = nullptr, *xb_hi = nullptr, *xb_lo = nullptr, *q_hi = nullptr, *q_lo = nullptr;
+    float *opart = nullptr, *mlpart = nullptr;
+    float *logits[2] = {nullptr, nullptr};
+    RowStat *stat = nullptr;
+    RowResult *res[2] = {nullptr, nullptr};
+    AcceptOut ao{};
+    int *ids = nullptr;                // prompt staging [max_seq]
+    double *theta[2] = {nullptr, nullptr};
+    size_t bytes = 0;
+};
+
+enum State { ST_INIT = 0, ST_PREFILLED, ST_DRAFTED, ST_VERIFIED };
+
+}  // namespace
+
+struct deer_ctx {
+    deer_init_params p{};
+    ModelRT m[2];
+    Work wk;
+    hipStream_t stream = nullptr;
+    State state = ST_INIT;
+    int batch = 0;
+    int cur_k = 0;
+    float cur_T = 0.f;
+    int max_tiles = 0;
+    const int *wk_draft = nullptr;   // draft buffer of the last verify_block
+    std::vector<int> h_len, h_ing_n, h_finished;
+    std::string err;
+};
+
+namespace {
+
+int fail(deer_ctx *c, int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf; else g_init_error = buf;
+    return code;
+}
+
+#define HIPCHK(c, expr)                                                                            \
+    do {                                                                                           \
+        hipError_t e_ = (expr);                                                                    \
+        if (e_ != hipSuccess) return fail((c), DEER_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+#define LAUNCHCHK(c, name)                                                                          \
+    do {                                                                                            \
+        hipError_t e_ = hipGetLastError();                                                          \
+        if (e_ != hipSuccess) return fail((c), DEER_EHIP, "launch %s: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+const char *check_model(const deer_model_cfg &c) {
+    if (c.n_layers < 1 || c.d_model < 128 || c.vocab < 128) return "n_layers/d_model/vocab too small";
+    if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return "head_dim must be 32, 64 or 128";
+    if (c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
+    if (c.d_model % CG) return "d_model must be a multiple of 128";
+    if (((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim) % CG) return "fused QKV width must be a multiple of 128";
+    if ((c.n_q_heads * c.head_dim) % 16) return "n_q_heads*head_dim must be a multiple of 16";
+    if (c.vocab % CG) return "vocab must be a multiple of 128";
+    if (c.n_experts) return "mixture-of-experts targets are not built yet";
+    if (c.d_ff < 64 || c.d_ff % 64) return "d_ff must be a multiple of 64";
+    if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return "bad rope_base / rms_eps";
+    return nullptr;
+}
+
+void plan_model(ModelRT &m, const deer_model_cfg &c, int max_batch, int max_seq) {
+    m.c = c;
+    m.n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    m.kattn = c.n_q_heads * c.head_dim;
+    m.F = c.d_ff;
+    size_t d = c.d_model;
+    m.off_embed = 0;
+    m.off_lm = align_up((size_t)c.vocab * d * 2);
+    m.off_layers = m.off_lm + align_up(d * (size_t)c.vocab * 2);
+    m.lo_qkv = 0;
+    m.lo_o = m.lo_qkv + align_up(d * m.n_qkv * 2);
+    m.lo_gu = m.lo_o + align_up((size_t)m.kattn * d * 2);
+    m.lo_d = m.lo_gu + align_up(d * 2 * m.F * 2);
+    m.layer_bytes = m.lo_d + align_up((size_t)m.F * d * 2);
+    m.weight_bytes = m.off_layers + m.layer_bytes * c.n_layers;
+    m.kv_head_stride = (size_t)max_seq * c.head_dim;
+    m.kv_seq_stride = m.kv_head_stride * c.n_kv_heads;
+    m.kv_layer_stride = m.kv_seq_stride * max_batch;
+    m.kv_k_base = 0;
+    m.kv_v_base = m.kv_layer_stride * c.n_layers;
+    m.kv_bytes = align_up(2 * m.kv_layer_stride * c.n_layers * 2);
+}
+
+// Carves the workspace; with base == nullptr only computes the size.
+void plan_work(Work &w, const deer_init_params &p, char *base) {
+    const int B = p.max_batch;
+    const int MAXT = std::max(2 * B, 2), MAXR = MAXT * 32;
+    const deer_model_cfg &t = p.target, &d = p.drafter;
+    const size_t dmax = std::max(t.d_model, d.d_model);
+    const size_t kattn = std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
+    const size_t fmax = std::max(t.d_ff, d.d_ff);
+    const size_t kb = std::max(kattn, fmax);
+    const size_t hq = std::max(t.n_q_heads, d.n_q_heads);
+    const size_t hdmax = std::max(t.head_dim, d.head_dim);
+    const size_t V = std::max(t.vocab, d.vocab);
+    const size_t lmrows = (size_t)B * 32;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return base ? base + o : nullptr; };
+    w.st.len = (int *)take(B * 4); w.st.dr_len = (int *)take(B * 4); w.st.pending = (int *)take(B * 4);
+    w.st.ing_n = (int *)take(B * 4); w.st.finished = (int *)take(B * 4); w.st.ing_tok = (int *)take((size_t)B * 32 * 4);
+    w.rm.tok = (int *)take(MAXR * 4); w.rm.pos = (int *)take(MAXR * 4); w.rm.limit = (int *)take(MAXR * 4);
+    w.rm.slot = (int *)take(MAXR * 4); w.rm.tile_seq = (int *)take(MAXT * 4);
+    w.cs = (float2 *)take((size_t)MAXR * 64 * sizeof(float2));
+    w.theta[0] = (double *)take(64 * 8); w.theta[1] = (double *)take(64 * 8);
+    w.h = (float *)take((size_t)MAXR * dmax * 4);
+    w.ssq = (float *)take((size_t)MAXR * (dmax / CG) * 4);
+    w.xa_hi = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024); w.xa_lo = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024);
+    w.xb_hi = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024); w.xb_lo = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024);
+    w.q_hi = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024); w.q_lo = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024);
+    w.part = (float *)take((size_t)MAXR * PART_COLS * 4);
+    w.lmpart = (float *)take(lmrows * V * 4);
+    w.opart = (float *)take((size_t)MAXT * hq * MAX_NS * 32 * hdmax * 4);
+    w.mlpart = (float *)take((size_t)MAXT * hq * MAX_NS * 64 * 4);
+    w.logits[0] = (float *)take(lmrows * V * 4); w.logits[1] = (float *)take(lmrows * V * 4);
+    w.stat = (RowStat *)take(lmrows * (V / CG) * sizeof(RowStat));
+    w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
+    w.ao.accept_len = (int *)take(B * 4); w.ao.n_committed = (int *)take(B * 4); w.ao.committed = (int *)take((size_t)B * 32 * 4);
+    w.ids = (int *)take((size_t)p.max_seq * 4);
+    w.bytes = off;
+}
+
+const char *check_params(const deer_init_params *p) {
+    if (!p) return "null params";
+    if (p->max_batch < 1 || p->max_batch > 1024) return "max_batch out of range";
+    if (p->max_k < 1 || p->max_k > 32) return "max_k must be in 1..32";
+    if (p->max_seq < 64 || p->max_seq % 64) return "max_seq must be a positive multiple of 64";
+    if (const char *e = check_model(p->target)) return e;
+    if (const char *e = check_model(p->drafter)) return e;
+    if (p->target.vocab != p->drafter.vocab) return "target and drafter must share the vocabulary";
+    if (p->mask_token_id < 0 || p->mask_token_id >= p->drafter.vocab) return "mask_token_id outside the vocabulary";
+    if (p->eos_token_id >= p->target.vocab) return "eos_token_id outside the vocabulary";
+    return nullptr;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launches
+// ---------------------------------------------------------------------------------------------
+int choose_split(int N, int KS, int zgroups) {
+    int blocks = (N / CG) * zgroups;
+    int S = (512 + blocks - 1) / blocks;
+    S = std::min(S, std::max(1, KS / 8));            // at least 2 k-steps per wave
+    S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
+    return std::max(S, 1);
+}
+
+struct GemmOut { int S, rows_total; };
+
+int launch_gemm(deer_ctx *c, const void *W, const uint4 *xhi, const uint4 *xlo, float *part, int N, int K, int ntiles,
+                int mt0, int mt_stride, int force_S, GemmOut *o) {
+    const int KS = K / 16;
+    const int MT = (ntiles % 2 == 0) ? 2 : 1;
+    const int zg = ntiles / MT;
+    const int S = force_S > 0 ? force_S : choose_split(N, KS, zg);
+    dim3 grid(N / CG, S, zg);
+    if (MT == 2)
+        hipLaunchKernelGGL(k_gemm<2>, grid, dim3(256), 0, c->stream, (const uint4 *)W, xhi, xlo, part, N, KS, S, mt0, mt_stride, ntiles * 32);
+    else
+        hipLaunchKernelGGL(k_gemm<1>, grid, dim3(256), 0, c->stream, (const uint4 *)W, xhi, xlo, part, N, KS, S, mt0, mt_stride, ntiles * 32);
+    LAUNCHCHK(c, "k_gemm");
+    o->S = S;
+    o->rows_total = ntiles * 32;
+    return DEER_OK;
+}
+
+struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; };
+
+template <int HD>
+int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float scale_log2e) {
+    Work &w = c->wk;
+    const deer_model_cfg &mc = m.c;
+    const int G = mc.n_q_heads / mc.n_kv_heads;
+    const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
+    const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
+    hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * G * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
+                       m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart, w.mlpart,
+                       mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e);
+    LAUNCHCHK(c, "k_attn");
+    hipLaunchKernelGGL(k_attn_combine<HD>, dim3(mc.n_q_heads, ntiles), dim3(256), 0, c->stream, w.opart, w.mlpart, NS,
+                       mc.n_q_heads, scale_log2e, w.xb_hi, w.xb_lo);
+    LAUNCHCHK(c, "k_attn_combine");
+    return DEER_OK;
+}
+
+// One forward pass of `model` over the rows described by the row metadata (ntiles tiles).
+int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm) {
+    ModelRT &m = c->m[model];
+    Work &w = c->wk;
+    const deer_model_cfg &mc = m.c;
+    const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG;
+    hipStream_t s = c->stream;
+    hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
+                       w.xa_hi, w.xa_lo, w.ssq, d, ncg_d);
+    LAUNCHCHK(c, "k_embed");
+    {
+        int n = rows * (hd / 2);
+        hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, w.rm.pos, m.theta, w.cs, hd / 2, rows);
+        LAUNCHCHK(c, "k_rope_table");
+    }
+    const int nkt = (max_limit + 31) / 32;
+    int NS = (512 + mc.n_q_heads * ntiles - 1) / (mc.n_q_heads * ntiles);
+    NS = std::max(1, std::min({NS, MAX_NS, (nkt + 3) / 4}));
+    const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
+    GemmOut go{};
+    for (int l = 0; l < mc.n_layers; ++l) {
+        const char *lw = m.w + m.off_layers + (size_t)l * m.layer_bytes;
+        int rc = launch_gemm(c, lw + m.lo_qkv, w.xa_hi, w.xa_lo, w.part, m.n_qkv, d, ntiles, 0, 1, 0, &go);
+        if (rc) return rc;
+        KvView kv{m.kv + m.kv_k_base + (size_t)l * m.kv_layer_stride, m.kv + m.kv_v_base + (size_t)l * m.kv_layer_stride,
+                  m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
+        hipLaunchKernelGGL(k_epi_qkv, dim3(m.n_qkv / CG, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, m.n_qkv,
+                           w.ssq, ncg_d, d, mc.rms_eps, w.cs, w.rm, w.q_hi, w.q_lo, kv, mc.n_q_heads, mc.n_kv_heads, hd);
+        LAUNCHCHK(c, "k_epi_qkv");
+        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, scale_log2e);
+        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, scale_log2e);
+        else rc = launch_attn<32>(c, m, l, ntiles, NS, scale_log2e);
+        if (rc) return rc;
+        rc = launch_gemm(c, lw + m.lo_o, w.xb_hi, w.xb_lo, w.part, d, m.kattn, ntiles, 0, 1, 0, &go);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_epi_residual, dim3(ncg_d, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, d, w.h,
+                           w.xa_hi, w.xa_lo, w.ssq);
+        LAUNCHCHK(c, "k_epi_residual");
+        rc = launch_gemm(c, lw + m.lo_gu, w.xa_hi, w.xa_lo, w.part, 2 * m.F, d, ntiles, 0, 1, 0, &go);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_epi_swiglu, dim3(2 * m.F / CG, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, 2 * m.F,
+                           w.ssq, ncg_d, d, mc.rms_eps, w.xb_hi, w.xb_lo, m.F);
+        LAUNCHCHK(c, "k_epi_swiglu");
+        rc = launch_gemm(c, lw + m.lo_d, w.xb_hi, w.xb_lo, w.part, d, m.F, ntiles, 0, 1, 0, &go);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_epi_residual, dim3(ncg_d, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, d, w.h,
+                           w.xa_hi, w.xa_lo, w.ssq);
+        LAUNCHCHK(c, "k_epi_residual");
+    }
+    if (lm.on) {
+        const int V = mc.vocab;
+        int rc = launch_gemm(c, m.w + m.off_lm, w.xa_hi, w.xa_lo, w.lmpart, V, d, lm.n_tiles, lm.mt0, lm.mt_stride, 1, &go);
+        if (rc) return rc;
+        float *logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
+        hipLaunchKernelGGL(k_epi_lmhead, dim3(V / CG, lm.n_tiles), dim3(256), 0, s, w.lmpart, go.rows_total, V, w.ssq, ncg_d,
+                           d, mc.rms_eps, lm.mt0, lm.mt_stride, lm.k, logits, lm.T, lm.seed, w.rm.tile_seq, w.rm.pos, w.stat,
+                           V / CG);
+        LAUNCHCHK(c, "k_epi_lmhead");
+        hipLaunchKernelGGL(k_rowstat_final, dim3(lm.n_tiles * lm.k), dim3(256), 0, s, w.stat, V / CG, lm.T, w.res[model]);
+        LAUNCHCHK(c, "k_rowstat_final");
+    }
+    return DEER_OK;
+}
+
+int upload_state(deer_ctx *c, int B, const int *len, const int *dr_len, const int *pending) {
+    Work &w = c->wk;
+    std::vector<int> zeros(B, 0);
+    HIPCHK(c, hipMemcpyAsync(w.st.len, len, B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(w.st.dr_len, dr_len, B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(w.st.pending, pending, B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(w.st.ing_n, zeros.data(), B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(w.st.finished, zeros.data(), B * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->batch = B;
+    c->h_len.assign(len, len + B);
+    c->h_ing_n.assign(B, 0);
+    c->h_finished.assign(B, 0);
+    c->state = ST_PREFILLED;
+    return DEER_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+// C ABI
+// =============================================================================================
+extern "C" {
+
+int deer_query_sizes(const deer_init_params *p, deer_sizes *out) {
+    if (!out) return fail(nullptr, DEER_EINVAL, "null output");
+    if (p && (p->struct_size != sizeof(deer_init_params) || p->abi_version != DEER_ABI_VERSION))
+        return fail(nullptr, DEER_EVERSION, "struct_size/abi_version mismatch");
+    if (const char *e = check_params(p)) return fail(nullptr, DEER_EINVAL, "%s", e);
+    ModelRT m;
+    for (int i = 0; i < 2; ++i) {
+        plan_model(m, i == 0 ? p->target : p->drafter, p->max_batch, p->max_seq);
+        out->weights[i] = m.weight_bytes;
+        out->kv[i] = m.kv_bytes;
+    }
+    Work w;
+    plan_work(w, *p, nullptr);
+    out->workspace = w.bytes;
+    out->staging = 0;
+    return DEER_OK;
+}
+
+int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const deer_sizes *buf_sizes, deer_ctx **out) {
+    if (out) *out = nullptr;
+    if (!out || !bufs || !buf_sizes) return fail(nullptr, DEER_EINVAL, "null argument");
+    deer_sizes need;
+    int rc = deer_query_sizes(p, &need);
+    if (rc) return rc;
+    for (int i = 0; i < 2; ++i) {
+        if (!bufs->weights[i] || !bufs->kv[i]) return fail(nullptr, DEER_EINVAL, "null device buffer");
+        if (buf_sizes->weights[i] < need.weights[i] || buf_sizes->kv[i] < need.kv[i])
+            return fail(nullptr, DEER_ECAPACITY, "weights/kv buffer %d too small", i);
+    }
+    if (!bufs->workspace) return fail(nullptr, DEER_EINVAL, "null workspace");
+    if (buf_sizes->workspace < need.workspace) return fail(nullptr, DEER_ECAPACITY, "workspace too small");
+    deer_ctx *c = new (std::nothrow) deer_ctx();
+    if (!c) return fail(nullptr, DEER_EINVAL, "out of host memory");
+    c->p = *p;
+    c->stream = (hipStream_t)p->hip_stream;
+    hipError_t e = hipSetDevice(p->device);
+    if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipSetDevice: %s", hipGetErrorString(e)); }
+    for (int i = 0; i < 2; ++i) {
+        plan_model(c->m[i], i == 0 ? p->target : p->drafter, p->max_batch, p->max_seq);
+        c->m[i].w = (char *)bufs->weights[i];
+        c->m[i].kv = (uint16_t *)bufs->kv[i];
+    }
+    plan_work(c->wk, *p, (char *)bufs->workspace);
+    c->max_tiles = std::max(2 * p->max_batch, 2);
+    // caches must hold finite values everywhere: masked keys are multiplied by zero weights
+    for (int i = 0; i < 2; ++i) {
+        e = hipMemsetAsync(bufs->kv[i], 0, need.kv[i], c->stream);
+        if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+        const deer_model_cfg &mc = c->m[i].c;
+        double th[64];
+        for (int k = 0; k < mc.head_dim / 2; ++k) th[k] = std::pow((double)mc.rope_base, -2.0 * k / mc.head_dim);
+        c->m[i].theta = c->wk.theta[i];
+        e = hipMemcpy(c->m[i].theta, th, sizeof(double) * (mc.head_dim / 2), hipMemcpyHostToDevice);
+        if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemcpy: %s", hipGetErrorString(e)); }
+    }
+    e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e)); }
+    *out = c;
+    return DEER_OK;
+}
+
+int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int expert, const void *src, int src_dtype,
+                     int64_t rows, int64_t cols) {
+    if (!c) return DEER_EINVAL;
+    if (!src || model < 0 || model > 1 || (src_dtype != DEER_F32 && src_dtype != DEER_BF16))
+        return fail(c, DEER_EINVAL, "bad model/dtype/pointer");
+    (void)expert;
+    ModelRT &m = c->m[model];
+    const deer_model_cfg &mc = m.c;
+    const int d = mc.d_model, hd = mc.head_dim;
+    int64_t er = 0, ec = 0;
+    char *dst = nullptr;
+    int mode = 0, col_off = 0, K = 0;
+    const bool per_layer = tensor_id >= DEER_T_WQ && tensor_id <= DEER_T_WD;
+    if (per_layer && (layer < 0 || layer >= mc.n_layers)) return fail(c, DEER_EINVAL, "layer out of range");
+    char *lw = m.w + m.off_layers + (size_t)(per_layer ? layer : 0) * m.layer_bytes;
+    switch (tensor_id) {
+        case DEER_T_EMBED: er = mc.vocab; ec = d; dst = m.w + m.off_embed; break;
+        case DEER_T_LM_HEAD: er = d; ec = mc.vocab; dst = m.w + m.off_lm; K = d; break;
+        case DEER_T_WQ: er = d; ec = mc.n_q_heads * hd; dst = lw + m.lo_qkv; K = d; break;
+        case DEER_T_WK: er = d; ec = mc.n_kv_heads * hd; dst = lw + m.lo_qkv; K = d; col_off = mc.n_q_heads * hd; break;
+        case DEER_T_WV: er = d; ec = mc.n_kv_heads * hd; dst = lw + m.lo_qkv; K = d; col_off = (mc.n_q_heads + mc.n_kv_heads) * hd; break;
+        case DEER_T_WO: er = m.kattn; ec = d; dst = lw + m.lo_o; K = m.kattn; break;
+        case DEER_T_WG: er = d; ec = m.F; dst = lw + m.lo_gu; K = d; mode = 1; break;
+        case DEER_T_WU: er = d; ec = m.F; dst = lw + m.lo_gu; K = d; mode = 2; break;
+        case DEER_T_WD: er = m.F; ec = d; dst = lw + m.lo_d; K = m.F; break;
+        default: return fail(c, DEER_EINVAL, "unknown tensor id %d", tensor_id);
+    }
+    if (rows != er || cols != ec) return fail(c, DEER_EINVAL, "tensor %d: expected %lld x %lld, got %lld x %lld", tensor_id,
+                                              (long long)er, (long long)ec, (long long)rows, (long long)cols);
+    if (tensor_id == DEER_T_EMBED) {
+        size_t n = (size_t)rows * cols;
+        dim3 grid((unsigned)((n + 255) / 256));
+        if (src_dtype == DEER_F32) hipLaunchKernelGGL(k_convert_rows<float>, grid, dim3(256), 0, c->stream, (const float *)src, (uint16_t *)dst, n);
+        else hipLaunchKernelGGL(k_convert_rows<uint16_t>, grid, dim3(256), 0, c->stream, (const uint16_t *)src, (uint16_t *)dst, n);
+    } else {
+        size_t n = (size_t)(K / 8) * cols;
+        dim3 grid((unsigned)((n + 255) / 256));
+        if (src_dtype == DEER_F32) hipLaunchKernelGGL(k_repack<float>, grid, dim3(256), 0, c->stream, (const float *)src, (uint4 *)dst, K, (int)cols, K / 16, mode, col_off);
+        else hipLaunchKernelGGL(k_repack<uint16_t>, grid, dim3(256), 0, c->stream, (const uint16_t *)src, (uint4 *)dst, K, (int)cols, K / 16, mode, col_off);
+    }
+    LAUNCHCHK(c, "k_repack");
+    return DEER_OK;
+}
+
+int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *lens) {
+    if (!c) return DEER_EINVAL;
+    if (!ids || !lens || batch < 1 || batch > c->p.max_batch) return fail(c, DEER_EINVAL, "bad batch or null pointer");
+    for (int b = 0; b < batch; ++b) {
+        if (lens[b] < 1) return fail(c, DEER_EINVAL, "prompt %d is empty", b);
+        if (lens[b] + c->p.max_k > c->p.max_seq) return fail(c, DEER_ECAPACITY, "prompt %d: %d tokens + one block exceed max_seq %d", b, lens[b], c->p.max_seq);
+    }
+    Work &w = c->wk;
+    std::vector<int> pend(batch), lenv(lens, lens + batch);
+    size_t off = 0;
+    for (int b = 0; b < batch; ++b) {
+        const int n = lens[b];
+        for (int i = 0; i < n; ++i)
+            if (ids[off + i] < 0 || ids[off + i] >= c->p.target.vocab) return fail(c, DEER_EINVAL, "token id outside the vocabulary");
+        HIPCHK(c, hipMemcpyAsync(w.ids, ids + off, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+        for (int model = 0; model < 2; ++model) {
+            const int nrows = (model == DEER_TARGET) ? n - 1 : n;   // the last token stays pending for the target
+            for (int c0 = 0; c0 < nrows; c0 += 64) {
+                const int nr = std::min(64, nrows - c0);
+                const int ntiles = (nr + 31) / 32;
+                hipLaunchKernelGGL(k_rows_prefill, dim3(ntiles), dim3(32), 0, c->stream, w.rm, w.ids, b, c0, nr);
+                LAUNCHCHK(c, "k_rows_prefill");
+                LmPlan lm{false, 0, 1, 0, 0, 0.f, 0};
+                int rc = run_pass(c, model, ntiles, c0 + nr, lm);
+                if (rc) return rc;
+            }
+        }
+        HIPCHK(c, hipStreamSynchronize(c->stream));   // w.ids is reused by the next sequence
+        pend[b] = ids[off + n - 1];
+        off += n;
+    }
+    return upload_state(c, batch, lenv.data(), lenv.data(), pend.data());
+}
+
+int deer_set_prefilled(deer_ctx *c, int32_t batch, const int32_t *lens, const int32_t *last) {
+    if (!c) return DEER_EINVAL;
+    if (!lens || !last || batch < 1 || batch > c->p.max_batch) return fail(c, DEER_EINVAL, "bad batch or null pointer");
+    for (int b = 0; b < batch; ++b) {
+        if (lens[b] < 1) return fail(c, DEER_EINVAL, "sequence %d is empty", b);
+        if (lens[b] + c->p.max_k > c->p.max_seq) return fail(c, DEER_ECAPACITY, "sequence %d exceeds max_seq", b);
+        if (last[b] < 0 || last[b] >= c->p.target.vocab) return fail(c, DEER_EINVAL, "token id outside the vocabulary");
+    }
+    return upload_state(c, batch, lens, lens, last);
+}
+
+int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *draft_dev) {
+    if (!c) return DEER_EINVAL;
+    if (!draft_dev || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
+    if (c->state != ST_PREFILLED) return fail(c, DEER_ESTATE, "draft_block needs a prefilled or committed state");
+    const int B = c->batch;
+    int maxlim = 0, any_ing = 0;
+    for (int b = 0; b < B; ++b) {
+        if (c->h_len[b] + k > c->p.max_seq) return fail(c, DEER_ECAPACITY, "sequence %d: length %d + k exceeds max_seq", b, c->h_len[b]);
+        maxlim = std::max(maxlim, c->h_len[b] + k);
+        any_ing |= c->h_ing_n[b] > 0;
+    }
+    Work &w = c->wk;
+    const int tps = any_ing ? 2 : 1;
+    hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps);
+    LAUNCHCHK(c, "k_rows_draft");
+    LmPlan lm{true, 0, tps, B, k, T, seed};
+    int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_draft_finish, dim3(B), dim3(32), 0, c->stream, w.st, w.res[DEER_DRAFTER], draft_dev, k);
+    LAUNCHCHK(c, "k_draft_finish");
+    std::fill(c->h_ing_n.begin(), c->h_ing_n.end(), 0);
+    c->cur_k = k;
+    c->cur_T = T;
+    c->state = ST_DRAFTED;
+    return DEER_OK;
+}
+
+int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev) {
+    if (!c) return DEER_EINVAL;
+    if (!draft_dev || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
+    if (c->state != ST_DRAFTED) return fail(c, DEER_ESTATE, "verify_block must follow draft_block");
+    if (k != c->cur_k || T != c->cur_T) return fail(c, DEER_EINVAL, "k and T must match the draft_block call");
+    const int B = c->batch;
+    int maxlim = 0;
+    for (int b = 0; b < B; ++b) maxlim = std::max(maxlim, c->h_len[b] - 1 + k);
+    Work &w = c->wk;
+    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k);
+    LAUNCHCHK(c, "k_rows_verify");
+    LmPlan lm{true, 0, 1, B, k, T, 0};
+    int rc = run_pass(c, DEER_TARGET, B, maxlim, lm);
+    if (rc) return rc;
+    c->wk_draft = draft_dev;
+    c->state = ST_VERIFIED;
+    return DEER_OK;
+}
+
+int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom) {
+    if (!c) return DEER_EINVAL;
+    if (!acc || !committed || !ncom || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
+    if (c->state != ST_VERIFIED) return fail(c, DEER_ESTATE, "accept_and_commit must follow verify_block");
+    if (k != c->cur_k || T != c->cur_T) return fail(c, DEER_EINVAL, "k and T must match the draft_block call");
+    const int B = c->batch;
+    Work &w = c->wk;
+    const int V = c->p.target.vocab;
+    if (T == 0.f)
+        hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET], k, c->p.eos_token_id);
+    else
+        hipLaunchKernelGGL(k_accept_sample, dim3(B), dim3(1024), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET],
+                           w.res[DEER_DRAFTER], w.logits[DEER_TARGET], w.logits[DEER_DRAFTER], k, V, T, seed, c->p.eos_token_id);
+    LAUNCHCHK(c, "k_accept");
+    HIPCHK(c, hipMemcpyAsync(acc, w.ao.accept_len, B * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(ncom, w.ao.n_committed, B * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(committed, w.ao.committed, (size_t)B * k * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    for (int b = 0; b < B; ++b) {
+        c->h_len[b] += ncom[b];
+        c->h_ing_n[b] = ncom[b];
+        if (c->p.eos_token_id >= 0 && ncom[b] > 0 && committed[(size_t)b * k + ncom[b] - 1] == c->p.eos_token_id) c->h_finished[b] = 1;
+    }
+    c->state = ST_PREFILLED;
+    return DEER_OK;
+}
+
+int deer_destroy(deer_ctx *c) {
+    if (!c) return DEER_EINVAL;
+    hipStreamSynchronize(c->stream);
+    delete c;
+    return DEER_OK;
+}
+
+const char *deer_last_error(const deer_ctx *c) { return c ? c->err.c_str() : g_init_error.c_str(); }
+
+int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
+    if (!c) return DEER_EINVAL;
+    if (!out || model < 0 || model > 1) return fail(c, DEER_EINVAL, "bad model or null pointer");
+    if (c->cur_k < 1) return fail(c, DEER_ESTATE, "no pass has run yet");
+    if (!c->p.keep_logits && c->cur_T == 0.f) return fail(c, DEER_ESTATE, "logits were not kept (keep_logits = 0 and T = 0)");
+    const size_t n = (size_t)c->batch * c->cur_k * c->p.target.vocab;
+    if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
+    HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return DEER_OK;
+}
+
+int deer_get_lengths(const deer_ctx *c, int32_t *len) {
+    if (!c || !len) return DEER_EINVAL;
+    for (int b = 0; b < c->batch; ++b) len[b] = c->h_len[b];
+    return DEER_OK;
+}
+
+int deer_get_kv_layout(const deer_ctx *c, int model, deer_kv_layout *out) {
+    if (!c || !out || model < 0 || model > 1) return DEER_EINVAL;
+    const ModelRT &m = c->m[model];
+    out->k_base = m.kv_k_base; out->v_base = m.kv_v_base;
+    out->layer_stride = m.kv_layer_stride; out->seq_stride = m.kv_seq_stride; out->head_stride = m.kv_head_stride;
+    out->max_seq = c->p.max_seq; out->head_dim = m.c.head_dim;
+    return DEER_OK;
+}
+
+}  // extern "C"

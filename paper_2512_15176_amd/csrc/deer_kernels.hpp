@@ -1,0 +1,908 @@
+// Device code of libdeer: every step of the draft-verify iteration as HIP kernels for gfx950.
+//
+// Data layouts (all chosen for 64-lane wavefronts and the 32x32x16 bf16 MFMA):
+//   * "fragment" layout of a [32 rows x K] operand tile: 16-byte vectors ordered [K/16][64 lanes],
+//     lane l holding row (l % 32), k-indices 16*ks + 8*(l / 32) .. +8.  One wave-wide 16-byte load
+//     is one MFMA operand.  Weights use it per 32-column block ([N/32][K/16][64][8], so a block's
+//     whole K extent is one contiguous stream); activations use it per 32-row tile, as two planes
+//     (hi, lo) with x ~= hi + lo in bf16, so that products against bf16 weights are exact to
+//     ~2^-17 and accumulate in fp32.
+//   * residual stream h: fp32 row-major [rows][d_model].
+//   * K cache [layer][seq][kv_head][slot][head_dim] bf16;  V cache transposed
+//     [layer][seq][kv_head][head_dim][slot] bf16, so that both attention contractions read
+//     contraction-contiguous 16-byte vectors.
+//   * a pass works on row tiles of 32; every tile belongs to one sequence; unused rows have
+//     limit 0 and slot -1.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace deer {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int TILE_M = 32;       // rows per tile
+constexpr int CG = 128;          // columns per column group (4 MFMA column blocks)
+constexpr int RED_STRIDE = 136;  // padded LDS row stride (floats) of a 32x128 tile
+
+// ------------------------------------------------------------------------------------------
+// small helpers
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even; finite inputs
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+
+// x ~= hi + lo, both bf16
+__device__ __forceinline__ void split_bf(float x, uint32_t &hi, uint32_t &lo) {
+    hi = f2bf(x);
+    lo = f2bf(x - bf2f(hi));
+}
+
+__device__ __forceinline__ void pack8_split(const float *v, uint4 &hi, uint4 &lo) {
+    uint32_t h[8], l[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split_bf(v[e], h[e], l[e]);
+    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+}
+
+__device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
+__device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+
+// Index (in 16-byte vectors) of (row, k-octet) inside a fragment-layout tile with KS k-steps.
+__device__ __forceinline__ size_t frag_vec(int row, int oct) { return (size_t)(oct >> 1) * 64 + row + 32 * (oct & 1); }
+
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {  // splitmix64 finaliser
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+constexpr uint64_t GOLDEN = 0x9E3779B97F4A7C15ULL;
+enum { TAG_DRAFT = 1, TAG_ACCEPT = 2, TAG_RESID = 3 };
+__device__ __forceinline__ uint64_t row_key(uint64_t seed, uint64_t tag, uint64_t seq, uint64_t pos) {
+    return mix64(mix64(seed + GOLDEN * tag) ^ ((seq << 40) + pos));
+}
+__device__ __forceinline__ float uniform01(uint64_t key, uint64_t idx) {  // (r + 0.5) / 2^23, r < 2^23
+    uint64_t bits = mix64(key + GOLDEN * (idx + 1));
+    return ((float)(uint32_t)(bits >> 41) + 0.5f) * (1.0f / 8388608.0f);
+}
+__device__ __forceinline__ float gumbel(uint64_t key, uint64_t idx) { return -logf(-logf(uniform01(key, idx))); }
+
+// (value, index) max with lowest index on ties
+__device__ __forceinline__ void argmax_merge(float &v, int &i, float v2, int i2) {
+    if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
+}
+
+// ------------------------------------------------------------------------------------------
+// weight repack: canonical [K][N_src] (fp32 or bf16) -> fragment layout, bf16
+//   dest column n_dst = col_map(n_src):  plain offset (QKV concatenation) or gate/up interleave
+//   (group of 128 columns = 64 gate channels followed by the same 64 up channels).
+// ------------------------------------------------------------------------------------------
+template <typename SrcT>
+__device__ __forceinline__ uint32_t load_as_bf16(const SrcT *p);
+template <>
+__device__ __forceinline__ uint32_t load_as_bf16<float>(const float *p) { return f2bf(*p); }
+template <>
+__device__ __forceinline__ uint32_t load_as_bf16<uint16_t>(const uint16_t *p) { return *p; }
+
+// mode 0: n_dst = n_src + col_off.  mode 1 (gate) / 2 (up): n_dst = (n_src/64)*128 + (mode-1)*64 + n_src%64
+template <typename SrcT>
+__global__ void k_repack(const SrcT *__restrict__ src, uint4 *__restrict__ dst, int K, int N_src, int KS_dst,
+                         int mode, int col_off) {
+    // one thread per (src column n, k-octet): reads 8 strided values, writes one 16-byte vector
+    size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int n = (int)(gid % N_src);
+    size_t oct = gid / N_src;
+    if (oct >= (size_t)K / 8) return;
+    int n_dst = (mode == 0) ? n + col_off : (n / 64) * 128 + (mode - 1) * 64 + (n % 64);
+    uint32_t v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = load_as_bf16<SrcT>(src + ((size_t)oct * 8 + e) * N_src + n);
+    int nb = n_dst >> 5;
+    size_t vec = ((size_t)nb * KS_dst) * 64 + frag_vec(n_dst & 31, (int)oct);
+    dst[vec] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+}
+
+template <typename SrcT>
+__global__ void k_convert_rows(const SrcT *__restrict__ src, uint16_t *__restrict__ dst, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = (uint16_t)load_as_bf16<SrcT>(src + i);
+}
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// per-sequence state and row metadata
+// ------------------------------------------------------------------------------------------
+struct SeqState {       // device arrays, one entry per sequence
+    int *len;           // j: committed tokens
+    int *dr_len;        // tokens in the drafter cache
+    int *pending;       // x_j
+    int *ing_n;         // committed tokens the drafter has not cached yet
+    int *ing_tok;       // [B][32]
+    int *finished;      // EOS seen
+};
+
+struct RowMeta {        // device arrays over the rows of a pass
+    int *tok, *pos, *limit, *slot;   // [rows]; slot < 0: do not write K,V
+    int *tile_seq;                   // [tiles]
+};
+
+// verify rows of sequence b: tile b; row i < k: [x_j, y^_1 .. y^_{k-1}] at positions j-1+i
+__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k) {
+    int b = blockIdx.x, i = threadIdx.x;
+    int row = b * 32 + i;
+    int j = st.len[b];
+    if (i == 0) rm.tile_seq[b] = b;
+    if (i < k) {
+        int p = j - 1 + i;
+        rm.tok[row] = (i == 0) ? st.pending[b] : draft[b * k + i - 1];
+        rm.pos[row] = p;
+        rm.slot[row] = p;
+        rm.limit[row] = p + 1;
+    } else {
+        rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
+    }
+}
+
+// draft rows of sequence b: tile 2b = k MASK rows at positions j..j+k-1 (see cache + ingested rows +
+// every MASK row; their K,V land in slots past the cached length and are never kept); tile 2b+1 =
+// the m not-yet-cached committed tokens, causal.  With tiles_per_seq == 1 only the MASK tile exists.
+__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq) {
+    int b = blockIdx.x, i = threadIdx.x;   // 64 threads
+    int t = i >> 5, r = i & 31;
+    if (t >= tiles_per_seq) return;
+    int tile = b * tiles_per_seq + t;
+    int row = tile * 32 + r;
+    int j = st.len[b], dl = st.dr_len[b], m = st.ing_n[b];
+    if (r == 0) rm.tile_seq[tile] = b;
+    if (t == 0 && r < k) {
+        rm.tok[row] = mask_id; rm.pos[row] = j + r; rm.slot[row] = j + r; rm.limit[row] = j + k;
+    } else if (t == 1 && r < m) {
+        rm.tok[row] = st.ing_tok[b * 32 + r]; rm.pos[row] = dl + r; rm.slot[row] = dl + r; rm.limit[row] = dl + r + 1;
+    } else {
+        rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
+    }
+}
+
+// prefill chunk: rows c0..c0+n-1 of sequence b's prompt, causal; tiles 0..ntiles-1
+__global__ void k_rows_prefill(RowMeta rm, const int *__restrict__ ids, int b, int c0, int n) {
+    int row = blockIdx.x * 32 + threadIdx.x;
+    if (threadIdx.x == 0) rm.tile_seq[blockIdx.x] = b;
+    if (row < n) {
+        rm.tok[row] = ids[c0 + row]; rm.pos[row] = c0 + row; rm.slot[row] = c0 + row; rm.limit[row] = c0 + row + 1;
+    } else {
+        rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
+    }
+}
+
+// cos/sin of pos * theta_i, evaluated in double, stored fp32: cs[row][i] = (cos, sin)
+__global__ void k_rope_table(const int *__restrict__ pos, const double *__restrict__ theta, float2 *__restrict__ cs,
+                             int half, int rows) {
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= rows * half) return;
+    int row = idx / half, i = idx % half;
+    double s, c;
+    sincos((double)pos[row] * theta[i], &s, &c);
+    cs[idx] = make_float2((float)c, (float)s);
+}
+
+// ------------------------------------------------------------------------------------------
+// write a 32 x 128 fp32 tile (LDS, stride RED_STRIDE) into fragment layout (hi/lo) at k-columns
+// k0 .. k0+127 of a tile with KS k-steps; 512 (row, octet) items over 256 threads
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void tile_to_frag(const float *tile, uint4 *xhi, uint4 *xlo, size_t tile_base_vec, int k0) {
+    for (int item = threadIdx.x; item < 512; item += 256) {
+        int row = item & 31, oct = item >> 5;
+        uint4 hi, lo;
+        pack8_split(tile + row * RED_STRIDE + oct * 8, hi, lo);
+        size_t v = tile_base_vec + frag_vec(row, (k0 >> 3) + oct);
+        xhi[v] = hi;
+        xlo[v] = lo;
+    }
+}
+
+// embedding gather: h[row] = E[tok[row]] (bf16 table), plus fragment planes and sum of squares
+__global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ tok,
+                                               float *__restrict__ h, uint4 *__restrict__ xhi, uint4 *__restrict__ xlo,
+                                               float *__restrict__ ssq, int d, int ncg) {
+    __shared__ float tile[32 * RED_STRIDE];
+    int cg = blockIdx.x, t = blockIdx.y;
+    for (int e = threadIdx.x; e < 32 * CG; e += 256) {
+        int row = e >> 7, col = e & 127;
+        int grow = t * 32 + row;
+        float v = bf2f(E[(size_t)tok[grow] * d + cg * CG + col]);
+        tile[row * RED_STRIDE + col] = v;
+        h[(size_t)grow * d + cg * CG + col] = v;
+    }
+    __syncthreads();
+    tile_to_frag(tile, xhi, xlo, (size_t)t * (d / 16) * 64, cg * CG);
+    if (threadIdx.x < 32) {
+        float s = 0.f;
+        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
+        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// weight-streaming GEMM for short row counts:  part[s][ct*32 + i][n] = sum over k-slice of x[i][k] W[k][n]
+//   grid: x = column group (128 columns), y = split s, z = group of MT row tiles
+//   block: 4 waves; wave w takes k-slice (s*4 + w) of 4*S; each wave owns all 4 column blocks, so
+//   one activation fragment feeds 4 weight fragments; the 4 waves are reduced through LDS.
+//   Tiles of the launch: tile(ct) = mt0 + ct * mt_stride, ct = z*MT + mt.
+// ------------------------------------------------------------------------------------------
+template <int MT>
+__global__ __launch_bounds__(256) void k_gemm(const uint4 *__restrict__ W, const uint4 *__restrict__ Xhi,
+                                              const uint4 *__restrict__ Xlo, float *__restrict__ part, int N, int KS,
+                                              int S, int mt0, int mt_stride, int rows_total) {
+    __shared__ float red[2 * 32 * RED_STRIDE];
+    const int cg = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int slices = S * 4, sl = s * 4 + w;
+    const int per = (KS + slices - 1) / slices;
+    const int ks0 = sl * per;
+    const int ks1 = min(KS, ks0 + per);
+
+    f32x16 acc[MT][4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mt][nb][r] = 0.f;
+
+    const uint4 *wp = W + ((size_t)(cg * 4) * KS) * 64 + lane;
+    const size_t wstride = (size_t)KS * 64;   // between column blocks
+    const uint4 *xh[MT], *xl[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        size_t tile = (size_t)(mt0 + (z * MT + mt) * mt_stride);
+        xh[mt] = Xhi + tile * KS * 64 + lane;
+        xl[mt] = Xlo + tile * KS * 64 + lane;
+    }
+
+    constexpr int D = 4;  // k-steps in flight
+    uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd) {
+        int ks = ks0 + dd;
+        if (ks < ks1) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)ks * 64]; xlb[dd][mt] = xl[mt][(size_t)ks * 64]; }
+        }
+    }
+    for (int kb = ks0; kb < ks1; kb += D) {
+#pragma unroll
+        for (int dd = 0; dd < D; ++dd) {
+            int ks = kb + dd;
+            if (ks < ks1) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        acc[mt][nb] = mfma32(xhb[dd][mt], wb[dd][nb], acc[mt][nb]);
+                        acc[mt][nb] = mfma32(xlb[dd][mt], wb[dd][nb], acc[mt][nb]);
+                    }
+                int kn = ks + D;
+                if (kn < ks1) {
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)kn * 64]; xlb[dd][mt] = xl[mt][(size_t)kn * 64]; }
+                }
+            }
+        }
+    }
+
+    // reduce the 4 waves through LDS in a fixed order, (w0 + w2) + (w1 + w3), one row tile at a time
+    const int half = lane >> 5, cl = lane & 31;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        if (mt > 0) __syncthreads();
+        if (w >= 2) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    red[((w - 2) * 32 + mfma_row(r, half)) * RED_STRIDE + nb * 32 + cl] = acc[mt][nb][r];
+        }
+        __syncthreads();
+        if (w < 2) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    red[(w * 32 + mfma_row(r, half)) * RED_STRIDE + nb * 32 + cl] += acc[mt][nb][r];
+        }
+        __syncthreads();
+        const int col = threadIdx.x & 127;
+        const int ct = z * MT + mt;
+        float *out = part + ((size_t)s * rows_total + (size_t)ct * 32) * N + (size_t)cg * CG + col;
+        for (int row = threadIdx.x >> 7; row < 32; row += 2)
+            out[(size_t)row * N] = red[row * RED_STRIDE + col] + red[(32 + row) * RED_STRIDE + col];
+    }
+}
+
+// sum the S split partials of a 32x128 tile into LDS (stride RED_STRIDE), fixed order s = 0..S-1
+__device__ __forceinline__ void sum_partials(const float *__restrict__ part, float *tile, int S, int rows_total, int N,
+                                             int ct, int cg) {
+    const int col = threadIdx.x & 127;
+    for (int row = threadIdx.x >> 7; row < 32; row += 2) {
+        const float *p = part + ((size_t)ct * 32 + row) * N + (size_t)cg * CG + col;
+        float v = 0.f;
+        for (int s = 0; s < S; ++s) v += p[(size_t)s * rows_total * N];
+        tile[row * RED_STRIDE + col] = v;
+    }
+}
+
+// rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
+__device__ __forceinline__ void tile_rstd(const float *__restrict__ ssq, float *rstd, int grow0, int ncg, int d, float eps) {
+    if (threadIdx.x < 32) {
+        const float *p = ssq + (size_t)(grow0 + threadIdx.x) * ncg;
+        float s = 0.f;
+        for (int g = 0; g < ncg; ++g) s += p[g];
+        rstd[threadIdx.x] = rsqrtf(s / (float)d + eps);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// epilogue of the fused QKV projection: RMSNorm scale, RoPE, Q -> fragment planes per head,
+// K -> cache, V -> transposed cache.  grid: x = column group of (Hq + 2 Hkv) * hd, y = tile
+// ------------------------------------------------------------------------------------------
+struct KvView {
+    uint16_t *k, *vt;                                  // layer base already applied
+    size_t seq_stride, head_stride;                    // elements
+    int max_seq;
+};
+
+__global__ __launch_bounds__(256) void k_epi_qkv(const float *__restrict__ part, int S, int rows_total, int N,
+                                                 const float *__restrict__ ssq, int ncg_in, int d, float eps,
+                                                 const float2 *__restrict__ cs, RowMeta rm, uint4 *__restrict__ qhi,
+                                                 uint4 *__restrict__ qlo, KvView kv, int Hq, int Hkv, int hd) {
+    __shared__ float tile[32 * RED_STRIDE];
+    __shared__ float rstd[32];
+    const int cg = blockIdx.x, t = blockIdx.y;   // all tiles of the pass take part: ct == t
+    sum_partials(part, tile, S, rows_total, N, t, cg);
+    tile_rstd(ssq, rstd, t * 32, ncg_in, d, eps);
+    __syncthreads();
+    const int half_hd = hd >> 1;
+    const int b = rm.tile_seq[t];
+    for (int item = threadIdx.x; item < 512; item += 256) {
+        const int row = item & 31, oct = item >> 5;
+        const int grow = t * 32 + row;
+        const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
+        const int kind = col0 < Hq * hd ? 0 : (col0 < (Hq + Hkv) * hd ? 1 : 2);
+        const int hc = col0 - (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd));
+        const int head = hc / hd, i0 = hc % hd;
+        const float sc = rstd[row];
+        float v[8];
+        if (kind < 2) {
+            const int poff = (i0 < half_hd) ? half_hd : -half_hd;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float x = tile[row * RED_STRIDE + oct * 8 + e] * sc;
+                float xp = tile[row * RED_STRIDE + oct * 8 + e + poff] * sc;
+                float2 c = cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
+                v[e] = (i0 < half_hd) ? x * c.x - xp * c.y : x * c.x + xp * c.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = tile[row * RED_STRIDE + oct * 8 + e] * sc;
+        }
+        if (kind == 0) {
+            uint4 hi, lo;
+            pack8_split(v, hi, lo);
+            size_t vec = ((size_t)(t * Hq + head) * (hd / 16)) * 64 + frag_vec(row, i0 >> 3);
+            qhi[vec] = hi;
+            qlo[vec] = lo;
+        } else {
+            const int slot = rm.slot[grow];
+            if (slot >= 0) {
+                uint32_t u[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) u[e] = f2bf(v[e]);
+                size_t base = (size_t)b * kv.seq_stride + (size_t)head * kv.head_stride;
+                if (kind == 1) {
+                    *(uint4 *)(kv.k + base + (size_t)slot * hd + i0) =
+                        make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kv.vt[base + (size_t)(i0 + e) * kv.max_seq + slot] = (uint16_t)u[e];
+                }
+            }
+        }
+    }
+}
+
+// epilogue of O-proj / down-proj: h += y; new fragment planes of h; per-group sum of squares
+__global__ __launch_bounds__(256) void k_epi_residual(const float *__restrict__ part, int S, int rows_total, int N,
+                                                      float *__restrict__ h, uint4 *__restrict__ xhi,
+                                                      uint4 *__restrict__ xlo, float *__restrict__ ssq) {
+    __shared__ float tile[32 * RED_STRIDE];
+    const int cg = blockIdx.x, t = blockIdx.y, ncg = gridDim.x;
+    sum_partials(part, tile, S, rows_total, N, t, cg);
+    __syncthreads();
+    for (int e = threadIdx.x; e < 32 * CG; e += 256) {
+        int row = e >> 7, col = e & 127;
+        size_t gi = (size_t)(t * 32 + row) * N + cg * CG + col;
+        float v = h[gi] + tile[row * RED_STRIDE + col];
+        h[gi] = v;
+        tile[row * RED_STRIDE + col] = v;
+    }
+    __syncthreads();
+    tile_to_frag(tile, xhi, xlo, (size_t)t * (N / 16) * 64, cg * CG);
+    if (threadIdx.x < 32) {
+        float s = 0.f;
+        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
+        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
+    }
+}
+
+// epilogue of the gate/up projection: group = 64 gate + 64 up channels -> SiLU(g) * u, fragment planes over F
+__global__ __launch_bounds__(256) void k_epi_swiglu(const float *__restrict__ part, int S, int rows_total, int N,
+                                                    const float *__restrict__ ssq, int ncg_in, int d, float eps,
+                                                    uint4 *__restrict__ ahi, uint4 *__restrict__ alo, int F) {
+    __shared__ float tile[32 * RED_STRIDE];
+    __shared__ float rstd[32];
+    const int cg = blockIdx.x, t = blockIdx.y;
+    sum_partials(part, tile, S, rows_total, N, t, cg);
+    tile_rstd(ssq, rstd, t * 32, ncg_in, d, eps);
+    __syncthreads();
+    const int row = threadIdx.x & 31, oct = threadIdx.x >> 5;   // 8 octets of 8 channels
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float g = tile[row * RED_STRIDE + oct * 8 + e] * rstd[row];
+        float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * rstd[row];
+        v[e] = g / (1.f + expf(-g)) * u;
+    }
+    uint4 hi, lo;
+    pack8_split(v, hi, lo);
+    size_t vec = (size_t)t * (F / 16) * 64 + frag_vec(row, cg * 8 + oct);
+    ahi[vec] = hi;
+    alo[vec] = lo;
+}
+
+// ------------------------------------------------------------------------------------------
+// LM head epilogue and row statistics
+// ------------------------------------------------------------------------------------------
+struct RowStat {   // per (row, column group) partial over 128 vocabulary entries
+    float m; int idx;        // max logit, its index (lowest on ties)
+    float sumexp;            // sum exp(z/T - m/T)  (T > 0)
+    float gm; int gidx;      // max of z/T + Gumbel, its index (T > 0)
+};
+
+// grid: x = vocab group, y = compact LM tile ct (pass tile = mt0 + ct*mt_stride; LM rows are the
+// first k rows of that tile; lm_row = ct*k + i)
+__global__ __launch_bounds__(256) void k_epi_lmhead(float *__restrict__ part, int rows_total, int V,
+                                                    const float *__restrict__ ssq, int ncg_in, int d, float eps, int mt0,
+                                                    int mt_stride, int k, float *__restrict__ logits, float T,
+                                                    uint64_t seed, const int *__restrict__ tile_seq,
+                                                    const int *__restrict__ row_pos, RowStat *__restrict__ stat,
+                                                    int ncg_v) {
+    __shared__ float rstd[32];
+    const int cg = blockIdx.x, ct = blockIdx.y;
+    const int tile = mt0 + ct * mt_stride;
+    tile_rstd(ssq, rstd, tile * 32, ncg_in, d, eps);
+    __syncthreads();
+    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;   // 8 threads per row, 16 columns each
+    const bool live = row < k;
+    float m = -INFINITY, gm = -INFINITY, se = 0.f;
+    int idx = 0x7fffffff, gidx = 0x7fffffff;
+    float z[16];
+    const float invT = T > 0.f ? 1.f / T : 1.f;
+    uint64_t key = 0;
+    if (live) {
+        const float *p = part + ((size_t)ct * 32 + row) * V + (size_t)cg * CG + sub * 16;
+        const float sc = rstd[row];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = p[e] * sc;
+        if (logits) {
+            float *q = logits + ((size_t)ct * k + row) * V + (size_t)cg * CG + sub * 16;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) q[e] = z[e];
+        }
+        if (T > 0.f) key = row_key(seed, TAG_DRAFT, (uint64_t)tile_seq[tile], (uint64_t)row_pos[tile * 32 + row]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            int v = cg * CG + sub * 16 + e;
+            argmax_merge(m, idx, z[e], v);
+            if (T > 0.f) argmax_merge(gm, gidx, z[e] * invT + gumbel(key, (uint64_t)v), v);
+        }
+    }
+    // reduce over the 8 threads of a row (they are adjacent lanes)
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+        float m2 = __shfl_xor(m, off); int i2 = __shfl_xor(idx, off);
+        argmax_merge(m, idx, m2, i2);
+        float g2 = __shfl_xor(gm, off); int gi2 = __shfl_xor(gidx, off);
+        argmax_merge(gm, gidx, g2, gi2);
+    }
+    if (live && T > 0.f) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) se += expf((z[e] - m) * invT);
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
+    if (live && sub == 0) {
+        RowStat s;
+        s.m = m; s.idx = idx; s.sumexp = se; s.gm = gm; s.gidx = gidx;
+        stat[((size_t)ct * k + row) * ncg_v + cg] = s;
+    }
+}
+
+struct RowResult {   // per LM row
+    int argmax;      // lowest index of the max logit
+    int sample;      // Gumbel-max sample of softmax(z/T) (T > 0), else = argmax
+    float lse;       // log sum exp(z/T) (T > 0), else 0
+    float zmax;
+};
+
+// one block per LM row: merge the per-group partials
+__global__ __launch_bounds__(256) void k_rowstat_final(const RowStat *__restrict__ stat, int ncg_v, float T,
+                                                       RowResult *__restrict__ res) {
+    __shared__ float sm[256]; __shared__ int si[256]; __shared__ float sg[256]; __shared__ int sgi[256];
+    __shared__ float ss[256];
+    const int row = blockIdx.x;
+    const RowStat *p = stat + (size_t)row * ncg_v;
+    float m = -INFINITY, gm = -INFINITY; int idx = 0x7fffffff, gidx = 0x7fffffff;
+    for (int g = threadIdx.x; g < ncg_v; g += 256) {
+        argmax_merge(m, idx, p[g].m, p[g].idx);
+        argmax_merge(gm, gidx, p[g].gm, p[g].gidx);
+    }
+    sm[threadIdx.x] = m; si[threadIdx.x] = idx; sg[threadIdx.x] = gm; sgi[threadIdx.x] = gidx;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            argmax_merge(sm[threadIdx.x], si[threadIdx.x], sm[threadIdx.x + off], si[threadIdx.x + off]);
+            argmax_merge(sg[threadIdx.x], sgi[threadIdx.x], sg[threadIdx.x + off], sgi[threadIdx.x + off]);
+        }
+        __syncthreads();
+    }
+    const float M = sm[0];
+    float se = 0.f;
+    if (T > 0.f) {
+        const float invT = 1.f / T;
+        for (int g = threadIdx.x; g < ncg_v; g += 256) se += p[g].sumexp * expf((p[g].m - M) * invT);
+    }
+    ss[threadIdx.x] = se;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (threadIdx.x < off) ss[threadIdx.x] += ss[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        RowResult r;
+        r.argmax = si[0];
+        r.zmax = M;
+        if (T > 0.f) { r.sample = sgi[0]; r.lse = M / T + logf(ss[0]); }
+        else { r.sample = si[0]; r.lse = 0.f; }
+        res[row] = r;
+    }
+}
+
+// draft pass tail: draft tokens out, drafter cache length advances over the ingested rows
+__global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, int *__restrict__ draft, int k) {
+    int b = blockIdx.x, i = threadIdx.x;
+    if (i < k) draft[b * k + i] = res[b * k + i].sample;
+    if (i == 0) { st.dr_len[b] += st.ing_n[b]; st.ing_n[b] = 0; }
+}
+
+// ------------------------------------------------------------------------------------------
+// block attention: 32 query rows of ONE query head per block, a contiguous range of key tiles split
+// over the 4 waves, online softmax in fp32; S^T = K Q^T and O^T = V^T P^T so that every MFMA operand
+// is a contraction-contiguous 16-byte vector and the softmax row of a lane is its own column.
+//   grid: x = kvh + Hkv * (g + G * split), y = pass tile.
+//   Key order inside a 32-key tile is permuted (operand row rho holds key 16*((rho/4)%2) +
+//   4*(rho/8) + rho%4) so that a lane's 16 results are 16 consecutive keys.
+// ------------------------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
+                                              const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
+                                              size_t seq_stride, size_t head_stride, int max_seq,
+                                              const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
+                                              float *__restrict__ Opart, float *__restrict__ MLpart, int Hq, int Hkv,
+                                              int NS, float scale_log2e) {
+    constexpr int KSQ = HD / 16;   // k-steps of the score contraction
+    constexpr int HT = HD / 32;    // 32-row tiles of O^T
+    __shared__ float sm_o[2 * HD * 33];
+    __shared__ float sm_m[2 * 32], sm_l[2 * 32];
+    const int G = Hq / Hkv;
+    const int kvh = blockIdx.x % Hkv;
+    const int g = (blockIdx.x / Hkv) % G;
+    const int split = blockIdx.x / (Hkv * G);
+    const int t = blockIdx.y;
+    const int head = kvh * G + g;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, qrow = lane & 31;
+    const int b = tile_seq[t];
+    const int lim = row_limit[t * 32 + qrow];
+    int maxlim = lim;
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, off));
+    const int nkt = (maxlim + 31) >> 5;
+    const int per = (nkt + NS - 1) / NS;
+    const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
+
+    uint4 qh[KSQ], ql[KSQ];
+    {
+        const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
+    }
+    const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
+    const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
+    const int rho = qrow;                                              // operand row of the K fragment
+    const int keyperm = 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+
+    f32x16 oacc[HT];
+#pragma unroll
+    for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int kt = kt0 + w; kt < kt1; kt += 4) {
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) {
+            uint4 kf = *(const uint4 *)(kp + s * 16);
+            sacc = mfma32(kf, qh[s], sacc);
+            sacc = mfma32(kf, ql[s], sacc);
+        }
+        // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
+        const int key0 = kt * 32 + 16 * half;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            if (key0 + r >= lim) sacc[r] = -INFINITY;
+            mx = fmaxf(mx, sacc[r]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        float p[16];
+        float alpha = 1.f;
+        if (m_new == -INFINITY) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) p[r] = 0.f;
+        } else {
+            alpha = exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+            float ls = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { p[r] = exp2f((sacc[r] - m_new) * scale_log2e); ls += p[r]; }
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+        }
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+        uint4 ph[2], pl[2];
+        pack8_split(p, ph[0], pl[0]);
+        pack8_split(p + 8, ph[1], pl[1]);
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt) {
+            const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                uint4 vf = *(const uint4 *)(vp + 8 * s2);
+                oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
+                oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+            }
+        }
+    }
+    // merge the 4 waves in a fixed order: (w0 (+) w2), (w1 (+) w3), then the two results
+    float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (w >= 2) {
+        if (half == 0) { sm_m[(w - 2) * 32 + qrow] = m_run; sm_l[(w - 2) * 32 + qrow] = l_tot; }
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sm_o[((w - 2) * HD + tt * 32 + mfma_row(r, half)) * 33 + qrow] = oacc[tt][r];
+    }
+    __syncthreads();
+    if (w < 2) {
+        const float m_b = sm_m[w * 32 + qrow], l_b = sm_l[w * 32 + qrow];
+        const float M = fmaxf(m_run, m_b);
+        const float fa = (m_run == -INFINITY) ? 0.f : exp2f((m_run - M) * scale_log2e);
+        const float fb = (m_b == -INFINITY) ? 0.f : exp2f((m_b - M) * scale_log2e);
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int li = (w * HD + tt * 32 + mfma_row(r, half)) * 33 + qrow;
+                sm_o[li] = oacc[tt][r] * fa + sm_o[li] * fb;
+            }
+        if (half == 0) { sm_l[w * 32 + qrow] = l_tot * fa + l_b * fb; }
+        // both halves read m_b above before either writes: order the write after the reads
+        __builtin_amdgcn_wave_barrier();
+        if (half == 0) sm_m[w * 32 + qrow] = M;
+    }
+    __syncthreads();
+    const size_t pidx = (size_t)(t * Hq + head) * NS + split;
+    for (int e = threadIdx.x; e < 32 * HD; e += 256) {
+        const int row = e / HD, dim = e % HD;
+        const float m0 = sm_m[row], m1 = sm_m[32 + row];
+        const float M = fmaxf(m0, m1);
+        float o = 0.f;
+        if (m0 != -INFINITY) o += exp2f((m0 - M) * scale_log2e) * sm_o[dim * 33 + row];
+        if (m1 != -INFINITY) o += exp2f((m1 - M) * scale_log2e) * sm_o[(HD + dim) * 33 + row];
+        Opart[pidx * 32 * HD + e] = o;
+    }
+    if (threadIdx.x < 32) {
+        const int row = threadIdx.x;
+        const float m0 = sm_m[row], m1 = sm_m[32 + row];
+        const float M = fmaxf(m0, m1);
+        float L = 0.f;
+        if (m0 != -INFINITY) L += exp2f((m0 - M) * scale_log2e) * sm_l[row];
+        if (m1 != -INFINITY) L += exp2f((m1 - M) * scale_log2e) * sm_l[32 + row];
+        MLpart[pidx * 64 + row] = M;
+        MLpart[pidx * 64 + 32 + row] = L;
+    }
+}
+
+// merge the NS key-range partials of one (tile, head), normalise, write fragment planes over Hq*HD
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_combine(const float *__restrict__ Opart, const float *__restrict__ MLpart,
+                                                      int NS, int Hq, float scale_log2e, uint4 *__restrict__ xhi,
+                                                      uint4 *__restrict__ xlo) {
+    __shared__ float wgt[16 * 32];   // NS <= 16
+    __shared__ float invL[32];
+    const int head = blockIdx.x, t = blockIdx.y;
+    const size_t p0 = (size_t)(t * Hq + head) * NS;
+    if (threadIdx.x < 32) {
+        const int row = threadIdx.x;
+        float M = -INFINITY;
+        for (int s = 0; s < NS; ++s) M = fmaxf(M, MLpart[(p0 + s) * 64 + row]);
+        float L = 0.f;
+        for (int s = 0; s < NS; ++s) {
+            float ms = MLpart[(p0 + s) * 64 + row];
+            float f = (ms == -INFINITY) ? 0.f : exp2f((ms - M) * scale_log2e);
+            wgt[s * 32 + row] = f;
+            L += f * MLpart[(p0 + s) * 64 + 32 + row];
+        }
+        invL[row] = L > 0.f ? 1.f / L : 0.f;
+    }
+    __syncthreads();
+    const int KS = Hq * HD / 16;
+    for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
+        const int row = item & 31, oct = item >> 5;
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = 0.f;
+        for (int s = 0; s < NS; ++s) {
+            const float f = wgt[s * 32 + row];
+            const float *o = Opart + (p0 + s) * 32 * HD + row * HD + oct * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] += f * o[e];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= invL[row];
+        uint4 hi, lo;
+        pack8_split(v, hi, lo);
+        size_t vec = (size_t)t * KS * 64 + frag_vec(row, head * (HD / 8) + oct);
+        xhi[vec] = hi;
+        xlo[vec] = lo;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// acceptance and commit, one block per sequence
+// ------------------------------------------------------------------------------------------
+struct AcceptOut { int *accept_len, *n_committed, *committed; };   // device [B], [B], [B][k]
+
+__device__ __forceinline__ void commit_tokens(SeqState st, AcceptOut out, int b, int k, int a, int corr, const int *d,
+                                              int eos) {
+    // thread 0 only
+    int n = (a < k) ? a + 1 : k;
+    int fin = 0;
+    for (int i = 0; i < n; ++i) {
+        int tok = (i < a) ? d[i] : corr;
+        out.committed[b * k + i] = tok;
+        st.ing_tok[b * 32 + i] = tok;
+        if (eos >= 0 && tok == eos) { n = i + 1; fin = 1; break; }
+    }
+    out.accept_len[b] = a;
+    out.n_committed[b] = n;
+    st.ing_n[b] = n;
+    st.len[b] += n;
+    st.pending[b] = out.committed[b * k + n - 1];
+    if (fin) st.finished[b] = 1;
+}
+
+// T = 0: accept while the draft equals the target's argmax; the first mismatch is replaced by it
+__global__ void k_accept_greedy(SeqState st, AcceptOut out, const int *__restrict__ draft,
+                                const RowResult *__restrict__ tres, int k, int eos) {
+    const int b = blockIdx.x;
+    if (threadIdx.x != 0) return;
+    if (st.finished[b]) { out.accept_len[b] = 0; out.n_committed[b] = 0; return; }
+    const int *d = draft + b * k;
+    int a = k, corr = -1;
+    for (int i = 0; i < k; ++i) {
+        int tgt = tres[b * k + i].argmax;
+        if (d[i] != tgt) { a = i; corr = tgt; break; }
+    }
+    commit_tokens(st, out, b, k, a, corr, d, eos);
+}
+
+// T > 0: u_i <= min(1, p_i(y^_i) / q_i(y^_i)) in log space, stop at the first rejection and draw the
+// replacement from max(0, p_i - q_i) by Gumbel-max (falls back to p_i when the residual is empty).
+__global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut out, const int *__restrict__ draft,
+                                                        const RowResult *__restrict__ tres,
+                                                        const RowResult *__restrict__ dres,
+                                                        const float *__restrict__ tlogits,
+                                                        const float *__restrict__ dlogits, int k, int V, float T,
+                                                        uint64_t seed, int eos) {
+    __shared__ int s_a;
+    __shared__ float sv[1024]; __shared__ int sx[1024]; __shared__ int s_any[1024];
+    const int b = blockIdx.x;
+    if (st.finished[b]) {
+        if (threadIdx.x == 0) { out.accept_len[b] = 0; out.n_committed[b] = 0; }
+        return;
+    }
+    const int *d = draft + b * k;
+    const int j = st.len[b];
+    const float invT = 1.f / T;
+    if (threadIdx.x == 0) {
+        int a = k;
+        for (int i = 0; i < k; ++i) {
+            const size_t r = (size_t)b * k + i;
+            const int y = d[i];
+            const float logp = tlogits[r * V + y] * invT - tres[r].lse;
+            const float logq = dlogits[r * V + y] * invT - dres[r].lse;
+            const float u = uniform01(row_key(seed, TAG_ACCEPT, (uint64_t)b, (uint64_t)(j + i)), 0);
+            if (!(logf(u) <= fminf(0.f, logp - logq))) { a = i; break; }
+        }
+        s_a = a;
+    }
+    __syncthreads();
+    const int a = s_a;
+    int corr = -1;
+    if (a < k) {
+        const size_t r = (size_t)b * k + a;
+        const float lt = tres[r].lse, ld = dres[r].lse;
+        const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
+        float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
+        for (int v = threadIdx.x; v < V; v += 1024) {
+            const float logp = tlogits[r * V + v] * invT - lt;
+            const float logq = dlogits[r * V + v] * invT - ld;
+            const float diff = expf(logp) - expf(logq);
+            const float gn = gumbel(key, (uint64_t)v);
+            if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+            argmax_merge(bestp, bpi, logp + gn, v);
+        }
+        s_any[threadIdx.x] = any;
+        __syncthreads();
+        for (int off = 512; off > 0; off >>= 1) {
+            if (threadIdx.x < off) s_any[threadIdx.x] |= s_any[threadIdx.x + off];
+            __syncthreads();
+        }
+        const int use_resid = s_any[0];
+        sv[threadIdx.x] = use_resid ? best : bestp;
+        sx[threadIdx.x] = use_resid ? bi : bpi;
+        __syncthreads();
+        for (int off = 512; off > 0; off >>= 1) {
+            if (threadIdx.x < off) argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
+            __syncthreads();
+        }
+        corr = sx[0];
+    }
+    if (threadIdx.x == 0) commit_tokens(st, out, b, k, a, corr, d, eos);
+}
+
+}  // namespace deer

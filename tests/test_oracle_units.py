@@ -147,3 +147,12 @@ def test_bf16_roundtrip_plumbing():
         assert (t == b).all()
     except ImportError:
         pass
+
+
+def test_round_to_bf16_matches_torch_cast():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(9)
+    x = np.concatenate([rng.normal(size=5000) * 3, [1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -1.0 - 2 ** -8, 0.0]]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(O.round_to_bf16(x), ref)
+    assert O.round_to_bf16(x.astype(np.float64)).dtype == np.float64
