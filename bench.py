@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of DEER's draft-verify step on one MI355X.
+
+A "step" is one pass of the whole hot path - draft_block, verify_block, accept_and_commit - over
+the headline workload: Qwen3-8B-shaped target, 24-layer d=896 drafter, batch 1, prefix 4096,
+block size k=32, T=0, bf16 weights and caches, random-init weights, uniform-random prompt.
+Everything is resident in HBM before the timed region starts.
+
+Because random-init weights accept (almost) nothing at T=0, committed tokens/s is reported under a
+stated accepted-length law: truncated geometric on a in {0..k} with mean k/4 (= `value`) and 3k/4.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import deer_inputs as di  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+
+
+def trunc_geom(k, mean):
+    """rho with E[a] = mean for P(a=i) = (1-rho) rho^i (i<k), P(a=k) = rho^k; returns (rho, E[n_committed])."""
+    lo, hi = 0.0, 1.0 - 1e-12
+    f = lambda r: r * (1 - r ** k) / (1 - r)
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if f(mid) < mean:
+            lo = mid
+        else:
+            hi = mid
+    rho = 0.5 * (lo + hi)
+    return rho, f(rho) + 1 - rho ** k
+
+
+def verify_bytes(shape, prefix, k):
+    """Algorithmic HBM bytes of one verify pass at batch 1: every projection + LM head once (bf16),
+    plus the K,V rows of the prefix and the block (bf16)."""
+    d, hd = shape.d_model, shape.head_dim
+    layer = d * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * d + 3 * d * shape.d_ff
+    weights = 2.0 * (shape.n_layers * layer + d * shape.vocab)
+    kv = 2.0 * 2 * shape.n_layers * shape.n_kv_heads * hd * (prefix - 1 + k)
+    return weights, kv
+
+
+def load_random_model(eng, model, shape, seed):
+    """Random-init N(0, 0.02) bf16 weights generated on the device (the benchmark needs the shapes
+    and the value distribution, not a particular seed stream)."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+
+    def rnd(rows, cols):
+        return (torch.randn(rows, cols, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+
+    eng.load_tensor(model, "embed", -1, -1, rnd(*shape.tensor_shape("embed")))
+    eng.load_tensor(model, "lm_head", -1, -1, rnd(*shape.tensor_shape("lm_head")))
+    for l in range(shape.n_layers):
+        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            eng.load_tensor(model, name, l, -1, rnd(*shape.tensor_shape(name)))
+
+
+def cpu_baseline(cfg, k, prefix, e_ncommit):
+    """The oracle, as it stands, timed on this host on a bounded sample of the workload."""
+    from threadpoolctl import threadpool_info
+    from oracle import deer_oracle as O
+    cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+
+    def provider(shape, seed):
+        cache = {}
+
+        def get(name, layer=-1, expert=-1):
+            key = (name, layer)
+            if key not in cache:
+                cache[key] = di.weight_f32(shape, seed, name, layer, expert, threads=cores)
+            return cache[key]
+        return get
+
+    def time_pass(shape, seed, n_layers, drafter):
+        s = di.scaled(shape, n_layers=n_layers)
+        dec = O.Decoder(s, provider(s, seed), np.float32, "bf16")
+        cache = O.KVCache(s, prefix + k + 1, np.float32)
+        n_old = prefix if drafter else prefix - 1
+        for l in range(n_layers):
+            cache.K[l, :n_old] = di.bf16_bits_to_f32(di.kv_fill_bits(s, "k", l, 0, n_old, threads=cores))
+            cache.V[l, :n_old] = di.bf16_bits_to_f32(di.kv_fill_bits(s, "v", l, 0, n_old, threads=cores))
+        cache.n = n_old
+        ids = di.prompt_ids(s.vocab, k, seq=7)
+        for name in ("embed", "lm_head"):
+            dec._w(name)
+        for l in range(n_layers):
+            for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+                dec._w(name, l)
+        t0 = time.perf_counter()
+        if drafter:
+            z = dec.forward([di.mask_token_id(s.vocab)] * k, np.arange(n_old, n_old + k), cache, O.drafter_block_mask(0, k), 0)
+        else:
+            z = dec.forward(ids, np.arange(n_old, n_old + k), cache, O.causal_mask(k), k)
+        tok = [O.argmax_lowest(z[i]) for i in range(k)]
+        dt = time.perf_counter() - t0
+        return dt, tok
+
+    t, d = cfg["target"], cfg["drafter"]
+    t1, tok_t = time_pass(t, di.TARGET_SEED, 1, False)
+    t2, _ = time_pass(t, di.TARGET_SEED, 2, False)
+    d1, tok_d = time_pass(d, di.DRAFTER_SEED, 1, True)
+    d2, _ = time_pass(d, di.DRAFTER_SEED, 2, True)
+    t0 = time.perf_counter()
+    O.accept_block_greedy(tok_t, tok_d)
+    t_acc = time.perf_counter() - t0
+    per_t, per_d = max(t2 - t1, 1e-9), max(d2 - d1, 1e-9)
+    full = (t1 - per_t) + t.n_layers * per_t + (d1 - per_d) + d.n_layers * per_d + t_acc
+    return {
+        "value": e_ncommit / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"one draft+verify+accept iteration of the numpy fp32 oracle at the workload's widths, vocab, "
+                   f"prefix {prefix} (seeded KV fill) and k={k}, run with 1 and 2 layers of each model "
+                   f"(target {t1:.2f}s/{t2:.2f}s, drafter {d1:.2f}s/{d2:.2f}s) and extrapolated linearly to "
+                   f"{t.n_layers}+{d.n_layers} layers: {full:.1f}s per iteration"),
+        "iteration_s": full,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="qwen3_8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding or collectives are built); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_15176_amd import DeerEngine, binding
+
+    cfg = di.CONFIGS[args.config]
+    t, d, k, prefix = cfg["target"], cfg["drafter"], cfg["k"], cfg["prefix"]
+    max_seq = (prefix + (args.steps + args.warmup + 8) * k + k + 63) // 64 * 64
+    eng = DeerEngine(t, d, 1, max_seq, k, di.mask_token_id(t.vocab), -1, False)
+    load_random_model(eng, binding.DEER_TARGET, t, di.TARGET_SEED)
+    load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
+    prompt = di.prompt_ids(t.vocab, prefix)
+    t0 = time.perf_counter()
+    eng.prefill([prompt])
+    prefill_s = time.perf_counter() - t0
+
+    def step(events=None):
+        if events:
+            events[0].record()
+        dr = eng.draft_block(k, 0.0, 0)
+        if events:
+            events[1].record()
+        eng.verify_block(k, 0.0, dr)
+        if events:
+            events[2].record()
+        out = eng.accept_and_commit(k, 0.0, 0)
+        if events:
+            events[3].record()
+        return out
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    acc_hist = np.zeros(k + 1, dtype=np.int64)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        acc, _, _ = step(evs[i])
+        acc_hist[acc[0]] += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall / args.steps * 1e3
+    td = np.median([e[0].elapsed_time(e[1]) for e in evs])
+    tv = np.median([e[1].elapsed_time(e[2]) for e in evs])
+    ta = np.median([e[2].elapsed_time(e[3]) for e in evs])
+
+    # per-launch timing of the dominant kernel (weight-streaming GEMM) inside verify passes
+    eng.debug_profile(True)
+    n_prof = 3
+    g_ms = g_bytes = a_ms = a_bytes = 0.0
+    g_n = a_n = 0
+    for _ in range(n_prof):
+        dr = eng.draft_block(k, 0.0, 0)
+        eng.synchronize()
+        eng.debug_profile(True)   # drop the drafter's launches: keep verify only
+        eng.verify_block(k, 0.0, dr)
+        r0, r1 = eng.debug_profile_read(0), eng.debug_profile_read(1)
+        g_ms, g_n, g_bytes = g_ms + r0[0], g_n + r0[1], g_bytes + r0[2]
+        a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
+        eng.accept_and_commit(k, 0.0, 0)
+    eng.debug_profile(False)
+
+    wbytes, kvbytes = verify_bytes(t, prefix, k)
+    rho8, en8 = trunc_geom(k, k / 4)
+    rho24, en24 = trunc_geom(k, 3 * k / 4)
+    iter_ms = td + tv + ta
+    gemm_gbs = g_bytes / (g_ms * 1e-3) / 1e9
+    out = {
+        "metric": "committed tokens/s per draft-verify step, 8B shape k=32; verify HBM GB/s vs peak",
+        "value": en8 / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.config}: target {t.n_layers}L d={t.d_model}, drafter {d.n_layers}L d={d.d_model}, "
+                               f"batch 1, prefix {prefix}, k={k}, T=0, random-init bf16 weights",
+                   "accepted_length_law": f"truncated geometric, mean {k // 4} (value) / {3 * k // 4}",
+                   "expected_committed_per_step": [en8, en24]},
+        "tokens_per_s_mean_accept_8": en8 / (ms_per_step * 1e-3),
+        "tokens_per_s_mean_accept_24": en24 / (ms_per_step * 1e-3),
+        "draft_ms": float(td), "verify_ms": float(tv), "accept_ms": float(ta), "event_iter_ms": float(iter_ms),
+        "prefill_s": prefill_s,
+        "measured_accept_hist": {str(i): int(c) for i, c in enumerate(acc_hist) if c},
+        "verify_pass": {"algorithmic_bytes": wbytes + kvbytes, "GBs": (wbytes + kvbytes) / (tv * 1e-3) / 1e9,
+                        "frac_of_hbm_peak": (wbytes + kvbytes) / (tv * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "k_gemm (weight-streaming GEMM, verify pass)", "achieved": gemm_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "launches": int(g_n), "avg_launch_us": g_ms / max(g_n, 1) * 1e3,
+                     "bytes_per_launch": g_bytes / max(g_n, 1)},
+        "attention_kernel": {"launches": int(a_n), "avg_launch_us": a_ms / max(a_n, 1) * 1e3,
+                             "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, k, prefix, en8)
+    eng.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -156,8 +156,14 @@ const char *deer_last_error(const deer_ctx *c); /* c may be NULL: last init-time
  * or T > 0 in that pass.  Waits for the stream. */
 int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_floats);
 
-/* Replaces the commit decided by the last deer_accept_and_commit... not needed: instead, a test
- * that must follow the oracle after a low-margin split re-prefills.  Reserved. */
+/* Per-launch timing for the benchmark.  While enabled, every launch of the weight-streaming GEMM
+ * (kernel_class 0) and of the block-attention kernel (kernel_class 1) is bracketed by HIP events
+ * on the context's stream.  deer_debug_profile(c, on) waits for the stream, switches recording
+ * and forgets earlier records; deer_debug_profile_read waits for the stream and returns, for one
+ * class, the summed event time (ms), the number of launches, and their algorithmic bytes (weight
+ * bytes of each GEMM; K and V rows visible to each attention launch). */
+int deer_debug_profile(deer_ctx *c, int enable);
+int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes);
 
 /* Current committed length j per sequence (host mirror). */
 int deer_get_lengths(const deer_ctx *c, int32_t *len_host);
@@ -171,9 +177,6 @@ typedef struct {
     int32_t max_seq, head_dim;
 } deer_kv_layout;
 int deer_get_kv_layout(const deer_ctx *c, int model, deer_kv_layout *out);
-
-/* Runs the weight-streaming GEMM of the verify pass alone, `iters` times, on the given layer's
- * gate/up projection (benchmark aid; results are discarded). Reserved for profiling. */
 
 #ifdef __cplusplus
 }

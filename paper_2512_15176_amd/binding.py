@@ -16,7 +16,8 @@ TENSOR_IDS = {"embed": 1, "lm_head": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6, "wg"
 STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACITY", -4: "DEER_EHIP", -5: "DEER_EVERSION"}
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
-           "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout"]
+           "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
+           "deer_debug_profile_read"]
 
 
 class DeerError(RuntimeError):
@@ -77,6 +78,8 @@ def load_library(path: str = LIB_PATH):
     lib.deer_debug_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
     lib.deer_get_lengths.argtypes = [C.c_void_p, C.c_void_p]
     lib.deer_get_kv_layout.argtypes = [C.c_void_p, C.c_int, C.POINTER(KvLayout)]
+    lib.deer_debug_profile.argtypes = [C.c_void_p, C.c_int]
+    lib.deer_debug_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = lib
     return lib
 
@@ -132,7 +135,7 @@ class DeerEngine:
             raise DeerError(rc, self.lib.deer_last_error(None).decode())
         self.ctx = ctx
         self.batch = 0
-        self._draft = torch.zeros((max_batch, max_k), dtype=torch.int32, device=self.device)
+        self._draft = torch.zeros(max_batch * 32, dtype=torch.int32, device=self.device)
 
     # -- helpers ---------------------------------------------------------------------------------
     def _check(self, rc):
@@ -152,8 +155,16 @@ class DeerEngine:
 
     # -- weights ---------------------------------------------------------------------------------
     def load_tensor(self, model, name, layer, expert, array):
-        """array: numpy float32 (canonical values) or uint16 (bf16 bit patterns), [rows][cols]."""
+        """array: numpy float32 (canonical values) or uint16 (bf16 bit patterns), [rows][cols]; or a
+        contiguous torch device tensor (float32 / bfloat16) that is already resident."""
         torch = self.torch
+        if isinstance(array, torch.Tensor):
+            assert array.is_cuda and array.is_contiguous() and array.dim() == 2
+            dt = {torch.float32: DEER_F32, torch.bfloat16: DEER_BF16}[array.dtype]
+            self._check(self.lib.deer_load_tensor(self.ctx, model, TENSOR_IDS[name], layer, expert, array.data_ptr(), dt,
+                                                  array.shape[0], array.shape[1]))
+            torch.cuda.current_stream(self.device).synchronize()
+            return
         a = np.ascontiguousarray(array)
         if a.dtype == np.uint16:
             dev = torch.from_numpy(a.view(np.int16)).to(self.device)
@@ -190,9 +201,8 @@ class DeerEngine:
 
     def draft_block(self, k, T=0.0, seed=0):
         """Returns the device tensor [batch][k] (int32) of drafted tokens."""
-        buf = self._draft.view(-1)[: self.batch * k].view(self.batch, k)
-        self._check(self.lib.deer_draft_block(self.ctx, k, T, seed, buf.data_ptr()))
-        return buf
+        self._check(self.lib.deer_draft_block(self.ctx, k, T, seed, self._draft.data_ptr()))
+        return self._draft[: self.batch * k].view(self.batch, k)
 
     def verify_block(self, k, T, draft_dev):
         assert draft_dev.is_cuda and draft_dev.dtype == self.torch.int32 and draft_dev.is_contiguous()
@@ -211,6 +221,15 @@ class DeerEngine:
         out = np.empty((self.batch, k, self.target.vocab), dtype=np.float32)
         self._check(self.lib.deer_debug_get_logits(self.ctx, model, out.ctypes.data, out.size))
         return out
+
+    def debug_profile(self, enable):
+        self._check(self.lib.deer_debug_profile(self.ctx, int(enable)))
+
+    def debug_profile_read(self, kernel_class):
+        """(total_ms, launches, algorithmic_bytes) of the recorded launches of one kernel class."""
+        ms, n, by = C.c_double(), C.c_int64(), C.c_double()
+        self._check(self.lib.deer_debug_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(by)))
+        return ms.value, n.value, by.value
 
     def get_lengths(self):
         out = np.zeros(self.batch, dtype=np.int32)

@@ -72,6 +72,12 @@ struct deer_ctx {
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
     std::string err;
+    // optional per-launch timing (deer_debug_profile)
+    bool prof_on = false;
+    struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
 };
 
 namespace {
@@ -85,6 +91,30 @@ int fail(deer_ctx *c, int code, const char *fmt, ...) {
     if (c) c->err = buf; else g_init_error = buf;
     return code;
 }
+
+hipEvent_t prof_event(deer_ctx *c) {
+    if (c->ev_used == c->ev_pool.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        c->ev_pool.push_back(e);
+    }
+    return c->ev_pool[c->ev_used++];
+}
+
+// brackets one launch with events when profiling is on
+struct ProfScope {
+    deer_ctx *c; int cls; double bytes; hipEvent_t a = nullptr;
+    ProfScope(deer_ctx *c_, int cls_, double bytes_) : c(c_), cls(cls_), bytes(bytes_) {
+        if (c->prof_on && (a = prof_event(c))) (void)hipEventRecord(a, c->stream);
+    }
+    ~ProfScope() {
+        if (!a) return;
+        hipEvent_t b = prof_event(c);
+        if (!b) return;
+        (void)hipEventRecord(b, c->stream);
+        c->prof.push_back({cls, a, b, bytes});
+    }
+};
 
 #define HIPCHK(c, expr)                                                                            \
     do {                                                                                           \
@@ -206,6 +236,7 @@ int launch_gemm(deer_ctx *c, const void *W, const uint4 *xhi, const uint4 *xlo, 
     const int zg = ntiles / MT;
     const int S = force_S > 0 ? force_S : choose_split(N, KS, zg);
     dim3 grid(N / CG, S, zg);
+    ProfScope ps(c, 0, (double)N * K * 2.0);
     if (MT == 2)
         hipLaunchKernelGGL(k_gemm<2>, grid, dim3(256), 0, c->stream, (const uint4 *)W, xhi, xlo, part, N, KS, S, mt0, mt_stride, ntiles * 32);
     else
@@ -219,15 +250,18 @@ int launch_gemm(deer_ctx *c, const void *W, const uint4 *xhi, const uint4 *xlo, 
 struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; };
 
 template <int HD>
-int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float scale_log2e) {
+int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float scale_log2e, double kv_bytes) {
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
     const int G = mc.n_q_heads / mc.n_kv_heads;
     const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
     const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
+    {
+    ProfScope ps(c, 1, kv_bytes);
     hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * G * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                        m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart, w.mlpart,
                        mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e);
+    }
     LAUNCHCHK(c, "k_attn");
     hipLaunchKernelGGL(k_attn_combine<HD>, dim3(mc.n_q_heads, ntiles), dim3(256), 0, c->stream, w.opart, w.mlpart, NS,
                        mc.n_q_heads, scale_log2e, w.xb_hi, w.xb_lo);
@@ -236,7 +270,7 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
 }
 
 // One forward pass of `model` over the rows described by the row metadata (ntiles tiles).
-int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm) {
+int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total = 0.0) {
     ModelRT &m = c->m[model];
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
@@ -255,6 +289,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     NS = std::max(1, std::min({NS, MAX_NS, (nkt + 3) / 4}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
     GemmOut go{};
+    const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     for (int l = 0; l < mc.n_layers; ++l) {
         const char *lw = m.w + m.off_layers + (size_t)l * m.layer_bytes;
         int rc = launch_gemm(c, lw + m.lo_qkv, w.xa_hi, w.xa_lo, w.part, m.n_qkv, d, ntiles, 0, 1, 0, &go);
@@ -264,9 +299,9 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         hipLaunchKernelGGL(k_epi_qkv, dim3(m.n_qkv / CG, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, m.n_qkv,
                            w.ssq, ncg_d, d, mc.rms_eps, w.cs, w.rm, w.q_hi, w.q_lo, kv, mc.n_q_heads, mc.n_kv_heads, hd);
         LAUNCHCHK(c, "k_epi_qkv");
-        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, scale_log2e);
-        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, scale_log2e);
-        else rc = launch_attn<32>(c, m, l, ntiles, NS, scale_log2e);
+        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
+        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
+        else rc = launch_attn<32>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
         if (rc) return rc;
         rc = launch_gemm(c, lw + m.lo_o, w.xb_hi, w.xb_lo, w.part, d, m.kattn, ntiles, 0, 1, 0, &go);
         if (rc) return rc;
@@ -489,7 +524,9 @@ int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *dr
     hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps);
     LAUNCHCHK(c, "k_rows_draft");
     LmPlan lm{true, 0, tps, B, k, T, seed};
-    int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm);
+    double keys = 0;
+    for (int b = 0; b < B; ++b) keys += c->h_len[b] + k;
+    int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm, keys);
     if (rc) return rc;
     hipLaunchKernelGGL(k_draft_finish, dim3(B), dim3(32), 0, c->stream, w.st, w.res[DEER_DRAFTER], draft_dev, k);
     LAUNCHCHK(c, "k_draft_finish");
@@ -512,7 +549,9 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k);
     LAUNCHCHK(c, "k_rows_verify");
     LmPlan lm{true, 0, 1, B, k, T, 0};
-    int rc = run_pass(c, DEER_TARGET, B, maxlim, lm);
+    double keys = 0;
+    for (int b = 0; b < B; ++b) keys += c->h_len[b] - 1 + k;
+    int rc = run_pass(c, DEER_TARGET, B, maxlim, lm, keys);
     if (rc) return rc;
     c->wk_draft = draft_dev;
     c->state = ST_VERIFIED;
@@ -548,7 +587,8 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
 
 int deer_destroy(deer_ctx *c) {
     if (!c) return DEER_EINVAL;
-    hipStreamSynchronize(c->stream);
+    (void)hipStreamSynchronize(c->stream);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     delete c;
     return DEER_OK;
 }
@@ -564,6 +604,28 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
     if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
     HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    return DEER_OK;
+}
+
+int deer_debug_profile(deer_ctx *c, int enable) {
+    if (!c) return DEER_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->prof_on = enable != 0;
+    c->prof.clear();
+    c->ev_used = 0;
+    return DEER_OK;
+}
+
+int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes) {
+    if (!c || !total_ms || !launches || !bytes) return DEER_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    *total_ms = 0.0; *launches = 0; *bytes = 0.0;
+    for (const auto &r : c->prof) {
+        if (r.cls != kernel_class) continue;
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, r.a, r.b));
+        *total_ms += ms; *launches += 1; *bytes += r.bytes;
+    }
     return DEER_OK;
 }
 

@@ -1,0 +1,62 @@
+"""GPU parity at the real layer widths (8B-, 4B- and drafter-shaped layers, 2 layers each so the
+fp32 oracle finishes in seconds): prefixes that span several 32-row tiles with a ragged tail, block
+sizes 32 and 16, forced accepted lengths so the drafter ingests 1, k and a middling number of rows."""
+import numpy as np
+import pytest
+
+import deer_inputs as di
+from oracle import deer_oracle as O
+from gpu_common import StoredWeights, gpu_available, make_engine, make_pair, top2_margin
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
+
+TOL = 2e-2   # logits, max abs (the stated bar); observed errors are far smaller and are printed
+
+
+CASES = {
+    "8b_layers": dict(target=di.scaled(di.CONFIGS["qwen3_8b"]["target"], n_layers=2, vocab=16384),
+                      drafter=di.scaled(di.DRAFTER_05B, n_layers=2, vocab=16384), prefix=203, k=32,
+                      forced=[0, 32, 7]),
+    "4b_layers_full_vocab": dict(target=di.scaled(di.CONFIGS["qwen3_4b"]["target"], n_layers=2),
+                                 drafter=di.scaled(di.DRAFTER_05B, n_layers=1), prefix=97, k=16,
+                                 forced=[16, 3]),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_lockstep_at_real_widths(name):
+    import torch
+    case = CASES[name]
+    t, d, k, n = case["target"], case["drafter"], case["k"], case["prefix"]
+    wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    eng = make_engine(t, d, wt, wd, 1, 512, k)
+    pair = make_pair(t, d, wt, wd, 512, dtype=np.float32)
+    prompt = di.prompt_ids(t.vocab, n)
+    pair.prefill(prompt)
+    eng.prefill([prompt])
+    dec = O.Decoder(t, wt.as_f32, np.float32, "bf16")
+    worst_d = worst_t = 0.0
+    for a_want in case["forced"]:
+        truth = O.ar_decode(dec, pair.prefix(), k)
+        block = list(truth)
+        if a_want < k:
+            block[a_want] = (block[a_want] + 1) % t.vocab
+        gd = eng.draft_block(k, 0.0, 0).cpu().numpy()[0]
+        res = O.deer_iteration(pair, k, 0.0, None, draft_override=block)
+        zd = res["draft_logits"]
+        ed = float(np.abs(eng.debug_get_logits(1, k)[0] - zd).max())
+        ok = top2_margin(zd) > 1e-2
+        assert np.array_equal(gd[ok], np.argmax(zd, -1)[ok])
+        eng.verify_block(k, 0.0, torch.tensor([block], dtype=torch.int32, device="cuda"))
+        et = float(np.abs(eng.debug_get_logits(0, k)[0] - res["target_logits"]).max())
+        worst_d, worst_t = max(worst_d, ed), max(worst_t, et)
+        assert ed < TOL and et < TOL, (ed, et)
+        acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
+        margins = top2_margin(res["target_logits"])[: min(a_want + 1, k)]
+        if margins.min() > 1e-2:
+            assert acc[0] == a_want == res["accept_len"]
+            assert com[0] == res["committed"]
+        else:   # keep the two sides on the same text
+            pytest.skip("low-margin position inside the compared prefix")
+    print(f"\n[{name}] max |logit error|: drafter {worst_d:.2e}, target {worst_t:.2e}")
+    eng.close()

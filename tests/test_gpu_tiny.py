@@ -121,17 +121,19 @@ def test_t0_free_running_equals_greedy_ar(setup):
         acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
         assert 0 <= acc[0] <= k and ncom[0] == min(acc[0] + 1, k)
         out += com[0]
-    # compare up to the first position whose oracle margin is too small to fix the argmax
+    # token for token; a difference is tolerated only where the oracle's top-2 margin is below 1e-2
     cache = O.KVCache(t, 256, np.float64)
     x = list(prompt)
     z = dec.forward(x, np.arange(len(x)), cache, O.causal_mask(len(x)), len(x), logits_rows=[len(x) - 1])[0]
+    compared = 0
     for i in range(40):
-        if top2_margin(z[None])[0] < 1e-2:
+        if out[i] != truth[i]:
+            assert top2_margin(z[None])[0] < 1e-2, (i, out[i], truth[i])
             break
-        assert out[i] == truth[i], i
+        compared += 1
         z = dec.forward([truth[i]], [len(x)], cache, O.causal_mask(1), 1)[0]
         x.append(truth[i])
-    assert i > 10
+    assert compared >= 20
 
 
 def test_call_order_and_argument_errors(setup):
