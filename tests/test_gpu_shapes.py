@@ -52,11 +52,12 @@ def test_lockstep_at_real_widths(name):
         worst_d, worst_t = max(worst_d, ed), max(worst_t, et)
         assert ed < TOL and et < TOL, (ed, et)
         acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
-        margins = top2_margin(res["target_logits"])[: min(a_want + 1, k)]
-        if margins.min() > 1e-2:
-            assert acc[0] == a_want == res["accept_len"]
-            assert com[0] == res["committed"]
-        else:   # keep the two sides on the same text
-            pytest.skip("low-margin position inside the compared prefix")
+        if acc[0] != res["accept_len"] or com[0] != res["committed"]:
+            # only a position whose oracle top-2 margin is below 1e-2 may decide differently
+            first = min(acc[0], res["accept_len"])
+            assert top2_margin(res["target_logits"])[first] < 1e-2, (acc, com, res["accept_len"], res["committed"])
+            eng.prefill([pair.prefix()])      # put both sides back on the oracle's text
+        else:
+            assert acc[0] == a_want
     print(f"\n[{name}] max |logit error|: drafter {worst_d:.2e}, target {worst_t:.2e}")
     eng.close()
