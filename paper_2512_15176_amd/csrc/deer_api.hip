@@ -43,7 +43,7 @@ struct Work {   // carved from the workspace
     SeqState st{};
     RowMeta rm{};
     float2 *cs = nullptr;
-    float *h = nullptr, *ssq = nullptr, *part = nullptr, *lmpart = nullptr;
+    float *h = nullptr, *ssq = nullptr, *part = nullptr;
     uint4 *xa_hi = nullptr, *xa_lo = nullptr, *xb_hi = nullptr, *xb_lo = nullptr, *q_hi = nullptr, *q_lo = nullptr;
     float *opart = nullptr, *mlpart = nullptr;
     float *logits[2] = {nullptr, nullptr};
@@ -51,6 +51,8 @@ struct Work {   // carved from the workspace
     RowResult *res[2] = {nullptr, nullptr};
     AcceptOut ao{};
     int *ids = nullptr;                // prompt staging [max_seq]
+    int *gemm_cnt = nullptr, *attn_cnt = nullptr;   // arrival counters, zero between kernels
+    size_t cnt_bytes = 0; char *cnt_base = nullptr;
     double *theta[2] = {nullptr, nullptr};
     size_t bytes = 0;
 };
@@ -192,7 +194,6 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.xb_hi = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024); w.xb_lo = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024);
     w.q_hi = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024); w.q_lo = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024);
     w.part = (float *)take((size_t)MAXR * PART_COLS * 4);
-    w.lmpart = (float *)take(lmrows * V * 4);
     w.opart = (float *)take((size_t)MAXT * hq * MAX_NS * 32 * hdmax * 4);
     w.mlpart = (float *)take((size_t)MAXT * hq * MAX_NS * 64 * 4);
     w.logits[0] = (float *)take(lmrows * V * 4); w.logits[1] = (float *)take(lmrows * V * 4);
@@ -200,6 +201,13 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
     w.ao.accept_len = (int *)take(B * 4); w.ao.n_committed = (int *)take(B * 4); w.ao.committed = (int *)take((size_t)B * 32 * 4);
     w.ids = (int *)take((size_t)p.max_seq * 4);
+    {
+        const size_t ng = (size_t)(std::max(std::max(t.d_model, d.d_model), 4 * (int)fmax) / CG + 64) * MAXT, na = (size_t)MAXT * hq;
+        w.cnt_base = take((ng + na) * 4);
+        w.gemm_cnt = (int *)w.cnt_base;
+        w.attn_cnt = w.gemm_cnt ? w.gemm_cnt + ng : nullptr;
+        w.cnt_bytes = (ng + na) * 4;
+    }
     w.bytes = off;
 }
 
@@ -221,29 +229,26 @@ const char *check_params(const deer_init_params *p) {
 // ---------------------------------------------------------------------------------------------
 int choose_split(int N, int KS, int zgroups) {
     int blocks = (N / CG) * zgroups;
-    int S = (512 + blocks - 1) / blocks;
-    S = std::min(S, std::max(1, KS / 8));            // at least 2 k-steps per wave
+    int S = (256 + blocks - 1) / blocks;
+    S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);
 }
 
-struct GemmOut { int S, rows_total; };
-
-int launch_gemm(deer_ctx *c, const void *W, const uint4 *xhi, const uint4 *xlo, float *part, int N, int K, int ntiles,
-                int mt0, int mt_stride, int force_S, GemmOut *o) {
-    const int KS = K / 16;
+template <int EPI>
+int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
+    a.KS = K / 16;
     const int MT = (ntiles % 2 == 0) ? 2 : 1;
     const int zg = ntiles / MT;
-    const int S = force_S > 0 ? force_S : choose_split(N, KS, zg);
-    dim3 grid(N / CG, S, zg);
-    ProfScope ps(c, 0, (double)N * K * 2.0);
-    if (MT == 2)
-        hipLaunchKernelGGL(k_gemm<2>, grid, dim3(256), 0, c->stream, (const uint4 *)W, xhi, xlo, part, N, KS, S, mt0, mt_stride, ntiles * 32);
-    else
-        hipLaunchKernelGGL(k_gemm<1>, grid, dim3(256), 0, c->stream, (const uint4 *)W, xhi, xlo, part, N, KS, S, mt0, mt_stride, ntiles * 32);
+    a.S = force_S > 0 ? force_S : choose_split(a.N, a.KS, zg);
+    a.rows_total = ntiles * 32;
+    a.part = (EPI == EPI_LMHEAD) ? nullptr : c->wk.part;
+    a.counters = c->wk.gemm_cnt;
+    dim3 grid(a.N / CG, a.S, zg);
+    ProfScope ps(c, 0, (double)a.N * K * 2.0);
+    if (MT == 2) hipLaunchKernelGGL((k_gemm<2, EPI>), grid, dim3(512), 0, c->stream, a);
+    else hipLaunchKernelGGL((k_gemm<1, EPI>), grid, dim3(512), 0, c->stream, a);
     LAUNCHCHK(c, "k_gemm");
-    o->S = S;
-    o->rows_total = ntiles * 32;
     return DEER_OK;
 }
 
@@ -256,16 +261,11 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     const int G = mc.n_q_heads / mc.n_kv_heads;
     const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
     const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
-    {
     ProfScope ps(c, 1, kv_bytes);
     hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * G * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                        m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart, w.mlpart,
-                       mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e);
-    }
+                       mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.attn_cnt, w.xb_hi, w.xb_lo);
     LAUNCHCHK(c, "k_attn");
-    hipLaunchKernelGGL(k_attn_combine<HD>, dim3(mc.n_q_heads, ntiles), dim3(256), 0, c->stream, w.opart, w.mlpart, NS,
-                       mc.n_q_heads, scale_log2e, w.xb_hi, w.xb_lo);
-    LAUNCHCHK(c, "k_attn_combine");
     return DEER_OK;
 }
 
@@ -288,46 +288,48 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     int NS = (512 + mc.n_q_heads * ntiles - 1) / (mc.n_q_heads * ntiles);
     NS = std::max(1, std::min({NS, MAX_NS, (nkt + 3) / 4}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
-    GemmOut go{};
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
+    GemmArgs base{};
+    base.mt0 = 0; base.mt_stride = 1;
+    base.ssq_in = w.ssq; base.ncg_in = ncg_d; base.d_in = d; base.eps = mc.rms_eps;
+    base.cs = w.cs; base.rm = w.rm; base.qhi = w.q_hi; base.qlo = w.q_lo;
+    base.Hq = mc.n_q_heads; base.Hkv = mc.n_kv_heads; base.hd = hd;
+    base.h = w.h; base.xhi_out = w.xa_hi; base.xlo_out = w.xa_lo; base.ssq_out = w.ssq;
+    base.ahi = w.xb_hi; base.alo = w.xb_lo; base.F = m.F;
     for (int l = 0; l < mc.n_layers; ++l) {
         const char *lw = m.w + m.off_layers + (size_t)l * m.layer_bytes;
-        int rc = launch_gemm(c, lw + m.lo_qkv, w.xa_hi, w.xa_lo, w.part, m.n_qkv, d, ntiles, 0, 1, 0, &go);
+        GemmArgs a = base;
+        a.W = (const uint4 *)(lw + m.lo_qkv); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = m.n_qkv;
+        a.kv = KvView{m.kv + m.kv_k_base + (size_t)l * m.kv_layer_stride, m.kv + m.kv_v_base + (size_t)l * m.kv_layer_stride,
+                      m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
+        int rc = launch_gemm<EPI_QKV>(c, a, d, ntiles, 0);
         if (rc) return rc;
-        KvView kv{m.kv + m.kv_k_base + (size_t)l * m.kv_layer_stride, m.kv + m.kv_v_base + (size_t)l * m.kv_layer_stride,
-                  m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
-        hipLaunchKernelGGL(k_epi_qkv, dim3(m.n_qkv / CG, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, m.n_qkv,
-                           w.ssq, ncg_d, d, mc.rms_eps, w.cs, w.rm, w.q_hi, w.q_lo, kv, mc.n_q_heads, mc.n_kv_heads, hd);
-        LAUNCHCHK(c, "k_epi_qkv");
         if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
         else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
         else rc = launch_attn<32>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
         if (rc) return rc;
-        rc = launch_gemm(c, lw + m.lo_o, w.xb_hi, w.xb_lo, w.part, d, m.kattn, ntiles, 0, 1, 0, &go);
+        a = base;
+        a.W = (const uint4 *)(lw + m.lo_o); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
+        rc = launch_gemm<EPI_RESID>(c, a, m.kattn, ntiles, 0);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_epi_residual, dim3(ncg_d, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, d, w.h,
-                           w.xa_hi, w.xa_lo, w.ssq);
-        LAUNCHCHK(c, "k_epi_residual");
-        rc = launch_gemm(c, lw + m.lo_gu, w.xa_hi, w.xa_lo, w.part, 2 * m.F, d, ntiles, 0, 1, 0, &go);
+        a = base;
+        a.W = (const uint4 *)(lw + m.lo_gu); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = 2 * m.F;
+        rc = launch_gemm<EPI_SWIGLU>(c, a, d, ntiles, 0);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_epi_swiglu, dim3(2 * m.F / CG, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, 2 * m.F,
-                           w.ssq, ncg_d, d, mc.rms_eps, w.xb_hi, w.xb_lo, m.F);
-        LAUNCHCHK(c, "k_epi_swiglu");
-        rc = launch_gemm(c, lw + m.lo_d, w.xb_hi, w.xb_lo, w.part, d, m.F, ntiles, 0, 1, 0, &go);
+        a = base;
+        a.W = (const uint4 *)(lw + m.lo_d); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
+        rc = launch_gemm<EPI_RESID>(c, a, m.F, ntiles, 0);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_epi_residual, dim3(ncg_d, ntiles), dim3(256), 0, s, w.part, go.S, go.rows_total, d, w.h,
-                           w.xa_hi, w.xa_lo, w.ssq);
-        LAUNCHCHK(c, "k_epi_residual");
     }
     if (lm.on) {
         const int V = mc.vocab;
-        int rc = launch_gemm(c, m.w + m.off_lm, w.xa_hi, w.xa_lo, w.lmpart, V, d, lm.n_tiles, lm.mt0, lm.mt_stride, 1, &go);
+        GemmArgs a = base;
+        a.W = (const uint4 *)(m.w + m.off_lm); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = V;
+        a.mt0 = lm.mt0; a.mt_stride = lm.mt_stride;
+        a.k = lm.k; a.T = lm.T; a.seed = lm.seed; a.stat = w.stat; a.ncg_v = V / CG;
+        a.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
+        int rc = launch_gemm<EPI_LMHEAD>(c, a, d, lm.n_tiles, 1);
         if (rc) return rc;
-        float *logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
-        hipLaunchKernelGGL(k_epi_lmhead, dim3(V / CG, lm.n_tiles), dim3(256), 0, s, w.lmpart, go.rows_total, V, w.ssq, ncg_d,
-                           d, mc.rms_eps, lm.mt0, lm.mt_stride, lm.k, logits, lm.T, lm.seed, w.rm.tile_seq, w.rm.pos, w.stat,
-                           V / CG);
-        LAUNCHCHK(c, "k_epi_lmhead");
         hipLaunchKernelGGL(k_rowstat_final, dim3(lm.n_tiles * lm.k), dim3(256), 0, s, w.stat, V / CG, lm.T, w.res[model]);
         LAUNCHCHK(c, "k_rowstat_final");
     }
@@ -413,6 +415,8 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         e = hipMemcpy(c->m[i].theta, th, sizeof(double) * (mc.head_dim / 2), hipMemcpyHostToDevice);
         if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemcpy: %s", hipGetErrorString(e)); }
     }
+    e = hipMemsetAsync(c->wk.cnt_base, 0, c->wk.cnt_bytes, c->stream);
+    if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e)); }
     *out = c;
@@ -521,7 +525,7 @@ int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *dr
     }
     Work &w = c->wk;
     const int tps = any_ing ? 2 : 1;
-    hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps);
+    hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps, c->p.drafter.vocab);
     LAUNCHCHK(c, "k_rows_draft");
     LmPlan lm{true, 0, tps, B, k, T, seed};
     double keys = 0;
@@ -546,7 +550,7 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     int maxlim = 0;
     for (int b = 0; b < B; ++b) maxlim = std::max(maxlim, c->h_len[b] - 1 + k);
     Work &w = c->wk;
-    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k);
+    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k, c->p.target.vocab);
     LAUNCHCHK(c, "k_rows_verify");
     LmPlan lm{true, 0, 1, B, k, T, 0};
     double keys = 0;

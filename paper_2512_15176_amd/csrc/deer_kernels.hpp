@@ -21,6 +21,7 @@ namespace deer {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // a 16-byte operand fragment held in registers
 
 constexpr int TILE_M = 32;       // rows per tile
 constexpr int CG = 128;          // columns per column group (4 MFMA column blocks)
@@ -54,6 +55,10 @@ __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
 // Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
 __device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -75,6 +80,32 @@ __device__ __forceinline__ float uniform01(uint64_t key, uint64_t idx) {  // (r 
     return ((float)(uint32_t)(bits >> 41) + 0.5f) * (1.0f / 8388608.0f);
 }
 __device__ __forceinline__ float gumbel(uint64_t key, uint64_t idx) { return -logf(-logf(uniform01(key, idx))); }
+
+// Split-K / split-KV partials cross workgroups that may sit on different XCDs (separate L2s).  They
+// are written and read with agent-scope accesses, which are coherent without cache-wide
+// write-backs or invalidates; the arrival counter is an agent-scope atomic.
+__device__ __forceinline__ void st_agent2(float *p, float a, float b) {   // p 8-byte aligned
+    unsigned long long u = ((unsigned long long)__float_as_uint(b) << 32) | (unsigned long long)__float_as_uint(a);
+    __hip_atomic_store((unsigned long long *)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float *p) {
+    unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)(u & 0xffffffffu)), __uint_as_float((unsigned)(u >> 32)));
+}
+// Called by every thread after its partial stores: waits for them, then one thread counts the block
+// in.  Returns true in every thread of the block that arrived last (counter reset for the next use).
+__device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // drains this thread's stores
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int last = (old == expected - 1);
+        if (last) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = last;
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
 
 // (value, index) max with lowest index on ties
 __device__ __forceinline__ void argmax_merge(float &v, int &i, float v2, int i2) {
@@ -140,14 +171,17 @@ struct RowMeta {        // device arrays over the rows of a pass
 };
 
 // verify rows of sequence b: tile b; row i < k: [x_j, y^_1 .. y^_{k-1}] at positions j-1+i
-__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k) {
+// token ids that reach the embedding gather are forced into [0, vocab): drafts come from caller memory
+__device__ __forceinline__ int safe_tok(int t, int vocab) { return (t < 0 || t >= vocab) ? 0 : t; }
+
+__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k, int vocab) {
     int b = blockIdx.x, i = threadIdx.x;
     int row = b * 32 + i;
     int j = st.len[b];
     if (i == 0) rm.tile_seq[b] = b;
     if (i < k) {
         int p = j - 1 + i;
-        rm.tok[row] = (i == 0) ? st.pending[b] : draft[b * k + i - 1];
+        rm.tok[row] = safe_tok((i == 0) ? st.pending[b] : draft[b * k + i - 1], vocab);
         rm.pos[row] = p;
         rm.slot[row] = p;
         rm.limit[row] = p + 1;
@@ -159,7 +193,7 @@ __global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ d
 // draft rows of sequence b: tile 2b = k MASK rows at positions j..j+k-1 (see cache + ingested rows +
 // every MASK row; their K,V land in slots past the cached length and are never kept); tile 2b+1 =
 // the m not-yet-cached committed tokens, causal.  With tiles_per_seq == 1 only the MASK tile exists.
-__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq) {
+__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq, int vocab) {
     int b = blockIdx.x, i = threadIdx.x;   // 64 threads
     int t = i >> 5, r = i & 31;
     if (t >= tiles_per_seq) return;
@@ -170,7 +204,7 @@ __global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int ti
     if (t == 0 && r < k) {
         rm.tok[row] = mask_id; rm.pos[row] = j + r; rm.slot[row] = j + r; rm.limit[row] = j + k;
     } else if (t == 1 && r < m) {
-        rm.tok[row] = st.ing_tok[b * 32 + r]; rm.pos[row] = dl + r; rm.slot[row] = dl + r; rm.limit[row] = dl + r + 1;
+        rm.tok[row] = safe_tok(st.ing_tok[b * 32 + r], vocab); rm.pos[row] = dl + r; rm.slot[row] = dl + r; rm.limit[row] = dl + r + 1;
     } else {
         rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
     }
@@ -236,20 +270,228 @@ __global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, c
 }
 
 // ------------------------------------------------------------------------------------------
-// weight-streaming GEMM for short row counts:  part[s][ct*32 + i][n] = sum over k-slice of x[i][k] W[k][n]
-//   grid: x = column group (128 columns), y = split s, z = group of MT row tiles
-//   block: 4 waves; wave w takes k-slice (s*4 + w) of 4*S; each wave owns all 4 column blocks, so
-//   one activation fragment feeds 4 weight fragments; the 4 waves are reduced through LDS.
+// weight-streaming GEMM for short row counts with the layer's elementwise work fused behind it
+//   y[i][n] = sum_k x[i][k] W[k][n]  for MT row tiles of 32 and one group of 128 columns per block.
+//   grid: x = column group, y = split s of the K range, z = group of MT row tiles.
+//   block: 8 waves; wave w streams k-slice (s*8 + w) of 8*S for all 4 column blocks of the group
+//   (one activation fragment pair feeds 4 weight fragments); the 8 waves are summed through LDS in a
+//   fixed tree.  S == 1: the epilogue runs on the tile in LDS.  S > 1: the tile goes to a partial
+//   buffer and the block that arrives last at the group's counter sums the S partials in order
+//   s = 0..S-1 and runs the epilogue, so results do not depend on arrival order.
 //   Tiles of the launch: tile(ct) = mt0 + ct * mt_stride, ct = z*MT + mt.
 // ------------------------------------------------------------------------------------------
-template <int MT>
-__global__ __launch_bounds__(256) void k_gemm(const uint4 *__restrict__ W, const uint4 *__restrict__ Xhi,
-                                              const uint4 *__restrict__ Xlo, float *__restrict__ part, int N, int KS,
-                                              int S, int mt0, int mt_stride, int rows_total) {
-    __shared__ float red[2 * 32 * RED_STRIDE];
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+
+struct KvView {
+    uint16_t *k, *vt;                                  // layer base already applied
+    size_t seq_stride, head_stride;                    // elements
+    int max_seq;
+};
+
+struct RowStat {   // per (row, column group) partial over 128 vocabulary entries
+    float m; int idx;        // max logit, its index (lowest on ties)
+    float sumexp;            // sum exp(z/T - m/T)  (T > 0)
+    float gm; int gidx;      // max of z/T + Gumbel, its index (T > 0)
+};
+
+struct GemmArgs {
+    const uint4 *W, *Xhi, *Xlo;
+    float *part; int *counters;
+    int N, KS, S, mt0, mt_stride, rows_total;
+    // RMSNorm of the GEMM input rows: rstd from per-group sums of squares (QKV, SWIGLU, LMHEAD)
+    const float *ssq_in; int ncg_in, d_in; float eps;
+    // QKV: RoPE, Q fragments, cache writes
+    const float2 *cs; RowMeta rm; uint4 *qhi, *qlo; KvView kv; int Hq, Hkv, hd;
+    // RESID: h += y, new fragments and sums of squares of h
+    float *h; uint4 *xhi_out, *xlo_out; float *ssq_out;
+    // SWIGLU: activation fragments over F channels
+    uint4 *ahi, *alo; int F;
+    // LMHEAD: logits, per-group row statistics
+    int k; float *logits; float T; uint64_t seed; RowStat *stat; int ncg_v;
+};
+
+// rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
+__device__ __forceinline__ void tile_rstd(const float *__restrict__ ssq, float *rstd, int grow0, int ncg, int d, float eps) {
+    if (threadIdx.x < 32) {
+        const float *p = ssq + (size_t)(grow0 + threadIdx.x) * ncg;
+        float s = 0.f;
+        for (int g = 0; g < ncg; ++g) s += p[g];
+        rstd[threadIdx.x] = rsqrtf(s / (float)d + eps);
+    }
+}
+
+// QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
+__device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
+    const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
+    const int half_hd = hd >> 1;
+    const int b = a.rm.tile_seq[t];
+    for (int item = threadIdx.x; item < 512; item += blockDim.x) {
+        const int row = item & 31, oct = item >> 5;
+        const int grow = t * 32 + row;
+        const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
+        const int kind = col0 < Hq * hd ? 0 : (col0 < (Hq + Hkv) * hd ? 1 : 2);
+        const int hc = col0 - (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd));
+        const int head = hc / hd, i0 = hc % hd;
+        const float sc = rstd[row];
+        float v[8];
+        if (kind < 2) {
+            const int poff = (i0 < half_hd) ? half_hd : -half_hd;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float x = tile[row * RED_STRIDE + oct * 8 + e] * sc;
+                float xp = tile[row * RED_STRIDE + oct * 8 + e + poff] * sc;
+                float2 c = a.cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
+                v[e] = (i0 < half_hd) ? x * c.x - xp * c.y : x * c.x + xp * c.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = tile[row * RED_STRIDE + oct * 8 + e] * sc;
+        }
+        if (kind == 0) {
+            uint4 hi, lo;
+            pack8_split(v, hi, lo);
+            size_t vec = ((size_t)(t * Hq + head) * (hd / 16)) * 64 + frag_vec(row, i0 >> 3);
+            a.qhi[vec] = hi;
+            a.qlo[vec] = lo;
+        } else {
+            const int slot = a.rm.slot[grow];
+            if (slot >= 0) {
+                uint32_t u[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) u[e] = f2bf(v[e]);
+                size_t base = (size_t)b * a.kv.seq_stride + (size_t)head * a.kv.head_stride;
+                if (kind == 1) {
+                    *(uint4 *)(a.kv.k + base + (size_t)slot * hd + i0) =
+                        make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) a.kv.vt[base + (size_t)(i0 + e) * a.kv.max_seq + slot] = (uint16_t)u[e];
+                }
+            }
+        }
+    }
+}
+
+// O-proj / down-proj epilogue: h += y; new fragment planes of h; per-group sum of squares.
+// `tile` is overwritten with the new h values.
+__device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, int cg, int t) {
+    const int N = a.N;
+    for (int e = threadIdx.x; e < 32 * CG; e += blockDim.x) {
+        int row = e >> 7, col = e & 127;
+        size_t gi = (size_t)(t * 32 + row) * N + cg * CG + col;
+        float v = a.h[gi] + tile[row * RED_STRIDE + col];
+        a.h[gi] = v;
+        tile[row * RED_STRIDE + col] = v;
+    }
+    __syncthreads();
+    for (int item = threadIdx.x; item < 512; item += blockDim.x) {
+        int row = item & 31, oct = item >> 5;
+        uint4 hi, lo;
+        pack8_split(tile + row * RED_STRIDE + oct * 8, hi, lo);
+        size_t v = (size_t)t * (N / 16) * 64 + frag_vec(row, cg * 16 + oct);
+        a.xhi_out[v] = hi;
+        a.xlo_out[v] = lo;
+    }
+    if (threadIdx.x < 32) {
+        float s = 0.f;
+        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
+        a.ssq_out[(size_t)(t * 32 + threadIdx.x) * (N / CG) + cg] = s;
+    }
+}
+
+// gate/up epilogue: group = 64 gate + 64 up channels -> SiLU(g) * u, fragment planes over F
+__device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
+    for (int item = threadIdx.x; item < 256; item += blockDim.x) {
+        const int row = item & 31, oct = item >> 5;   // 8 octets of 8 channels
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float g = tile[row * RED_STRIDE + oct * 8 + e] * rstd[row];
+            float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * rstd[row];
+            v[e] = g / (1.f + expf(-g)) * u;
+        }
+        uint4 hi, lo;
+        pack8_split(v, hi, lo);
+        size_t vec = (size_t)t * (a.F / 16) * 64 + frag_vec(row, cg * 8 + oct);
+        a.ahi[vec] = hi;
+        a.alo[vec] = lo;
+    }
+}
+
+// LM-head epilogue: RMSNorm scale, optional logits store, per-(row, group) argmax / sumexp / Gumbel-max.
+// LM rows are the first k rows of the tile; lm_row = ct*k + i.
+__device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile, const float *rstd, int cg, int ct, int t) {
+    if (threadIdx.x >= 256) return;
+    const int V = a.N, k = a.k;
+    const float T = a.T;
+    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;   // 8 threads per row, 16 columns each
+    const bool live = row < k;
+    float m = -INFINITY, gm = -INFINITY, se = 0.f;
+    int idx = 0x7fffffff, gidx = 0x7fffffff;
+    float z[16];
+    const float invT = T > 0.f ? 1.f / T : 1.f;
+    if (live) {
+        const float sc = rstd[row];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = tile[row * RED_STRIDE + sub * 16 + e] * sc;
+        if (a.logits) {
+            float *q = a.logits + ((size_t)ct * k + row) * V + (size_t)cg * CG + sub * 16;
+#pragma unroll
+            for (int e = 0; e < 16; e += 4) *(float4 *)(q + e) = make_float4(z[e], z[e + 1], z[e + 2], z[e + 3]);
+        }
+        uint64_t key = 0;
+        if (T > 0.f) key = row_key(a.seed, TAG_DRAFT, (uint64_t)a.rm.tile_seq[t], (uint64_t)a.rm.pos[t * 32 + row]);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            int v = cg * CG + sub * 16 + e;
+            argmax_merge(m, idx, z[e], v);
+            if (T > 0.f) argmax_merge(gm, gidx, z[e] * invT + gumbel(key, (uint64_t)v), v);
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) {
+        float m2 = __shfl_xor(m, off); int i2 = __shfl_xor(idx, off);
+        argmax_merge(m, idx, m2, i2);
+        float g2 = __shfl_xor(gm, off); int gi2 = __shfl_xor(gidx, off);
+        argmax_merge(gm, gidx, g2, gi2);
+    }
+    if (live && T > 0.f) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) se += expf((z[e] - m) * invT);
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
+    if (live && sub == 0) {
+        RowStat s;
+        s.m = m; s.idx = idx; s.sumexp = se; s.gm = gm; s.gidx = gidx;
+        a.stat[((size_t)ct * k + row) * a.ncg_v + cg] = s;
+    }
+}
+
+template <int EPI>
+__device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, int cg, int ct) {
+    // caller has synchronised after filling `tile`
+    const int t = a.mt0 + ct * a.mt_stride;
+    if (EPI != EPI_RESID) {
+        tile_rstd(a.ssq_in, rstd, t * 32, a.ncg_in, a.d_in, a.eps);
+        __syncthreads();
+    }
+    if (EPI == EPI_QKV) epi_qkv(a, tile, rstd, cg, t);
+    else if (EPI == EPI_RESID) epi_resid(a, tile, cg, t);
+    else if (EPI == EPI_SWIGLU) epi_swiglu(a, tile, rstd, cg, t);
+    else epi_lmhead(a, tile, rstd, cg, ct, t);
+}
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
+    __shared__ float red[4 * 32 * 128];   // wave-reduction scratch; the finished tile lives at red + 4096
+    __shared__ float s_rstd[32];
+    __shared__ int s_last;
+    float *tile = red + 32 * 128;         // stride RED_STRIDE
     const int cg = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int slices = S * 4, sl = s * 4 + w;
+    const int N = a.N, KS = a.KS, S = a.S;
+    const int slices = S * 8, sl = s * 8 + w;
     const int per = (KS + slices - 1) / slices;
     const int ks0 = sl * per;
     const int ks1 = min(KS, ks0 + per);
@@ -262,17 +504,18 @@ __global__ __launch_bounds__(256) void k_gemm(const uint4 *__restrict__ W, const
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nb][r] = 0.f;
 
-    const uint4 *wp = W + ((size_t)(cg * 4) * KS) * 64 + lane;
+    const uint4 *wp = a.W + ((size_t)(cg * 4) * KS) * 64 + lane;
     const size_t wstride = (size_t)KS * 64;   // between column blocks
     const uint4 *xh[MT], *xl[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        size_t tile = (size_t)(mt0 + (z * MT + mt) * mt_stride);
-        xh[mt] = Xhi + tile * KS * 64 + lane;
-        xl[mt] = Xlo + tile * KS * 64 + lane;
+        size_t tl = (size_t)(a.mt0 + (z * MT + mt) * a.mt_stride);
+        xh[mt] = a.Xhi + tl * KS * 64 + lane;
+        xl[mt] = a.Xlo + tl * KS * 64 + lane;
     }
 
-    constexpr int D = 4;  // k-steps in flight
+    // Software pipeline: D k-steps of loads are in flight while older steps are multiplied.
+    constexpr int D = (MT == 1) ? 4 : 2;   // bounded by the register file: no spills
     uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) {
@@ -307,240 +550,79 @@ __global__ __launch_bounds__(256) void k_gemm(const uint4 *__restrict__ W, const
         }
     }
 
-    // reduce the 4 waves through LDS in a fixed order, (w0 + w2) + (w1 + w3), one row tile at a time
+    // fixed-order tree over the 8 waves: ((w0+w4)+(w2+w6)) + ((w1+w5)+(w3+w7))
     const int half = lane >> 5, cl = lane & 31;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         if (mt > 0) __syncthreads();
-        if (w >= 2) {
+#pragma unroll
+        for (int round = 0; round < 3; ++round) {
+            const int hi_lo = 4 >> round;   // waves [hi_lo, 2*hi_lo) store, waves [0, hi_lo) add
+            if (w >= hi_lo && w < 2 * hi_lo) {
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        red[((w - hi_lo) * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl] = acc[mt][nb][r];
+            }
+            __syncthreads();
+            if (w < hi_lo) {
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        acc[mt][nb][r] += red[(w * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl];
+            }
+            __syncthreads();
+        }
+        if (w == 0) {
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    red[((w - 2) * 32 + mfma_row(r, half)) * RED_STRIDE + nb * 32 + cl] = acc[mt][nb][r];
+                for (int r = 0; r < 16; ++r) tile[mfma_row(r, half) * RED_STRIDE + nb * 32 + cl] = acc[mt][nb][r];
         }
         __syncthreads();
-        if (w < 2) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    red[(w * 32 + mfma_row(r, half)) * RED_STRIDE + nb * 32 + cl] += acc[mt][nb][r];
-        }
-        __syncthreads();
-        const int col = threadIdx.x & 127;
         const int ct = z * MT + mt;
-        float *out = part + ((size_t)s * rows_total + (size_t)ct * 32) * N + (size_t)cg * CG + col;
-        for (int row = threadIdx.x >> 7; row < 32; row += 2)
-            out[(size_t)row * N] = red[row * RED_STRIDE + col] + red[(32 + row) * RED_STRIDE + col];
-    }
-}
-
-// sum the S split partials of a 32x128 tile into LDS (stride RED_STRIDE), fixed order s = 0..S-1
-__device__ __forceinline__ void sum_partials(const float *__restrict__ part, float *tile, int S, int rows_total, int N,
-                                             int ct, int cg) {
-    const int col = threadIdx.x & 127;
-    for (int row = threadIdx.x >> 7; row < 32; row += 2) {
-        const float *p = part + ((size_t)ct * 32 + row) * N + (size_t)cg * CG + col;
-        float v = 0.f;
-        for (int s = 0; s < S; ++s) v += p[(size_t)s * rows_total * N];
-        tile[row * RED_STRIDE + col] = v;
-    }
-}
-
-// rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
-__device__ __forceinline__ void tile_rstd(const float *__restrict__ ssq, float *rstd, int grow0, int ncg, int d, float eps) {
-    if (threadIdx.x < 32) {
-        const float *p = ssq + (size_t)(grow0 + threadIdx.x) * ncg;
-        float s = 0.f;
-        for (int g = 0; g < ncg; ++g) s += p[g];
-        rstd[threadIdx.x] = rsqrtf(s / (float)d + eps);
-    }
-}
-
-// ------------------------------------------------------------------------------------------
-// epilogue of the fused QKV projection: RMSNorm scale, RoPE, Q -> fragment planes per head,
-// K -> cache, V -> transposed cache.  grid: x = column group of (Hq + 2 Hkv) * hd, y = tile
-// ------------------------------------------------------------------------------------------
-struct KvView {
-    uint16_t *k, *vt;                                  // layer base already applied
-    size_t seq_stride, head_stride;                    // elements
-    int max_seq;
-};
-
-__global__ __launch_bounds__(256) void k_epi_qkv(const float *__restrict__ part, int S, int rows_total, int N,
-                                                 const float *__restrict__ ssq, int ncg_in, int d, float eps,
-                                                 const float2 *__restrict__ cs, RowMeta rm, uint4 *__restrict__ qhi,
-                                                 uint4 *__restrict__ qlo, KvView kv, int Hq, int Hkv, int hd) {
-    __shared__ float tile[32 * RED_STRIDE];
-    __shared__ float rstd[32];
-    const int cg = blockIdx.x, t = blockIdx.y;   // all tiles of the pass take part: ct == t
-    sum_partials(part, tile, S, rows_total, N, t, cg);
-    tile_rstd(ssq, rstd, t * 32, ncg_in, d, eps);
-    __syncthreads();
-    const int half_hd = hd >> 1;
-    const int b = rm.tile_seq[t];
-    for (int item = threadIdx.x; item < 512; item += 256) {
-        const int row = item & 31, oct = item >> 5;
-        const int grow = t * 32 + row;
-        const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
-        const int kind = col0 < Hq * hd ? 0 : (col0 < (Hq + Hkv) * hd ? 1 : 2);
-        const int hc = col0 - (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd));
-        const int head = hc / hd, i0 = hc % hd;
-        const float sc = rstd[row];
-        float v[8];
-        if (kind < 2) {
-            const int poff = (i0 < half_hd) ? half_hd : -half_hd;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float x = tile[row * RED_STRIDE + oct * 8 + e] * sc;
-                float xp = tile[row * RED_STRIDE + oct * 8 + e + poff] * sc;
-                float2 c = cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
-                v[e] = (i0 < half_hd) ? x * c.x - xp * c.y : x * c.x + xp * c.y;
-            }
+        if (S == 1) {
+            run_epilogue<EPI>(a, tile, s_rstd, cg, ct);
         } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = tile[row * RED_STRIDE + oct * 8 + e] * sc;
-        }
-        if (kind == 0) {
-            uint4 hi, lo;
-            pack8_split(v, hi, lo);
-            size_t vec = ((size_t)(t * Hq + head) * (hd / 16)) * 64 + frag_vec(row, i0 >> 3);
-            qhi[vec] = hi;
-            qlo[vec] = lo;
-        } else {
-            const int slot = rm.slot[grow];
-            if (slot >= 0) {
-                uint32_t u[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) u[e] = f2bf(v[e]);
-                size_t base = (size_t)b * kv.seq_stride + (size_t)head * kv.head_stride;
-                if (kind == 1) {
-                    *(uint4 *)(kv.k + base + (size_t)slot * hd + i0) =
-                        make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) kv.vt[base + (size_t)(i0 + e) * kv.max_seq + slot] = (uint16_t)u[e];
-                }
+            float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
+            for (int e = threadIdx.x; e < 32 * 64; e += 512) {
+                const int row = e >> 6, c2 = (e & 63) * 2;
+                const float *tp = tile + row * RED_STRIDE + c2;
+                st_agent2(out + (size_t)row * N + c2, tp[0], tp[1]);
             }
         }
     }
-}
+    if (S == 1) return;
 
-// epilogue of O-proj / down-proj: h += y; new fragment planes of h; per-group sum of squares
-__global__ __launch_bounds__(256) void k_epi_residual(const float *__restrict__ part, int S, int rows_total, int N,
-                                                      float *__restrict__ h, uint4 *__restrict__ xhi,
-                                                      uint4 *__restrict__ xlo, float *__restrict__ ssq) {
-    __shared__ float tile[32 * RED_STRIDE];
-    const int cg = blockIdx.x, t = blockIdx.y, ncg = gridDim.x;
-    sum_partials(part, tile, S, rows_total, N, t, cg);
-    __syncthreads();
-    for (int e = threadIdx.x; e < 32 * CG; e += 256) {
-        int row = e >> 7, col = e & 127;
-        size_t gi = (size_t)(t * 32 + row) * N + cg * CG + col;
-        float v = h[gi] + tile[row * RED_STRIDE + col];
-        h[gi] = v;
-        tile[row * RED_STRIDE + col] = v;
-    }
-    __syncthreads();
-    tile_to_frag(tile, xhi, xlo, (size_t)t * (N / 16) * 64, cg * CG);
-    if (threadIdx.x < 32) {
-        float s = 0.f;
-        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
-        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
-    }
-}
-
-// epilogue of the gate/up projection: group = 64 gate + 64 up channels -> SiLU(g) * u, fragment planes over F
-__global__ __launch_bounds__(256) void k_epi_swiglu(const float *__restrict__ part, int S, int rows_total, int N,
-                                                    const float *__restrict__ ssq, int ncg_in, int d, float eps,
-                                                    uint4 *__restrict__ ahi, uint4 *__restrict__ alo, int F) {
-    __shared__ float tile[32 * RED_STRIDE];
-    __shared__ float rstd[32];
-    const int cg = blockIdx.x, t = blockIdx.y;
-    sum_partials(part, tile, S, rows_total, N, t, cg);
-    tile_rstd(ssq, rstd, t * 32, ncg_in, d, eps);
-    __syncthreads();
-    const int row = threadIdx.x & 31, oct = threadIdx.x >> 5;   // 8 octets of 8 channels
-    float v[8];
+    // the block that arrives last at this column group's counter sums all partials and finishes
+    if (!arrive_last(a.counters + (size_t)z * gridDim.x + cg, S, &s_last)) return;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        float g = tile[row * RED_STRIDE + oct * 8 + e] * rstd[row];
-        float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * rstd[row];
-        v[e] = g / (1.f + expf(-g)) * u;
-    }
-    uint4 hi, lo;
-    pack8_split(v, hi, lo);
-    size_t vec = (size_t)t * (F / 16) * 64 + frag_vec(row, cg * 8 + oct);
-    ahi[vec] = hi;
-    alo[vec] = lo;
-}
-
-// ------------------------------------------------------------------------------------------
-// LM head epilogue and row statistics
-// ------------------------------------------------------------------------------------------
-struct RowStat {   // per (row, column group) partial over 128 vocabulary entries
-    float m; int idx;        // max logit, its index (lowest on ties)
-    float sumexp;            // sum exp(z/T - m/T)  (T > 0)
-    float gm; int gidx;      // max of z/T + Gumbel, its index (T > 0)
-};
-
-// grid: x = vocab group, y = compact LM tile ct (pass tile = mt0 + ct*mt_stride; LM rows are the
-// first k rows of that tile; lm_row = ct*k + i)
-__global__ __launch_bounds__(256) void k_epi_lmhead(float *__restrict__ part, int rows_total, int V,
-                                                    const float *__restrict__ ssq, int ncg_in, int d, float eps, int mt0,
-                                                    int mt_stride, int k, float *__restrict__ logits, float T,
-                                                    uint64_t seed, const int *__restrict__ tile_seq,
-                                                    const int *__restrict__ row_pos, RowStat *__restrict__ stat,
-                                                    int ncg_v) {
-    __shared__ float rstd[32];
-    const int cg = blockIdx.x, ct = blockIdx.y;
-    const int tile = mt0 + ct * mt_stride;
-    tile_rstd(ssq, rstd, tile * 32, ncg_in, d, eps);
-    __syncthreads();
-    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;   // 8 threads per row, 16 columns each
-    const bool live = row < k;
-    float m = -INFINITY, gm = -INFINITY, se = 0.f;
-    int idx = 0x7fffffff, gidx = 0x7fffffff;
-    float z[16];
-    const float invT = T > 0.f ? 1.f / T : 1.f;
-    uint64_t key = 0;
-    if (live) {
-        const float *p = part + ((size_t)ct * 32 + row) * V + (size_t)cg * CG + sub * 16;
-        const float sc = rstd[row];
-#pragma unroll
-        for (int e = 0; e < 16; ++e) z[e] = p[e] * sc;
-        if (logits) {
-            float *q = logits + ((size_t)ct * k + row) * V + (size_t)cg * CG + sub * 16;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) q[e] = z[e];
+    for (int mt = 0; mt < MT; ++mt) {
+        const int ct = z * MT + mt;
+        if (mt > 0) __syncthreads();
+        const size_t sstride = (size_t)a.rows_total * N;
+        for (int e = threadIdx.x; e < 32 * 64; e += 512) {
+            const int row = e >> 6, c2 = (e & 63) * 2;
+            const float *p = a.part + ((size_t)ct * 32 + row) * N + (size_t)cg * CG + c2;
+            float2 v = make_float2(0.f, 0.f);
+            int ss = 0;
+            for (; ss + 4 <= S; ss += 4) {
+                float2 p0 = ld_agent2(p + (size_t)ss * sstride), p1 = ld_agent2(p + (size_t)(ss + 1) * sstride);
+                float2 p2 = ld_agent2(p + (size_t)(ss + 2) * sstride), p3 = ld_agent2(p + (size_t)(ss + 3) * sstride);
+                v.x = (((v.x + p0.x) + p1.x) + p2.x) + p3.x;
+                v.y = (((v.y + p0.y) + p1.y) + p2.y) + p3.y;
+            }
+            for (; ss < S; ++ss) {
+                float2 p0 = ld_agent2(p + (size_t)ss * sstride);
+                v.x += p0.x; v.y += p0.y;
+            }
+            tile[row * RED_STRIDE + c2] = v.x;
+            tile[row * RED_STRIDE + c2 + 1] = v.y;
         }
-        if (T > 0.f) key = row_key(seed, TAG_DRAFT, (uint64_t)tile_seq[tile], (uint64_t)row_pos[tile * 32 + row]);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            int v = cg * CG + sub * 16 + e;
-            argmax_merge(m, idx, z[e], v);
-            if (T > 0.f) argmax_merge(gm, gidx, z[e] * invT + gumbel(key, (uint64_t)v), v);
-        }
-    }
-    // reduce over the 8 threads of a row (they are adjacent lanes)
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) {
-        float m2 = __shfl_xor(m, off); int i2 = __shfl_xor(idx, off);
-        argmax_merge(m, idx, m2, i2);
-        float g2 = __shfl_xor(gm, off); int gi2 = __shfl_xor(gidx, off);
-        argmax_merge(gm, gidx, g2, gi2);
-    }
-    if (live && T > 0.f) {
-#pragma unroll
-        for (int e = 0; e < 16; ++e) se += expf((z[e] - m) * invT);
-    }
-#pragma unroll
-    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
-    if (live && sub == 0) {
-        RowStat s;
-        s.m = m; s.idx = idx; s.sumexp = se; s.gm = gm; s.gidx = gidx;
-        stat[((size_t)ct * k + row) * ncg_v + cg] = s;
+        __syncthreads();
+        run_epilogue<EPI>(a, tile, s_rstd, cg, ct);
     }
 }
 
@@ -586,10 +668,11 @@ __global__ __launch_bounds__(256) void k_rowstat_final(const RowStat *__restrict
     }
     if (threadIdx.x == 0) {
         RowResult r;
-        r.argmax = si[0];
+        const int V = ncg_v * CG;
+        r.argmax = (si[0] >= 0 && si[0] < V) ? si[0] : 0;   // a row of NaNs never updates the index
         r.zmax = M;
-        if (T > 0.f) { r.sample = sgi[0]; r.lse = M / T + logf(ss[0]); }
-        else { r.sample = si[0]; r.lse = 0.f; }
+        if (T > 0.f) { r.sample = (sgi[0] >= 0 && sgi[0] < V) ? sgi[0] : 0; r.lse = M / T + logf(ss[0]); }
+        else { r.sample = r.argmax; r.lse = 0.f; }
         res[row] = r;
     }
 }
@@ -615,7 +698,8 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
                                               size_t seq_stride, size_t head_stride, int max_seq,
                                               const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
                                               float *__restrict__ Opart, float *__restrict__ MLpart, int Hq, int Hkv,
-                                              int NS, float scale_log2e) {
+                                              int NS, float scale_log2e, int *__restrict__ counters,
+                                              uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
     constexpr int KSQ = HD / 16;   // k-steps of the score contraction
     constexpr int HT = HD / 32;    // 32-row tiles of O^T
     __shared__ float sm_o[2 * HD * 33];
@@ -734,65 +818,84 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
         if (half == 0) sm_m[w * 32 + qrow] = M;
     }
     __syncthreads();
-    const size_t pidx = (size_t)(t * Hq + head) * NS + split;
-    for (int e = threadIdx.x; e < 32 * HD; e += 256) {
-        const int row = e / HD, dim = e % HD;
-        const float m0 = sm_m[row], m1 = sm_m[32 + row];
-        const float M = fmaxf(m0, m1);
-        float o = 0.f;
-        if (m0 != -INFINITY) o += exp2f((m0 - M) * scale_log2e) * sm_o[dim * 33 + row];
-        if (m1 != -INFINITY) o += exp2f((m1 - M) * scale_log2e) * sm_o[(HD + dim) * 33 + row];
-        Opart[pidx * 32 * HD + e] = o;
-    }
+    // this block's result: (M, L, O) over its key range, un-normalised
+    __shared__ float s_M[32], s_f0[32], s_f1[32], s_inv[32];
+    __shared__ int s_last;
     if (threadIdx.x < 32) {
         const int row = threadIdx.x;
         const float m0 = sm_m[row], m1 = sm_m[32 + row];
         const float M = fmaxf(m0, m1);
-        float L = 0.f;
-        if (m0 != -INFINITY) L += exp2f((m0 - M) * scale_log2e) * sm_l[row];
-        if (m1 != -INFINITY) L += exp2f((m1 - M) * scale_log2e) * sm_l[32 + row];
-        MLpart[pidx * 64 + row] = M;
-        MLpart[pidx * 64 + 32 + row] = L;
+        const float f0 = (m0 == -INFINITY) ? 0.f : exp2f((m0 - M) * scale_log2e);
+        const float f1 = (m1 == -INFINITY) ? 0.f : exp2f((m1 - M) * scale_log2e);
+        const float L = f0 * sm_l[row] + f1 * sm_l[32 + row];
+        s_M[row] = M; s_f0[row] = f0; s_f1[row] = f1;
+        s_inv[row] = L > 0.f ? 1.f / L : 0.f;
+        if (NS > 1) {
+            const size_t pidx = (size_t)(t * Hq + head) * NS + split;
+            st_agent2(MLpart + pidx * 64 + 2 * row, M, L);   // (M, L) pairs
+        }
     }
-}
-
-// merge the NS key-range partials of one (tile, head), normalise, write fragment planes over Hq*HD
-template <int HD>
-__global__ __launch_bounds__(256) void k_attn_combine(const float *__restrict__ Opart, const float *__restrict__ MLpart,
-                                                      int NS, int Hq, float scale_log2e, uint4 *__restrict__ xhi,
-                                                      uint4 *__restrict__ xlo) {
-    __shared__ float wgt[16 * 32];   // NS <= 16
-    __shared__ float invL[32];
-    const int head = blockIdx.x, t = blockIdx.y;
+    __syncthreads();
+    const int KS = Hq * HD / 16;
+    if (NS == 1) {
+        // single key range: normalise and write the O-projection's input fragments directly
+        for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
+            const int row = item & 31, oct = item >> 5;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int dim = oct * 8 + e;
+                v[e] = (s_f0[row] * sm_o[dim * 33 + row] + s_f1[row] * sm_o[(HD + dim) * 33 + row]) * s_inv[row];
+            }
+            uint4 hi, lo;
+            pack8_split(v, hi, lo);
+            size_t vec = (size_t)t * KS * 64 + frag_vec(row, head * (HD / 8) + oct);
+            xhi[vec] = hi;
+            xlo[vec] = lo;
+        }
+        return;
+    }
+    {
+        const size_t pidx = (size_t)(t * Hq + head) * NS + split;
+        for (int e = threadIdx.x; e < 32 * HD / 2; e += 256) {
+            const int row = e / (HD / 2), dim = (e % (HD / 2)) * 2;
+            st_agent2(Opart + pidx * 32 * HD + row * HD + dim,
+                      s_f0[row] * sm_o[dim * 33 + row] + s_f1[row] * sm_o[(HD + dim) * 33 + row],
+                      s_f0[row] * sm_o[(dim + 1) * 33 + row] + s_f1[row] * sm_o[(HD + dim + 1) * 33 + row]);
+        }
+    }
+    // the block that arrives last at this (tile, head)'s counter merges the NS key ranges in order
+    if (!arrive_last(counters + t * Hq + head, NS, &s_last)) return;
+    float *wgt = sm_o;   // [NS][32] weights, NS <= 16
     const size_t p0 = (size_t)(t * Hq + head) * NS;
     if (threadIdx.x < 32) {
         const int row = threadIdx.x;
         float M = -INFINITY;
-        for (int s = 0; s < NS; ++s) M = fmaxf(M, MLpart[(p0 + s) * 64 + row]);
+        for (int s2 = 0; s2 < NS; ++s2) M = fmaxf(M, ld_agent2(MLpart + (p0 + s2) * 64 + 2 * row).x);
         float L = 0.f;
-        for (int s = 0; s < NS; ++s) {
-            float ms = MLpart[(p0 + s) * 64 + row];
-            float f = (ms == -INFINITY) ? 0.f : exp2f((ms - M) * scale_log2e);
-            wgt[s * 32 + row] = f;
-            L += f * MLpart[(p0 + s) * 64 + 32 + row];
+        for (int s2 = 0; s2 < NS; ++s2) {
+            float2 ml = ld_agent2(MLpart + (p0 + s2) * 64 + 2 * row);
+            float f = (ml.x == -INFINITY) ? 0.f : exp2f((ml.x - M) * scale_log2e);
+            wgt[s2 * 32 + row] = f;
+            L += f * ml.y;
         }
-        invL[row] = L > 0.f ? 1.f / L : 0.f;
+        s_inv[row] = L > 0.f ? 1.f / L : 0.f;
     }
     __syncthreads();
-    const int KS = Hq * HD / 16;
     for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
         const int row = item & 31, oct = item >> 5;
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = 0.f;
-        for (int s = 0; s < NS; ++s) {
-            const float f = wgt[s * 32 + row];
-            const float *o = Opart + (p0 + s) * 32 * HD + row * HD + oct * 8;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] += f * o[e];
+        for (int s2 = 0; s2 < NS; ++s2) {
+            const float f = wgt[s2 * 32 + row];
+            const float *o = Opart + (p0 + s2) * 32 * HD + row * HD + oct * 8;
+            const float2 o0 = ld_agent2(o), o1 = ld_agent2(o + 2), o2 = ld_agent2(o + 4), o3 = ld_agent2(o + 6);
+            v[0] += f * o0.x; v[1] += f * o0.y; v[2] += f * o1.x; v[3] += f * o1.y;
+            v[4] += f * o2.x; v[5] += f * o2.y; v[6] += f * o3.x; v[7] += f * o3.y;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= invL[row];
+        for (int e = 0; e < 8; ++e) v[e] *= s_inv[row];
         uint4 hi, lo;
         pack8_split(v, hi, lo);
         size_t vec = (size_t)t * KS * 64 + frag_vec(row, head * (HD / 8) + oct);
@@ -900,7 +1003,7 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
             if (threadIdx.x < off) argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
             __syncthreads();
         }
-        corr = sx[0];
+        corr = (sx[0] >= 0 && sx[0] < V) ? sx[0] : 0;   // all-NaN rows never update the index
     }
     if (threadIdx.x == 0) commit_tokens(st, out, b, k, a, corr, d, eos);
 }
