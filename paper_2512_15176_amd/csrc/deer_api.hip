@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -19,7 +20,7 @@ namespace {
 
 thread_local std::string g_init_error;
 
-constexpr int MAX_NS = 16;          // key-range splits of block attention
+constexpr int MAX_NS = 32;          // key-range splits of block attention
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -45,7 +46,7 @@ struct Work {   // carved from the workspace
     float2 *cs = nullptr;
     float *h = nullptr, *ssq = nullptr, *part = nullptr;
     uint4 *xa_hi = nullptr, *xa_lo = nullptr, *xb_hi = nullptr, *xb_lo = nullptr, *q_hi = nullptr, *q_lo = nullptr;
-    float *opart = nullptr, *mlpart = nullptr;
+    float *opart = nullptr;
     float *logits[2] = {nullptr, nullptr};
     RowStat *stat = nullptr;
     RowResult *res[2] = {nullptr, nullptr};
@@ -194,8 +195,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.xb_hi = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024); w.xb_lo = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024);
     w.q_hi = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024); w.q_lo = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024);
     w.part = (float *)take((size_t)MAXR * PART_COLS * 4);
-    w.opart = (float *)take((size_t)MAXT * hq * MAX_NS * 32 * hdmax * 4);
-    w.mlpart = (float *)take((size_t)MAXT * hq * MAX_NS * 64 * 4);
+    w.opart = (float *)take((size_t)std::max(64, MAXT) * hq * (32 * hdmax + 64) * 4);
     w.logits[0] = (float *)take(lmrows * V * 4); w.logits[1] = (float *)take(lmrows * V * 4);
     w.stat = (RowStat *)take(lmrows * (V / CG) * sizeof(RowStat));
     w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
@@ -262,8 +262,9 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
     const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
     ProfScope ps(c, 1, kv_bytes);
-    hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * G * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
-                       m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart, w.mlpart,
+    (void)G;
+    hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
+                       m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart,
                        mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.attn_cnt, w.xb_hi, w.xb_lo);
     LAUNCHCHK(c, "k_attn");
     return DEER_OK;
@@ -285,8 +286,10 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         LAUNCHCHK(c, "k_rope_table");
     }
     const int nkt = (max_limit + 31) / 32;
-    int NS = (512 + mc.n_q_heads * ntiles - 1) / (mc.n_q_heads * ntiles);
-    NS = std::max(1, std::min({NS, MAX_NS, (nkt + 3) / 4}));
+    // key-range splits: aim at ~256 blocks; ntiles * NS never exceeds the partial buffer (max(64, tiles))
+    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 128;
+    int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
+    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     GemmArgs base{};

@@ -685,31 +685,73 @@ __global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, i
 }
 
 // ------------------------------------------------------------------------------------------
-// block attention: 32 query rows of ONE query head per block, a contiguous range of key tiles split
-// over the 4 waves, online softmax in fp32; S^T = K Q^T and O^T = V^T P^T so that every MFMA operand
-// is a contraction-contiguous 16-byte vector and the softmax row of a lane is its own column.
-//   grid: x = kvh + Hkv * (g + G * split), y = pass tile.
-//   Key order inside a 32-key tile is permuted (operand row rho holds key 16*((rho/4)%2) +
-//   4*(rho/8) + rho%4) so that a lane's 16 results are 16 consecutive keys.
+// block attention for short query blocks over a long GQA cache.
+//   grid: x = kv_head + Hkv * split, y = pass tile (32 query rows of one sequence).
+//   A block owns one K/V head and one contiguous range of 32-key tiles; wave w serves query heads
+//   g = w, w+4, .. of that K/V head's group, so the waves of a block read the same K/V lines
+//   (one trip from L2 per block, not per query head).  Online softmax in fp32.
+//   S^T = K Q^T and O^T = V^T P^T: every MFMA operand is a contraction-contiguous 16-byte vector and
+//   the softmax row of a lane is its own column.  Key order inside a 32-key tile is permuted
+//   (operand row rho holds key 16*((rho/4)%2) + 4*(rho/8) + rho%4) so that a lane's 16 scores are
+//   16 consecutive keys.  Q and P enter as (hi, lo) bf16 pairs.
+//   Each (tile, head, split) leaves an un-normalised partial (M, L, O) in the MFMA register layout;
+//   the block that arrives last at the (tile, kv_head) counter merges the splits in order and
+//   writes the O-projection's input fragments.
 // ------------------------------------------------------------------------------------------
+template <int HD>
+struct AttnPartial {   // per (tile, head, split): O in register layout [HD/32][8 reg pairs][64 lanes][2], then (M, L)[32]
+    static constexpr int O_FLOATS = 32 * HD;
+    static constexpr int FLOATS = 32 * HD + 64;
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int t, int head, int Hq, int lane,
+                                                uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+    // lane (qrow, half) holds dims 32*tt + 8*q + 4*half + 0..3 in regs 4q..4q+3; the partner lane (other
+    // half) holds the other 4 dims of the octet.  Half 0 writes octets with even q, half 1 odd q.
+    const int half = lane >> 5, qrow = lane & 31;
+    const int KS = Hq * HD / 16;
+#pragma unroll
+    for (int tt = 0; tt < HD / 32; ++tt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float mine[4], other[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                mine[e] = o[tt][4 * q + e] * inv;
+                other[e] = __shfl_xor(mine[e], 32);
+            }
+            // octet (tt, q): dims 32*tt + 8*q + 0..7 = half-0 lane's 4 values then half-1 lane's 4 values
+            if ((q & 1) == half) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[e] = half ? other[e] : mine[e]; v[4 + e] = half ? mine[e] : other[e]; }
+                uint4 hi, lo;
+                pack8_split(v, hi, lo);
+                size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
+                xhi[vec] = hi;
+                xlo[vec] = lo;
+            }
+        }
+    }
+}
+
 template <int HD>
 __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
                                               const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
                                               size_t seq_stride, size_t head_stride, int max_seq,
                                               const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
-                                              float *__restrict__ Opart, float *__restrict__ MLpart, int Hq, int Hkv,
-                                              int NS, float scale_log2e, int *__restrict__ counters,
-                                              uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+                                              float *__restrict__ part, int Hq, int Hkv, int NS, float scale_log2e,
+                                              int *__restrict__ counters, uint4 *__restrict__ xhi,
+                                              uint4 *__restrict__ xlo) {
     constexpr int KSQ = HD / 16;   // k-steps of the score contraction
     constexpr int HT = HD / 32;    // 32-row tiles of O^T
-    __shared__ float sm_o[2 * HD * 33];
-    __shared__ float sm_m[2 * 32], sm_l[2 * 32];
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    __shared__ int s_last;
     const int G = Hq / Hkv;
     const int kvh = blockIdx.x % Hkv;
-    const int g = (blockIdx.x / Hkv) % G;
-    const int split = blockIdx.x / (Hkv * G);
+    const int split = blockIdx.x / Hkv;
     const int t = blockIdx.y;
-    const int head = kvh * G + g;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, qrow = lane & 31;
     const int b = tile_seq[t];
     const int lim = row_limit[t * 32 + qrow];
@@ -719,188 +761,145 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
     const int nkt = (maxlim + 31) >> 5;
     const int per = (nkt + NS - 1) / NS;
     const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
-
-    uint4 qh[KSQ], ql[KSQ];
-    {
-        const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
-#pragma unroll
-        for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
-    }
     const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
-    const int rho = qrow;                                              // operand row of the K fragment
-    const int keyperm = 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+    const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);   // operand row -> key
 
-    f32x16 oacc[HT];
+    for (int g = w; g < G; g += 4) {
+        const int head = kvh * G + g;
+        uint4 qh[KSQ], ql[KSQ];
+        {
+            const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
 #pragma unroll
-    for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    for (int kt = kt0 + w; kt < kt1; kt += 4) {
-        f32x16 sacc;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-        const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
-#pragma unroll
-        for (int s = 0; s < KSQ; ++s) {
-            uint4 kf = *(const uint4 *)(kp + s * 16);
-            sacc = mfma32(kf, qh[s], sacc);
-            sacc = mfma32(kf, ql[s], sacc);
+            for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
         }
-        // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
-        const int key0 = kt * 32 + 16 * half;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (key0 + r >= lim) sacc[r] = -INFINITY;
-            mx = fmaxf(mx, sacc[r]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        float p[16];
-        float alpha = 1.f;
-        if (m_new == -INFINITY) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) p[r] = 0.f;
-        } else {
-            alpha = exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
-            float ls = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { p[r] = exp2f((sacc[r] - m_new) * scale_log2e); ls += p[r]; }
-            l_run = l_run * alpha + ls;
-            m_run = m_new;
-        }
+        f32x16 oacc[HT];
 #pragma unroll
         for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
-        uint4 ph[2], pl[2];
-        pack8_split(p, ph[0], pl[0]);
-        pack8_split(p + 8, ph[1], pl[1]);
+            for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
+        float m_run = -INFINITY, l_run = 0.f;
+
+        // K and V fragments of a 32-key tile are requested together, one tile ahead of their use
+        auto load_tile = [&](uint4 (&kf)[KSQ], uint4 (&vf)[HT][2], int kt) {
+            const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
 #pragma unroll
-        for (int tt = 0; tt < HT; ++tt) {
-            const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
+            for (int s = 0; s < KSQ; ++s) kf[s] = *(const uint4 *)(kp + s * 16);
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                uint4 vf = *(const uint4 *)(vp + 8 * s2);
-                oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
-                oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+            for (int tt = 0; tt < HT; ++tt) {
+                const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
+                vf[tt][0] = *(const uint4 *)(vp);
+                vf[tt][1] = *(const uint4 *)(vp + 8);
             }
-        }
-    }
-    // merge the 4 waves in a fixed order: (w0 (+) w2), (w1 (+) w3), then the two results
-    float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (w >= 2) {
-        if (half == 0) { sm_m[(w - 2) * 32 + qrow] = m_run; sm_l[(w - 2) * 32 + qrow] = l_tot; }
+        };
+        auto compute_tile = [&](const uint4 (&kf)[KSQ], const uint4 (&vf)[HT][2], int kt) {
+            f32x16 sacc;
 #pragma unroll
-        for (int tt = 0; tt < HT; ++tt)
+            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sm_o[((w - 2) * HD + tt * 32 + mfma_row(r, half)) * 33 + qrow] = oacc[tt][r];
-    }
-    __syncthreads();
-    if (w < 2) {
-        const float m_b = sm_m[w * 32 + qrow], l_b = sm_l[w * 32 + qrow];
-        const float M = fmaxf(m_run, m_b);
-        const float fa = (m_run == -INFINITY) ? 0.f : exp2f((m_run - M) * scale_log2e);
-        const float fb = (m_b == -INFINITY) ? 0.f : exp2f((m_b - M) * scale_log2e);
-#pragma unroll
-        for (int tt = 0; tt < HT; ++tt)
+            for (int s = 0; s < KSQ; ++s) {
+                sacc = mfma32(kf[s], qh[s], sacc);
+                sacc = mfma32(kf[s], ql[s], sacc);
+            }
+            // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
+            const int key0 = kt * 32 + 16 * half;
+            float mx = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int li = (w * HD + tt * 32 + mfma_row(r, half)) * 33 + qrow;
-                sm_o[li] = oacc[tt][r] * fa + sm_o[li] * fb;
+                if (key0 + r >= lim) sacc[r] = -INFINITY;
+                mx = fmaxf(mx, sacc[r]);
             }
-        if (half == 0) { sm_l[w * 32 + qrow] = l_tot * fa + l_b * fb; }
-        // both halves read m_b above before either writes: order the write after the reads
-        __builtin_amdgcn_wave_barrier();
-        if (half == 0) sm_m[w * 32 + qrow] = M;
-    }
-    __syncthreads();
-    // this block's result: (M, L, O) over its key range, un-normalised
-    __shared__ float s_M[32], s_f0[32], s_f1[32], s_inv[32];
-    __shared__ int s_last;
-    if (threadIdx.x < 32) {
-        const int row = threadIdx.x;
-        const float m0 = sm_m[row], m1 = sm_m[32 + row];
-        const float M = fmaxf(m0, m1);
-        const float f0 = (m0 == -INFINITY) ? 0.f : exp2f((m0 - M) * scale_log2e);
-        const float f1 = (m1 == -INFINITY) ? 0.f : exp2f((m1 - M) * scale_log2e);
-        const float L = f0 * sm_l[row] + f1 * sm_l[32 + row];
-        s_M[row] = M; s_f0[row] = f0; s_f1[row] = f1;
-        s_inv[row] = L > 0.f ? 1.f / L : 0.f;
-        if (NS > 1) {
-            const size_t pidx = (size_t)(t * Hq + head) * NS + split;
-            st_agent2(MLpart + pidx * 64 + 2 * row, M, L);   // (M, L) pairs
-        }
-    }
-    __syncthreads();
-    const int KS = Hq * HD / 16;
-    if (NS == 1) {
-        // single key range: normalise and write the O-projection's input fragments directly
-        for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
-            const int row = item & 31, oct = item >> 5;
-            float v[8];
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx);
+            float p[16];
+            float alpha = 1.f;
+            if (m_new == -INFINITY) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int dim = oct * 8 + e;
-                v[e] = (s_f0[row] * sm_o[dim * 33 + row] + s_f1[row] * sm_o[(HD + dim) * 33 + row]) * s_inv[row];
+                for (int r = 0; r < 16; ++r) p[r] = 0.f;
+            } else {
+                alpha = exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                float ls = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) { p[r] = exp2f((sacc[r] - m_new) * scale_log2e); ls += p[r]; }
+                l_run = l_run * alpha + ls;
+                m_run = m_new;
             }
-            uint4 hi, lo;
-            pack8_split(v, hi, lo);
-            size_t vec = (size_t)t * KS * 64 + frag_vec(row, head * (HD / 8) + oct);
-            xhi[vec] = hi;
-            xlo[vec] = lo;
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+            uint4 ph[2], pl[2];
+            pack8_split(p, ph[0], pl[0]);
+            pack8_split(p + 8, ph[1], pl[1]);
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    oacc[tt] = mfma32(vf[tt][s2], ph[s2], oacc[tt]);
+                    oacc[tt] = mfma32(vf[tt][s2], pl[s2], oacc[tt]);
+                }
+        };
+        uint4 kfa[KSQ], vfa[HT][2], kfb[KSQ], vfb[HT][2];
+        if (kt0 < kt1) load_tile(kfa, vfa, kt0);
+        for (int kt = kt0; kt < kt1; kt += 2) {
+            load_tile(kfb, vfb, min(kt + 1, kt1 - 1));     // a repeated last tile is a cache hit and is not used
+            compute_tile(kfa, vfa, kt);
+            load_tile(kfa, vfa, min(kt + 2, kt1 - 1));
+            if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
         }
-        return;
-    }
-    {
-        const size_t pidx = (size_t)(t * Hq + head) * NS + split;
-        for (int e = threadIdx.x; e < 32 * HD / 2; e += 256) {
-            const int row = e / (HD / 2), dim = (e % (HD / 2)) * 2;
-            st_agent2(Opart + pidx * 32 * HD + row * HD + dim,
-                      s_f0[row] * sm_o[dim * 33 + row] + s_f1[row] * sm_o[(HD + dim) * 33 + row],
-                      s_f0[row] * sm_o[(dim + 1) * 33 + row] + s_f1[row] * sm_o[(HD + dim + 1) * 33 + row]);
+        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        if (NS == 1) {
+            attn_write_frag<HD>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
+        } else {
+            float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int r2 = 0; r2 < 8; ++r2)
+                    st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+            if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
         }
     }
-    // the block that arrives last at this (tile, head)'s counter merges the NS key ranges in order
-    if (!arrive_last(counters + t * Hq + head, NS, &s_last)) return;
-    float *wgt = sm_o;   // [NS][32] weights, NS <= 16
-    const size_t p0 = (size_t)(t * Hq + head) * NS;
-    if (threadIdx.x < 32) {
-        const int row = threadIdx.x;
+    if (NS == 1) return;
+
+    // the block that arrives last at this (tile, kv_head) counter merges the NS key ranges in order
+    if (!arrive_last(counters + t * Hkv + kvh, NS, &s_last)) return;
+    for (int g = w; g < G; g += 4) {
+        const int head = kvh * G + g;
+        const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
         float M = -INFINITY;
-        for (int s2 = 0; s2 < NS; ++s2) M = fmaxf(M, ld_agent2(MLpart + (p0 + s2) * 64 + 2 * row).x);
+        for (int s2 = 0; s2 < NS; ++s2) M = fmaxf(M, ld_agent2(p0 + (size_t)s2 * PF + 32 * HD + 2 * qrow).x);
+        f32x16 o[HT];
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[tt][r] = 0.f;
         float L = 0.f;
-        for (int s2 = 0; s2 < NS; ++s2) {
-            float2 ml = ld_agent2(MLpart + (p0 + s2) * 64 + 2 * row);
-            float f = (ml.x == -INFINITY) ? 0.f : exp2f((ml.x - M) * scale_log2e);
-            wgt[s2 * 32 + row] = f;
-            L += f * ml.y;
-        }
-        s_inv[row] = L > 0.f ? 1.f / L : 0.f;
-    }
-    __syncthreads();
-    for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
-        const int row = item & 31, oct = item >> 5;
-        float v[8];
+        for (int s2 = 0; s2 < NS; s2 += 2) {   // two splits per round: their loads are independent
+            const bool two = s2 + 1 < NS;
+            const float *pa = p0 + (size_t)s2 * PF;
+            const float *pb = p0 + (size_t)(two ? s2 + 1 : s2) * PF;
+            const float2 mla = ld_agent2(pa + 32 * HD + 2 * qrow), mlb = ld_agent2(pb + 32 * HD + 2 * qrow);
+            float2 va[HT][8], vb[HT][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = 0.f;
-        for (int s2 = 0; s2 < NS; ++s2) {
-            const float f = wgt[s2 * 32 + row];
-            const float *o = Opart + (p0 + s2) * 32 * HD + row * HD + oct * 8;
-            const float2 o0 = ld_agent2(o), o1 = ld_agent2(o + 2), o2 = ld_agent2(o + 4), o3 = ld_agent2(o + 6);
-            v[0] += f * o0.x; v[1] += f * o0.y; v[2] += f * o1.x; v[3] += f * o1.y;
-            v[4] += f * o2.x; v[5] += f * o2.y; v[6] += f * o3.x; v[7] += f * o3.y;
-        }
+            for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= s_inv[row];
-        uint4 hi, lo;
-        pack8_split(v, hi, lo);
-        size_t vec = (size_t)t * KS * 64 + frag_vec(row, head * (HD / 8) + oct);
-        xhi[vec] = hi;
-        xlo[vec] = lo;
+                for (int r2 = 0; r2 < 8; ++r2) {
+                    va[tt][r2] = ld_agent2(pa + ((tt * 8 + r2) * 64 + lane) * 2);
+                    vb[tt][r2] = ld_agent2(pb + ((tt * 8 + r2) * 64 + lane) * 2);
+                }
+            const float fa = (mla.x == -INFINITY) ? 0.f : exp2f((mla.x - M) * scale_log2e);
+            const float fb = (!two || mlb.x == -INFINITY) ? 0.f : exp2f((mlb.x - M) * scale_log2e);
+            L = (L + fa * mla.y) + fb * mlb.y;
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int r2 = 0; r2 < 8; ++r2) {
+                    o[tt][2 * r2] = (o[tt][2 * r2] + fa * va[tt][r2].x) + fb * vb[tt][r2].x;
+                    o[tt][2 * r2 + 1] = (o[tt][2 * r2 + 1] + fa * va[tt][r2].y) + fb * vb[tt][r2].y;
+                }
+        }
+        attn_write_frag<HD>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo);
     }
 }
 
