@@ -265,8 +265,13 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     (void)G;
     hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                        m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart,
-                       mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.attn_cnt, w.xb_hi, w.xb_lo);
+                       mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.xb_hi, w.xb_lo);
     LAUNCHCHK(c, "k_attn");
+    if (NS > 1) {
+        hipLaunchKernelGGL(k_attn_merge<HD>, dim3(mc.n_q_heads, ntiles), dim3(256), 0, c->stream, w.opart, NS, mc.n_q_heads,
+                           scale_log2e, w.xb_hi, w.xb_lo);
+        LAUNCHCHK(c, "k_attn_merge");
+    }
     return DEER_OK;
 }
 
@@ -287,7 +292,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     }
     const int nkt = (max_limit + 31) / 32;
     // key-range splits: aim at ~256 blocks; ntiles * NS never exceeds the partial buffer (max(64, tiles))
-    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 128;
+    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
     NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));

@@ -30,12 +30,19 @@ constexpr int RED_STRIDE = 136;  // padded LDS row stride (floats) of a 32x128 t
 // ------------------------------------------------------------------------------------------
 // small helpers
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t f2bf(float f) {  // round to nearest even; finite inputs
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+
+// fp32 -> bf16, round to nearest even (the hardware conversion)
+__device__ __forceinline__ uint32_t f2bf(float f) {
+    return (uint32_t)__builtin_bit_cast(unsigned short, (__bf16)f);
 }
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+// two floats -> packed bf16 pair (a in the low half)
+__device__ __forceinline__ uint32_t f2bf2(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
 // x ~= hi + lo, both bf16
 __device__ __forceinline__ void split_bf(float x, uint32_t &hi, uint32_t &lo) {
@@ -43,12 +50,19 @@ __device__ __forceinline__ void split_bf(float x, uint32_t &hi, uint32_t &lo) {
     lo = f2bf(x - bf2f(hi));
 }
 
+__device__ __forceinline__ uint4 pack8(const float *v) {
+    return make_uint4(f2bf2(v[0], v[1]), f2bf2(v[2], v[3]), f2bf2(v[4], v[5]), f2bf2(v[6], v[7]));
+}
+
 __device__ __forceinline__ void pack8_split(const float *v, uint4 &hi, uint4 &lo) {
-    uint32_t h[8], l[8];
+    uint32_t h[4], l[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split_bf(v[e], h[e], l[e]);
-    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    for (int e = 0; e < 4; ++e) {
+        h[e] = f2bf2(v[2 * e], v[2 * e + 1]);
+        l[e] = f2bf2(v[2 * e] - __uint_as_float(h[e] << 16), v[2 * e + 1] - __uint_as_float(h[e] & 0xffff0000u));
+    }
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
@@ -58,6 +72,20 @@ __device__ __forceinline__ f32x16 mfma32(uint4 a, uint4 b, f32x16 c) {
 __device__ __forceinline__ f32x16 mfma32(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
+
+__device__ __forceinline__ f32x16 mfma32(u32x4 a, uint4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Hand-scheduled loads (used where the compiler's wait-count insertion would drain every outstanding
+// load at a loop header): the load is issued here and its result may only be read after wait_loads<N>()
+// (at most N younger loads still outstanding; loads return in order) followed by tie() on the register.
+__device__ __forceinline__ void load16_async(u32x4 &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void tie(u32x4 &r) { asm volatile("" : "+v"(r)); }
 
 // Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
 __device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
@@ -356,16 +384,12 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
         } else {
             const int slot = a.rm.slot[grow];
             if (slot >= 0) {
-                uint32_t u[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) u[e] = f2bf(v[e]);
                 size_t base = (size_t)b * a.kv.seq_stride + (size_t)head * a.kv.head_stride;
                 if (kind == 1) {
-                    *(uint4 *)(a.kv.k + base + (size_t)slot * hd + i0) =
-                        make_uint4(u[0] | (u[1] << 16), u[2] | (u[3] << 16), u[4] | (u[5] << 16), u[6] | (u[7] << 16));
+                    *(uint4 *)(a.kv.k + base + (size_t)slot * hd + i0) = pack8(v);
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) a.kv.vt[base + (size_t)(i0 + e) * a.kv.max_seq + slot] = (uint16_t)u[e];
+                    for (int e = 0; e < 8; ++e) a.kv.vt[base + (size_t)(i0 + e) * a.kv.max_seq + slot] = (uint16_t)f2bf(v[e]);
                 }
             }
         }
@@ -694,9 +718,10 @@ __global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, i
 //   the softmax row of a lane is its own column.  Key order inside a 32-key tile is permuted
 //   (operand row rho holds key 16*((rho/4)%2) + 4*(rho/8) + rho%4) so that a lane's 16 scores are
 //   16 consecutive keys.  Q and P enter as (hi, lo) bf16 pairs.
-//   Each (tile, head, split) leaves an un-normalised partial (M, L, O) in the MFMA register layout;
-//   the block that arrives last at the (tile, kv_head) counter merges the splits in order and
-//   writes the O-projection's input fragments.
+//   With one key range (NS == 1) the result goes straight to the O-projection's input fragments;
+//   otherwise each (tile, head, split) leaves an un-normalised partial (M, L, O) in the MFMA register
+//   layout and k_attn_merge combines them (a merge inside this kernel would serialise NS dependent
+//   round trips to memory on one block).
 // ------------------------------------------------------------------------------------------
 template <int HD>
 struct AttnPartial {   // per (tile, head, split): O in register layout [HD/32][8 reg pairs][64 lanes][2], then (M, L)[32]
@@ -706,19 +731,23 @@ struct AttnPartial {   // per (tile, head, split): O in register layout [HD/32][
 
 template <int HD>
 __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int t, int head, int Hq, int lane,
-                                                uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+                                                uint4 *__restrict__ xhi, uint4 *__restrict__ xlo, int tt0 = 0,
+                                                int ntt = HD / 32) {
+    // o[i] holds O^T tile tt0 + i
     // lane (qrow, half) holds dims 32*tt + 8*q + 4*half + 0..3 in regs 4q..4q+3; the partner lane (other
     // half) holds the other 4 dims of the octet.  Half 0 writes octets with even q, half 1 odd q.
     const int half = lane >> 5, qrow = lane & 31;
     const int KS = Hq * HD / 16;
 #pragma unroll
-    for (int tt = 0; tt < HD / 32; ++tt) {
+    for (int ti = 0; ti < HD / 32; ++ti) {
+        if (ti >= ntt) break;
+        const int tt = tt0 + ti;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             float mine[4], other[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                mine[e] = o[tt][4 * q + e] * inv;
+                mine[e] = o[ti][4 * q + e] * inv;
                 other[e] = __shfl_xor(mine[e], 32);
             }
             // octet (tt, q): dims 32*tt + 8*q + 0..7 = half-0 lane's 4 values then half-1 lane's 4 values
@@ -742,12 +771,10 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
                                               size_t seq_stride, size_t head_stride, int max_seq,
                                               const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
                                               float *__restrict__ part, int Hq, int Hkv, int NS, float scale_log2e,
-                                              int *__restrict__ counters, uint4 *__restrict__ xhi,
-                                              uint4 *__restrict__ xlo) {
+                                              uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
     constexpr int KSQ = HD / 16;   // k-steps of the score contraction
     constexpr int HT = HD / 32;    // 32-row tiles of O^T
     constexpr int PF = AttnPartial<HD>::FLOATS;
-    __shared__ int s_last;
     const int G = Hq / Hkv;
     const int kvh = blockIdx.x % Hkv;
     const int split = blockIdx.x / Hkv;
@@ -755,9 +782,12 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, qrow = lane & 31;
     const int b = tile_seq[t];
     const int lim = row_limit[t * 32 + qrow];
-    int maxlim = lim;
+    int maxlim = lim, minlim = lim;
 #pragma unroll
-    for (int off = 1; off < 32; off <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, off));
+    for (int off = 1; off < 32; off <<= 1) {
+        maxlim = max(maxlim, __shfl_xor(maxlim, off));
+        minlim = min(minlim, __shfl_xor(minlim, off));
+    }
     const int nkt = (maxlim + 31) >> 5;
     const int per = (nkt + NS - 1) / NS;
     const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
@@ -781,18 +811,23 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
         float m_run = -INFINITY, l_run = 0.f;
 
         // K and V fragments of a 32-key tile are requested together, one tile ahead of their use
-        auto load_tile = [&](uint4 (&kf)[KSQ], uint4 (&vf)[HT][2], int kt) {
+        auto load_tile = [&](u32x4 (&kf)[KSQ], u32x4 (&vf)[HT][2], int kt) {
             const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) kf[s] = *(const uint4 *)(kp + s * 16);
+            for (int s = 0; s < KSQ; ++s) load16_async(kf[s], kp + s * 16);
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt) {
                 const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
-                vf[tt][0] = *(const uint4 *)(vp);
-                vf[tt][1] = *(const uint4 *)(vp + 8);
+                load16_async(vf[tt][0], vp);
+                load16_async(vf[tt][1], vp + 8);
             }
         };
-        auto compute_tile = [&](const uint4 (&kf)[KSQ], const uint4 (&vf)[HT][2], int kt) {
+        auto compute_tile = [&](u32x4 (&kf)[KSQ], u32x4 (&vf)[HT][2], int kt) {
+            // the caller has waited for this tile's loads; tie its registers to that wait
+#pragma unroll
+            for (int s = 0; s < KSQ; ++s) tie(kf[s]);
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt) { tie(vf[tt][0]); tie(vf[tt][1]); }
             f32x16 sacc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
@@ -803,31 +838,36 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
             }
             // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
             const int key0 = kt * 32 + 16 * half;
-            float mx = -INFINITY;
+            if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (key0 + r >= lim) sacc[r] = -INFINITY;
-                mx = fmaxf(mx, sacc[r]);
+                for (int r = 0; r < 16; ++r)
+                    if (key0 + r >= lim) sacc[r] = -INFINITY;
             }
+            float mx = sacc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float m_new = fmaxf(m_run, mx);
             float p[16];
-            float alpha = 1.f;
             if (m_new == -INFINITY) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) p[r] = 0.f;
             } else {
-                alpha = exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                const float mb = m_new * scale_log2e;
                 float ls = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { p[r] = exp2f((sacc[r] - m_new) * scale_log2e); ls += p[r]; }
+                for (int r = 0; r < 16; ++r) { p[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += p[r]; }
                 l_run = l_run * alpha + ls;
                 m_run = m_new;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+#pragma unroll
+                    for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+                }
             }
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+            // P enters the second contraction as a (hi, lo) bf16 pair like every other activation
             uint4 ph[2], pl[2];
             pack8_split(p, ph[0], pl[0]);
             pack8_split(p + 8, ph[1], pl[1]);
@@ -839,13 +879,44 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
                     oacc[tt] = mfma32(vf[tt][s2], pl[s2], oacc[tt]);
                 }
         };
-        uint4 kfa[KSQ], vfa[HT][2], kfb[KSQ], vfb[HT][2];
-        if (kt0 < kt1) load_tile(kfa, vfa, kt0);
-        for (int kt = kt0; kt < kt1; kt += 2) {
-            load_tile(kfb, vfb, min(kt + 1, kt1 - 1));     // a repeated last tile is a cache hit and is not used
-            compute_tile(kfa, vfa, kt);
-            load_tile(kfa, vfa, min(kt + 2, kt1 - 1));
-            if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
+        // tile buffers: loads of later tiles stay in flight behind the one being multiplied (two tiles
+        // ahead for head_dim <= 64, one tile ahead for head_dim 128, bounded by the register file)
+        constexpr int LPT = KSQ + 2 * HT;   // loads per tile
+        if (kt0 < kt1) {
+            const int last = kt1 - 1;       // a repeated last tile is a cache hit and is not used
+            u32x4 kfa[KSQ], vfa[HT][2], kfb[KSQ], vfb[HT][2];
+            if constexpr (HD <= 64) {
+                u32x4 kfc[KSQ], vfc[HT][2];
+                load_tile(kfa, vfa, kt0);
+                load_tile(kfb, vfb, min(kt0 + 1, last));
+                for (int kt = kt0; kt < kt1; kt += 3) {
+                    load_tile(kfc, vfc, min(kt + 2, last));
+                    wait_loads<2 * LPT>();
+                    compute_tile(kfa, vfa, kt);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_tile(kfa, vfa, min(kt + 3, last));
+                    wait_loads<2 * LPT>();
+                    if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_tile(kfb, vfb, min(kt + 4, last));
+                    wait_loads<2 * LPT>();
+                    if (kt + 2 < kt1) compute_tile(kfc, vfc, kt + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                load_tile(kfa, vfa, kt0);
+                for (int kt = kt0; kt < kt1; kt += 2) {
+                    load_tile(kfb, vfb, min(kt + 1, last));
+                    wait_loads<LPT>();
+                    compute_tile(kfa, vfa, kt);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_tile(kfa, vfa, min(kt + 2, last));
+                    wait_loads<LPT>();
+                    if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            wait_loads<0>();
         }
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         if (NS == 1) {
@@ -856,51 +927,52 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
             for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
                 for (int r2 = 0; r2 < 8; ++r2)
-                    st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-            if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
+                    *(float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2) = make_float2(oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+            if (half == 0) *(float2 *)(pp + 32 * HD + 2 * qrow) = make_float2(m_run, l_tot);
         }
     }
-    if (NS == 1) return;
+}
 
-    // the block that arrives last at this (tile, kv_head) counter merges the NS key ranges in order
-    if (!arrive_last(counters + t * Hkv + kvh, NS, &s_last)) return;
-    for (int g = w; g < G; g += 4) {
-        const int head = kvh * G + g;
-        const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
-        float M = -INFINITY;
-        for (int s2 = 0; s2 < NS; ++s2) M = fmaxf(M, ld_agent2(p0 + (size_t)s2 * PF + 32 * HD + 2 * qrow).x);
-        f32x16 o[HT];
+// Merges the NS key-range partials of block attention in order s = 0..NS-1, normalises, and writes the
+// O-projection's input fragments.  grid: x = query head, y = pass tile; wave w merges O^T tile tt = w.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part, int NS, int Hq, float scale_log2e,
+                                                    uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    const int head = blockIdx.x, t = blockIdx.y;
+    const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, qrow = lane & 31;
+    if (tt >= HD / 32) return;
+    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
+    float M = -INFINITY;
+    for (int s0 = 0; s0 < NS; s0 += 8) {
+        float mv[8];
 #pragma unroll
-        for (int tt = 0; tt < HT; ++tt)
+        for (int u = 0; u < 8; ++u) mv[u] = p0[(size_t)min(s0 + u, NS - 1) * PF + 32 * HD + 2 * qrow];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[tt][r] = 0.f;
-        float L = 0.f;
-        for (int s2 = 0; s2 < NS; s2 += 2) {   // two splits per round: their loads are independent
-            const bool two = s2 + 1 < NS;
-            const float *pa = p0 + (size_t)s2 * PF;
-            const float *pb = p0 + (size_t)(two ? s2 + 1 : s2) * PF;
-            const float2 mla = ld_agent2(pa + 32 * HD + 2 * qrow), mlb = ld_agent2(pb + 32 * HD + 2 * qrow);
-            float2 va[HT][8], vb[HT][8];
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2) {
-                    va[tt][r2] = ld_agent2(pa + ((tt * 8 + r2) * 64 + lane) * 2);
-                    vb[tt][r2] = ld_agent2(pb + ((tt * 8 + r2) * 64 + lane) * 2);
-                }
-            const float fa = (mla.x == -INFINITY) ? 0.f : exp2f((mla.x - M) * scale_log2e);
-            const float fb = (!two || mlb.x == -INFINITY) ? 0.f : exp2f((mlb.x - M) * scale_log2e);
-            L = (L + fa * mla.y) + fb * mlb.y;
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2) {
-                    o[tt][2 * r2] = (o[tt][2 * r2] + fa * va[tt][r2].x) + fb * vb[tt][r2].x;
-                    o[tt][2 * r2 + 1] = (o[tt][2 * r2 + 1] + fa * va[tt][r2].y) + fb * vb[tt][r2].y;
-                }
-        }
-        attn_write_frag<HD>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo);
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mv[u]);
     }
+    f32x16 o[1];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[0][r] = 0.f;
+    float L = 0.f;
+    for (int s0 = 0; s0 < NS; s0 += 8) {   // eight splits per round: their loads are independent
+        float2 v[8][8], ml[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float *pp = p0 + (size_t)min(s0 + u, NS - 1) * PF;
+            ml[u] = *(const float2 *)(pp + 32 * HD + 2 * qrow);
+#pragma unroll
+            for (int r2 = 0; r2 < 8; ++r2) v[u][r2] = *(const float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float f = (s0 + u >= NS || ml[u].x == -INFINITY) ? 0.f : exp2f((ml[u].x - M) * scale_log2e);
+            L += f * ml[u].y;
+#pragma unroll
+            for (int r2 = 0; r2 < 8; ++r2) { o[0][2 * r2] += f * v[u][r2].x; o[0][2 * r2 + 1] += f * v[u][r2].y; }
+        }
+    }
+    attn_write_frag<HD>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo, tt, 1);
 }
 
 // ------------------------------------------------------------------------------------------
