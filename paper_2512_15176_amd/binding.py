@@ -183,8 +183,13 @@ class DeerEngine:
         self.load_tensor(model, "embed", -1, -1, provider("embed", -1, -1))
         self.load_tensor(model, "lm_head", -1, -1, provider("lm_head", -1, -1))
         for l in range(shape.n_layers):
-            for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+            for name in ("wq", "wk", "wv", "wo"):
                 self.load_tensor(model, name, l, -1, provider(name, l, -1))
+            if shape.n_experts:
+                self.load_tensor(model, "router", l, -1, provider("router", l, -1))
+            for e in (range(shape.n_experts) if shape.n_experts else [-1]):
+                for name in ("wg", "wu", "wd"):
+                    self.load_tensor(model, name, l, e, provider(name, l, e))
 
     # -- the path --------------------------------------------------------------------------------
     def prefill(self, prompts):

@@ -31,7 +31,8 @@ struct ModelRT {
     // weights (device)
     char *w = nullptr;
     size_t off_embed = 0, off_lm = 0, off_layers = 0, layer_bytes = 0;
-    size_t lo_qkv = 0, lo_o = 0, lo_gu = 0, lo_d = 0;   // offsets inside a layer
+    size_t lo_qkv = 0, lo_o = 0, lo_gu = 0, lo_d = 0;   // offsets inside a layer (gu/d: expert 0 for a mixture)
+    size_t lo_router = 0, exp_gu_bytes = 0, exp_d_bytes = 0;   // mixture: router, per-expert matrix sizes
     size_t weight_bytes = 0;
     // kv (device, elements of bf16)
     uint16_t *kv = nullptr;
@@ -52,6 +53,10 @@ struct Work {   // carved from the workspace
     RowResult *res[2] = {nullptr, nullptr};
     AcceptOut ao{};
     int *ids = nullptr;                // prompt staging [max_seq]
+    // mixture-of-experts routing and staging (target only)
+    int *route_e = nullptr, *exp_cnt = nullptr, *pair_row = nullptr, *pair_slot = nullptr;
+    float *route_w = nullptr, *moe_out = nullptr;
+    uint4 *act_hi = nullptr, *act_lo = nullptr;
     int *gemm_cnt = nullptr, *attn_cnt = nullptr;   // arrival counters, zero between kernels
     size_t cnt_bytes = 0; char *cnt_base = nullptr;
     double *theta[2] = {nullptr, nullptr};
@@ -139,8 +144,10 @@ const char *check_model(const deer_model_cfg &c) {
     if (((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim) % CG) return "fused QKV width must be a multiple of 128";
     if ((c.n_q_heads * c.head_dim) % 16) return "n_q_heads*head_dim must be a multiple of 16";
     if (c.vocab % CG) return "vocab must be a multiple of 128";
-    if (c.n_experts) return "mixture-of-experts targets are not built yet";
-    if (c.d_ff < 64 || c.d_ff % 64) return "d_ff must be a multiple of 64";
+    if (c.n_experts) {
+        if (c.n_experts > 128 || c.top_k < 1 || c.top_k > 8 || c.top_k > c.n_experts) return "mixture needs n_experts <= 128 and 1 <= top_k <= 8";
+        if (c.d_ff_expert < 64 || c.d_ff_expert % 64) return "d_ff_expert must be a multiple of 64";
+    } else if (c.d_ff < 64 || c.d_ff % 64) return "d_ff must be a multiple of 64";
     if (!(c.rope_base > 1.f) || !(c.rms_eps >= 0.f)) return "bad rope_base / rms_eps";
     return nullptr;
 }
@@ -149,16 +156,20 @@ void plan_model(ModelRT &m, const deer_model_cfg &c, int max_batch, int max_seq)
     m.c = c;
     m.n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     m.kattn = c.n_q_heads * c.head_dim;
-    m.F = c.d_ff;
+    m.F = c.n_experts ? c.d_ff_expert : c.d_ff;
     size_t d = c.d_model;
     m.off_embed = 0;
     m.off_lm = align_up((size_t)c.vocab * d * 2);
     m.off_layers = m.off_lm + align_up(d * (size_t)c.vocab * 2);
     m.lo_qkv = 0;
     m.lo_o = m.lo_qkv + align_up(d * m.n_qkv * 2);
-    m.lo_gu = m.lo_o + align_up((size_t)m.kattn * d * 2);
-    m.lo_d = m.lo_gu + align_up(d * 2 * m.F * 2);
-    m.layer_bytes = m.lo_d + align_up((size_t)m.F * d * 2);
+    m.lo_router = m.lo_o + align_up((size_t)m.kattn * d * 2);
+    m.lo_gu = m.lo_router + (c.n_experts ? align_up(d * CG * 2) : 0);
+    m.exp_gu_bytes = align_up(d * 2 * m.F * 2);
+    m.exp_d_bytes = align_up((size_t)m.F * d * 2);
+    const size_t ne = c.n_experts ? c.n_experts : 1;
+    m.lo_d = m.lo_gu + m.exp_gu_bytes * ne;
+    m.layer_bytes = m.lo_d + m.exp_d_bytes * ne;
     m.weight_bytes = m.off_layers + m.layer_bytes * c.n_layers;
     m.kv_head_stride = (size_t)max_seq * c.head_dim;
     m.kv_seq_stride = m.kv_head_stride * c.n_kv_heads;
@@ -175,7 +186,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     const deer_model_cfg &t = p.target, &d = p.drafter;
     const size_t dmax = std::max(t.d_model, d.d_model);
     const size_t kattn = std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
-    const size_t fmax = std::max(t.d_ff, d.d_ff);
+    const size_t fmax = std::max(t.n_experts ? t.d_ff_expert : t.d_ff, d.n_experts ? d.d_ff_expert : d.d_ff);
     const size_t kb = std::max(kattn, fmax);
     const size_t hq = std::max(t.n_q_heads, d.n_q_heads);
     const size_t hdmax = std::max(t.head_dim, d.head_dim);
@@ -201,6 +212,15 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
     w.ao.accept_len = (int *)take(B * 4); w.ao.n_committed = (int *)take(B * 4); w.ao.committed = (int *)take((size_t)B * 32 * 4);
     w.ids = (int *)take((size_t)p.max_seq * 4);
+    for (const deer_model_cfg *mc : {&t, &d}) {
+        if (!mc->n_experts || w.route_e) continue;
+        const size_t chunks = MAXT;   // 32-pair chunks per expert: at most every row of the pass
+        w.route_e = (int *)take((size_t)MAXR * 8 * 4); w.route_w = (float *)take((size_t)MAXR * 8 * 4);
+        w.exp_cnt = (int *)take(128 * 4);
+        w.pair_row = (int *)take((size_t)128 * MAXR * 4); w.pair_slot = (int *)take((size_t)128 * MAXR * 4);
+        w.moe_out = (float *)take((size_t)MAXR * 8 * dmax * 4);
+        w.act_hi = (uint4 *)take((size_t)128 * chunks * (fmax / 16) * 1024); w.act_lo = (uint4 *)take((size_t)128 * chunks * (fmax / 16) * 1024);
+    }
     {
         const size_t ng = (size_t)(std::max(std::max(t.d_model, d.d_model), 4 * (int)fmax) / CG + 64) * MAXT, na = (size_t)MAXT * hq;
         w.cnt_base = take((ng + na) * 4);
@@ -320,14 +340,48 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         a.W = (const uint4 *)(lw + m.lo_o); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
         rc = launch_gemm<EPI_RESID>(c, a, m.kattn, ntiles, 0);
         if (rc) return rc;
-        a = base;
-        a.W = (const uint4 *)(lw + m.lo_gu); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = 2 * m.F;
-        rc = launch_gemm<EPI_SWIGLU>(c, a, d, ntiles, 0);
-        if (rc) return rc;
-        a = base;
-        a.W = (const uint4 *)(lw + m.lo_d); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
-        rc = launch_gemm<EPI_RESID>(c, a, m.F, ntiles, 0);
-        if (rc) return rc;
+        if (!mc.n_experts) {
+            a = base;
+            a.W = (const uint4 *)(lw + m.lo_gu); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = 2 * m.F;
+            rc = launch_gemm<EPI_SWIGLU>(c, a, d, ntiles, 0);
+            if (rc) return rc;
+            a = base;
+            a.W = (const uint4 *)(lw + m.lo_d); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
+            rc = launch_gemm<EPI_RESID>(c, a, m.F, ntiles, 0);
+            if (rc) return rc;
+        } else {
+            // router -> per-expert grouping -> grouped gate/up and down GEMMs -> ordered combine
+            a = base;
+            a.W = (const uint4 *)(lw + m.lo_router); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = CG;
+            a.n_experts = mc.n_experts; a.top_k = mc.top_k; a.route_e = w.route_e; a.route_w = w.route_w;
+            rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, 0);
+            if (rc) return rc;
+            const int cap = rows, chunks = ntiles;
+            hipLaunchKernelGGL(k_moe_group, dim3(1), dim3(256), 0, s, w.route_e, w.rm.slot, rows, mc.top_k, mc.n_experts, cap,
+                               w.exp_cnt, w.pair_row, w.pair_slot);
+            LAUNCHCHK(c, "k_moe_group");
+            MoeArgs ma{};
+            ma.cap = cap; ma.chunks = chunks; ma.cnt = w.exp_cnt; ma.pair_row = w.pair_row; ma.pair_slot = w.pair_slot;
+            ma.ssq_in = w.ssq; ma.ncg_in = ncg_d; ma.d_in = d; ma.eps = mc.rms_eps;
+            ma.ahi = w.act_hi; ma.alo = w.act_lo; ma.Fe = m.F; ma.route_w = w.route_w; ma.moe_out = w.moe_out; ma.d = d;
+            ma.W = (const uint4 *)(lw + m.lo_gu); ma.wexp_stride = m.exp_gu_bytes / 16; ma.Xhi = w.xa_hi; ma.Xlo = w.xa_lo;
+            ma.N = 2 * m.F; ma.KS = d / 16;
+            {
+                ProfScope ps(c, 0, 0.0);
+                hipLaunchKernelGGL(k_gemm_moe<MOE_GATEUP>, dim3(2 * m.F / CG, mc.n_experts, chunks), dim3(512), 0, s, ma);
+            }
+            LAUNCHCHK(c, "k_gemm_moe gate/up");
+            ma.W = (const uint4 *)(lw + m.lo_d); ma.wexp_stride = m.exp_d_bytes / 16; ma.Xhi = w.act_hi; ma.Xlo = w.act_lo;
+            ma.N = d; ma.KS = m.F / 16;
+            {
+                ProfScope ps(c, 0, 0.0);
+                hipLaunchKernelGGL(k_gemm_moe<MOE_DOWN>, dim3(d / CG, mc.n_experts, chunks), dim3(512), 0, s, ma);
+            }
+            LAUNCHCHK(c, "k_gemm_moe down");
+            hipLaunchKernelGGL(k_moe_combine, dim3(ncg_d, ntiles), dim3(256), 0, s, w.moe_out, w.rm.slot, mc.top_k, w.h, w.xa_hi,
+                               w.xa_lo, w.ssq, d);
+            LAUNCHCHK(c, "k_moe_combine");
+        }
     }
     if (lm.on) {
         const int V = mc.vocab;
@@ -436,14 +490,17 @@ int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int exper
     if (!c) return DEER_EINVAL;
     if (!src || model < 0 || model > 1 || (src_dtype != DEER_F32 && src_dtype != DEER_BF16))
         return fail(c, DEER_EINVAL, "bad model/dtype/pointer");
-    (void)expert;
     ModelRT &m = c->m[model];
     const deer_model_cfg &mc = m.c;
     const int d = mc.d_model, hd = mc.head_dim;
     int64_t er = 0, ec = 0;
     char *dst = nullptr;
     int mode = 0, col_off = 0, K = 0;
-    const bool per_layer = tensor_id >= DEER_T_WQ && tensor_id <= DEER_T_WD;
+    const bool per_layer = tensor_id >= DEER_T_WQ && tensor_id <= DEER_T_ROUTER;
+    const bool per_expert = mc.n_experts && (tensor_id == DEER_T_WG || tensor_id == DEER_T_WU || tensor_id == DEER_T_WD);
+    if (per_expert && (expert < 0 || expert >= mc.n_experts)) return fail(c, DEER_EINVAL, "expert out of range");
+    if (!per_expert && expert >= 0) return fail(c, DEER_EINVAL, "tensor %d takes no expert index", tensor_id);
+    const size_t ex = per_expert ? (size_t)expert : 0;
     if (per_layer && (layer < 0 || layer >= mc.n_layers)) return fail(c, DEER_EINVAL, "layer out of range");
     char *lw = m.w + m.off_layers + (size_t)(per_layer ? layer : 0) * m.layer_bytes;
     switch (tensor_id) {
@@ -453,9 +510,12 @@ int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int exper
         case DEER_T_WK: er = d; ec = mc.n_kv_heads * hd; dst = lw + m.lo_qkv; K = d; col_off = mc.n_q_heads * hd; break;
         case DEER_T_WV: er = d; ec = mc.n_kv_heads * hd; dst = lw + m.lo_qkv; K = d; col_off = (mc.n_q_heads + mc.n_kv_heads) * hd; break;
         case DEER_T_WO: er = m.kattn; ec = d; dst = lw + m.lo_o; K = m.kattn; break;
-        case DEER_T_WG: er = d; ec = m.F; dst = lw + m.lo_gu; K = d; mode = 1; break;
-        case DEER_T_WU: er = d; ec = m.F; dst = lw + m.lo_gu; K = d; mode = 2; break;
-        case DEER_T_WD: er = m.F; ec = d; dst = lw + m.lo_d; K = m.F; break;
+        case DEER_T_WG: er = d; ec = m.F; dst = lw + m.lo_gu + ex * m.exp_gu_bytes; K = d; mode = 1; break;
+        case DEER_T_WU: er = d; ec = m.F; dst = lw + m.lo_gu + ex * m.exp_gu_bytes; K = d; mode = 2; break;
+        case DEER_T_WD: er = m.F; ec = d; dst = lw + m.lo_d + ex * m.exp_d_bytes; K = m.F; break;
+        case DEER_T_ROUTER:
+            if (!mc.n_experts) return fail(c, DEER_EINVAL, "model has no router");
+            er = d; ec = mc.n_experts; dst = lw + m.lo_router; K = d; break;
         default: return fail(c, DEER_EINVAL, "unknown tensor id %d", tensor_id);
     }
     if (rows != er || cols != ec) return fail(c, DEER_EINVAL, "tensor %d: expected %lld x %lld, got %lld x %lld", tensor_id,

@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, c
 //   s = 0..S-1 and runs the epilogue, so results do not depend on arrival order.
 //   Tiles of the launch: tile(ct) = mt0 + ct * mt_stride, ct = z*MT + mt.
 // ------------------------------------------------------------------------------------------
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_ROUTER = 4 };
 
 struct KvView {
     uint16_t *k, *vt;                                  // layer base already applied
@@ -336,6 +336,8 @@ struct GemmArgs {
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
     int k; float *logits; float T; uint64_t seed; RowStat *stat; int ncg_v;
+    // ROUTER: top-k of softmax over n_experts (<= 128), renormalised
+    int n_experts, top_k; int *route_e; float *route_w;
 };
 
 // rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
@@ -492,6 +494,51 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
     }
 }
 
+// router epilogue: logits over the experts -> softmax -> top_k (lowest index on ties) -> weights
+// renormalised to sum 1.  8 threads per row, 16 experts each.
+__device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile, const float *rstd, int t) {
+    if (threadIdx.x >= 256) return;
+    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    const int grow = t * 32 + row;
+    float z[16];
+    float m = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const int ex = sub * 16 + e;
+        z[e] = ex < a.n_experts ? tile[row * RED_STRIDE + ex] * rstd[row] : -INFINITY;
+        m = fmaxf(m, z[e]);
+    }
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+    float se = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { z[e] = expf(z[e] - m); se += z[e]; }   // exp(-inf) = 0 for padding
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
+    float wsel[8]; int esel[8];
+    float wsum = 0.f;
+    for (int j = 0; j < a.top_k; ++j) {
+        float bv = -1.f; int bi = 0x7fffffff;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) argmax_merge(bv, bi, z[e], sub * 16 + e);
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) {
+            float v2 = __shfl_xor(bv, off); int i2 = __shfl_xor(bi, off);
+            argmax_merge(bv, bi, v2, i2);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) if (sub * 16 + e == bi) z[e] = -1.f;   // taken
+        wsel[j] = bv / se; esel[j] = bi;
+        wsum += wsel[j];
+    }
+    if (sub == 0) {
+        for (int j = 0; j < a.top_k; ++j) {
+            a.route_e[grow * 8 + j] = esel[j];
+            a.route_w[grow * 8 + j] = wsel[j] / wsum;
+        }
+    }
+}
+
 template <int EPI>
 __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, int cg, int ct) {
     // caller has synchronised after filling `tile`
@@ -503,6 +550,7 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, flo
     if (EPI == EPI_QKV) epi_qkv(a, tile, rstd, cg, t);
     else if (EPI == EPI_RESID) epi_resid(a, tile, cg, t);
     else if (EPI == EPI_SWIGLU) epi_swiglu(a, tile, rstd, cg, t);
+    else if (EPI == EPI_ROUTER) epi_router(a, tile, rstd, t);
     else epi_lmhead(a, tile, rstd, cg, ct, t);
 }
 
@@ -647,6 +695,206 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
         }
         __syncthreads();
         run_epilogue<EPI>(a, tile, s_rstd, cg, ct);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// mixture-of-experts FFN: (row, expert) pairs are grouped per expert, every touched expert's weights
+// are streamed once, and the 8 weighted expert outputs of a row are summed in routing order.
+// ------------------------------------------------------------------------------------------
+// one block: cnt[e], and for pair i of expert e the pass row and its routing slot
+__global__ __launch_bounds__(256) void k_moe_group(const int *__restrict__ route_e, const int *__restrict__ row_slot,
+                                                   int rows, int top_k, int n_experts, int cap, int *__restrict__ cnt,
+                                                   int *__restrict__ pair_row, int *__restrict__ pair_slot) {
+    __shared__ int s_cnt[128];
+    if (threadIdx.x < 128) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
+    for (int p = threadIdx.x; p < rows * top_k; p += 256) {
+        const int row = p / top_k, j = p % top_k;
+        if (row_slot[row] < 0) continue;                 // unused rows of a tile route nowhere
+        const int e = route_e[row * 8 + j];
+        const int i = atomicAdd(&s_cnt[e], 1);           // order inside an expert does not affect results
+        pair_row[e * cap + i] = row;
+        pair_slot[e * cap + i] = j;
+    }
+    __syncthreads();
+    if (threadIdx.x < n_experts) cnt[threadIdx.x] = s_cnt[threadIdx.x];
+}
+
+enum { MOE_GATEUP = 0, MOE_DOWN = 1 };
+
+struct MoeArgs {
+    const uint4 *W; size_t wexp_stride;      // expert e's matrix at W + e * wexp_stride (16-byte units)
+    const uint4 *Xhi, *Xlo;                  // GATEUP: the pass's fragments of h; DOWN: activation tiles
+    int N, KS, cap, chunks;
+    const int *cnt, *pair_row, *pair_slot;
+    const float *ssq_in; int ncg_in, d_in; float eps;   // GATEUP: RMSNorm scale of each pair's row
+    uint4 *ahi, *alo; int Fe;                // GATEUP out: activation tile (e*chunks + chunk), Fe/16 k-steps
+    const float *route_w; float *moe_out; int d;        // DOWN out: moe_out[row][slot][d] = w * y
+};
+
+// grid: x = column group, y = expert, z = chunk of 32 pairs.  Same streaming loop and wave tree as k_gemm.
+template <int MODE>
+__global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
+    __shared__ float red[4 * 32 * 128];
+    __shared__ float s_rstd[32];
+    __shared__ int s_row[32], s_slot[32];
+    float *tile = red + 32 * 128;
+    const int cg = blockIdx.x, ex = blockIdx.y, chunk = blockIdx.z;
+    const int n = a.cnt[ex] - chunk * 32;
+    if (n <= 0) return;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, cl = lane & 31;
+    const int KS = a.KS;
+    if (threadIdx.x < 32) {
+        const bool v = threadIdx.x < n;
+        s_row[threadIdx.x] = v ? a.pair_row[ex * a.cap + chunk * 32 + threadIdx.x] : -1;
+        s_slot[threadIdx.x] = v ? a.pair_slot[ex * a.cap + chunk * 32 + threadIdx.x] : 0;
+    }
+    __syncthreads();
+    const int myrow = s_row[cl];
+    const int per = (KS + 7) / 8;
+    const int ks0 = w * per, ks1 = min(KS, ks0 + per);
+    f32x16 acc[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+    const uint4 *wp = a.W + (size_t)ex * a.wexp_stride + ((size_t)(cg * 4) * KS) * 64 + lane;
+    const size_t wstride = (size_t)KS * 64;
+    // activation fragment of this lane: GATEUP gathers the pair's own row out of the pass's tiles
+    const uint4 *xh, *xl;
+    if (MODE == MOE_GATEUP) {
+        const int r = myrow < 0 ? 0 : myrow;
+        const size_t off = ((size_t)(r >> 5) * KS) * 64 + (r & 31) + 32 * half;
+        xh = a.Xhi + off; xl = a.Xlo + off;
+    } else {
+        const size_t off = ((size_t)(ex * a.chunks + chunk) * KS) * 64 + lane;
+        xh = a.Xhi + off; xl = a.Xlo + off;
+    }
+    const bool live = myrow >= 0;
+    const uint4 z4 = make_uint4(0u, 0u, 0u, 0u);
+    constexpr int D = 4;
+    uint4 wb[D][4], xhb[D], xlb[D];
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd) {
+        int ks = ks0 + dd;
+        if (ks < ks1) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+            xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
+        }
+    }
+    for (int kb = ks0; kb < ks1; kb += D) {
+#pragma unroll
+        for (int dd = 0; dd < D; ++dd) {
+            int ks = kb + dd;
+            if (ks < ks1) {
+                const uint4 ah = live ? xhb[dd] : z4, al = live ? xlb[dd] : z4;
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    acc[nb] = mfma32(ah, wb[dd][nb], acc[nb]);
+                    acc[nb] = mfma32(al, wb[dd][nb], acc[nb]);
+                }
+                int kn = ks + D;
+                if (kn < ks1) {
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+                    xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int round = 0; round < 3; ++round) {
+        const int hi_lo = 4 >> round;
+        if (w >= hi_lo && w < 2 * hi_lo) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) red[((w - hi_lo) * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl] = acc[nb][r];
+        }
+        __syncthreads();
+        if (w < hi_lo) {
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[nb][r] += red[(w * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl];
+        }
+        __syncthreads();
+    }
+    if (w == 0) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tile[mfma_row(r, half) * RED_STRIDE + nb * 32 + cl] = acc[nb][r];
+    }
+    if (MODE == MOE_GATEUP && threadIdx.x < 32) {
+        float sc = 0.f;
+        const int r = s_row[threadIdx.x];
+        if (r >= 0) {
+            const float *p = a.ssq_in + (size_t)r * a.ncg_in;
+            float ss = 0.f;
+            for (int g = 0; g < a.ncg_in; ++g) ss += p[g];
+            sc = rsqrtf(ss / (float)a.d_in + a.eps);
+        }
+        s_rstd[threadIdx.x] = sc;
+    }
+    __syncthreads();
+    if (MODE == MOE_GATEUP) {
+        for (int item = threadIdx.x; item < 256; item += blockDim.x) {
+            const int row = item & 31, oct = item >> 5;
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float g = tile[row * RED_STRIDE + oct * 8 + e] * s_rstd[row];
+                float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * s_rstd[row];
+                v[e] = g / (1.f + expf(-g)) * u;
+            }
+            uint4 hi, lo;
+            pack8_split(v, hi, lo);
+            size_t vec = (size_t)(ex * a.chunks + chunk) * (a.Fe / 16) * 64 + frag_vec(row, cg * 8 + oct);
+            a.ahi[vec] = hi;
+            a.alo[vec] = lo;
+        }
+    } else {
+        for (int e = threadIdx.x; e < 32 * 32; e += blockDim.x) {
+            const int row = e >> 5, c4 = (e & 31) * 4;
+            const int pr = s_row[row];
+            if (pr < 0) continue;
+            const int slot = s_slot[row];
+            const float wgt = a.route_w[pr * 8 + slot];
+            const float *tp = tile + row * RED_STRIDE + c4;
+            *(float4 *)(a.moe_out + ((size_t)pr * 8 + slot) * a.d + cg * CG + c4) =
+                make_float4(tp[0] * wgt, tp[1] * wgt, tp[2] * wgt, tp[3] * wgt);
+        }
+    }
+}
+
+// h += sum over the row's experts in routing order; new fragment planes and sums of squares of h
+__global__ __launch_bounds__(256) void k_moe_combine(const float *__restrict__ moe_out, const int *__restrict__ row_slot,
+                                                     int top_k, float *__restrict__ h, uint4 *__restrict__ xhi,
+                                                     uint4 *__restrict__ xlo, float *__restrict__ ssq, int d) {
+    __shared__ float tile[32 * RED_STRIDE];
+    const int cg = blockIdx.x, t = blockIdx.y, ncg = gridDim.x;
+    for (int e = threadIdx.x; e < 32 * CG; e += 256) {
+        const int row = e >> 7, col = e & 127;
+        const int grow = t * 32 + row;
+        const size_t gi = (size_t)grow * d + cg * CG + col;
+        float v = h[gi];
+        if (row_slot[grow] >= 0) {
+            float add = 0.f;
+            for (int j = 0; j < top_k; ++j) add += moe_out[((size_t)grow * 8 + j) * d + cg * CG + col];
+            v += add;
+        }
+        h[gi] = v;
+        tile[row * RED_STRIDE + col] = v;
+    }
+    __syncthreads();
+    tile_to_frag(tile, xhi, xlo, (size_t)t * (d / 16) * 64, cg * CG);
+    if (threadIdx.x < 32) {
+        float s = 0.f;
+        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
+        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
     }
 }
 

@@ -1,0 +1,55 @@
+"""GPU parity for a mixture-of-experts target (softmax router, top-k of E, renormalised weights,
+grouped expert GEMMs): a small mixture, and one layer at the 30B-A3B layer widths with all 128 experts."""
+import numpy as np
+import pytest
+
+import deer_inputs as di
+from oracle import deer_oracle as O
+from gpu_common import StoredWeights, gpu_available, make_engine, make_pair, top2_margin
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
+
+CASES = {
+    "small_mixture": dict(
+        target=di.ModelShape(2, 256, 4, 2, 64, 0, 1024, n_experts=16, top_k=4, d_ff_expert=128, rope_base=1e4),
+        drafter=di.CONFIGS["tiny"]["drafter"], prefix=45, k=8, forced=[8, 0, 3], tol=2e-3),
+    "a3b_layer_widths": dict(
+        target=di.scaled(di.CONFIGS["qwen3_30b_a3b"]["target"], n_layers=1, vocab=4096),
+        drafter=di.scaled(di.DRAFTER_05B, n_layers=1, vocab=4096), prefix=70, k=32, forced=[5, 32], tol=2e-2),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_moe_lockstep(name):
+    import torch
+    case = CASES[name]
+    t, d, k, n = case["target"], case["drafter"], case["k"], case["prefix"]
+    wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    eng = make_engine(t, d, wt, wd, 1, 256, k)
+    dtype = np.float64 if name == "small_mixture" else np.float32
+    pair = make_pair(t, d, wt, wd, 256, dtype=dtype)
+    prompt = di.prompt_ids(t.vocab, n)
+    pair.prefill(prompt)
+    eng.prefill([prompt])
+    dec = O.Decoder(t, wt.as_f32, dtype, "bf16")
+    worst = 0.0
+    for a_want in case["forced"]:
+        truth = O.ar_decode(dec, pair.prefix(), k)
+        block = list(truth)
+        if a_want < k:
+            block[a_want] = (block[a_want] + 1) % t.vocab
+        eng.draft_block(k, 0.0, 0)
+        res = O.deer_iteration(pair, k, 0.0, None, draft_override=block)
+        eng.verify_block(k, 0.0, torch.tensor([block], dtype=torch.int32, device="cuda"))
+        err = float(np.abs(eng.debug_get_logits(0, k)[0] - res["target_logits"]).max())
+        worst = max(worst, err)
+        assert err < case["tol"], err
+        acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
+        if acc[0] != res["accept_len"] or com[0] != res["committed"]:
+            first = min(acc[0], res["accept_len"])
+            assert top2_margin(res["target_logits"])[first] < 1e-2
+            eng.prefill([pair.prefix()])
+        else:
+            assert acc[0] == a_want
+    print(f"\n[{name}] max |target logit error| {worst:.2e}")
+    eng.close()
