@@ -111,20 +111,27 @@ def cpu_baseline(cfg, k, prefix, e_ncommit):
         return dt, tok
 
     t, d = cfg["target"], cfg["drafter"]
-    t1, tok_t = time_pass(t, di.TARGET_SEED, 1, False)
-    t2, _ = time_pass(t, di.TARGET_SEED, 2, False)
-    d1, tok_d = time_pass(d, di.DRAFTER_SEED, 1, True)
-    d2, _ = time_pass(d, di.DRAFTER_SEED, 2, True)
+    la, lb, reps = 2, min(6, t.n_layers), 3
+
+    def med(shape, seed, n_layers, drafter):
+        runs = [time_pass(shape, seed, n_layers, drafter) for _ in range(reps)]
+        return float(np.median([r[0] for r in runs])), runs[0][1]
+
+    t1, tok_t = med(t, di.TARGET_SEED, la, False)
+    t2, _ = med(t, di.TARGET_SEED, lb, False)
+    d1, tok_d = med(d, di.DRAFTER_SEED, la, True)
+    d2, _ = med(d, di.DRAFTER_SEED, min(lb, d.n_layers), True)
     t0 = time.perf_counter()
     O.accept_block_greedy(tok_t, tok_d)
     t_acc = time.perf_counter() - t0
-    per_t, per_d = max(t2 - t1, 1e-9), max(d2 - d1, 1e-9)
-    full = (t1 - per_t) + t.n_layers * per_t + (d1 - per_d) + d.n_layers * per_d + t_acc
+    per_t = max((t2 - t1) / max(lb - la, 1), 1e-9)
+    per_d = max((d2 - d1) / max(min(lb, d.n_layers) - la, 1), 1e-9)
+    full = (t1 - la * per_t) + t.n_layers * per_t + (d1 - la * per_d) + d.n_layers * per_d + t_acc
     return {
         "value": e_ncommit / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
         "sample": (f"one draft+verify+accept iteration of the numpy fp32 oracle at the workload's widths, vocab, "
-                   f"prefix {prefix} (seeded KV fill) and k={k}, run with 1 and 2 layers of each model "
-                   f"(target {t1:.2f}s/{t2:.2f}s, drafter {d1:.2f}s/{d2:.2f}s) and extrapolated linearly to "
+                   f"prefix {prefix} (seeded KV fill) and k={k}, run with {la} and {lb} layers of each model, median of "
+                   f"{reps} (target {t1:.2f}s/{t2:.2f}s, drafter {d1:.2f}s/{d2:.2f}s) and extrapolated linearly to "
                    f"{t.n_layers}+{d.n_layers} layers: {full:.1f}s per iteration"),
         "iteration_s": full,
     }
@@ -137,6 +144,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="qwen3_8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-prefill", action="store_true",
+                    help="profiling aid: declare the prefix prefilled without running the models (zero caches)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="profiling aid: also run one plain 1 GiB device copy (scale factor for byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding or collectives are built); "
@@ -154,8 +165,17 @@ def main():
     load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
     prompt = di.prompt_ids(t.vocab, prefix)
     t0 = time.perf_counter()
-    eng.prefill([prompt])
+    if args.skip_prefill:
+        eng.set_prefilled([prefix], [int(prompt[-1])])
+    else:
+        eng.prefill([prompt])
     prefill_s = time.perf_counter() - t0
+    if args.copy_probe:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def step(events=None):
         if events:

@@ -312,7 +312,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     }
     const int nkt = (max_limit + 31) / 32;
     // key-range splits: aim at ~256 blocks; ntiles * NS never exceeds the partial buffer (max(64, tiles))
-    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 256;
+    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 128;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
     NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
