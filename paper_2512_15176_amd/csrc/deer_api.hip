@@ -247,9 +247,13 @@ const char *check_params(const deer_init_params *p) {
 // ---------------------------------------------------------------------------------------------
 // launches
 // ---------------------------------------------------------------------------------------------
+// K splits per column group.  Measured on MI355X (per-launch time vs S for the four 8B-shaped matrices):
+// the split-K tail (partial store, arrival, partial loads) costs more than idle CUs once ~190 blocks
+// exist; long-K matrices prefer ~256 blocks.
 int choose_split(int N, int KS, int zgroups) {
-    int blocks = (N / CG) * zgroups;
-    int S = (256 + blocks - 1) / blocks;
+    const int blocks = (N / CG) * zgroups;
+    const int target = KS > 256 ? 256 : 192;
+    int S = (target + blocks - 1) / blocks;
     S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);
