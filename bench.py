@@ -43,13 +43,18 @@ def trunc_geom(k, mean):
     return rho, f(rho) + 1 - rho ** k
 
 
-def verify_bytes(shape, prefix, k):
+def verify_bytes(shape, prefix, k, batch=1):
     """Algorithmic HBM bytes of one verify pass at batch 1: every projection + LM head once (bf16),
     plus the K,V rows of the prefix and the block (bf16)."""
     d, hd = shape.d_model, shape.head_dim
-    layer = d * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * d + 3 * d * shape.d_ff
-    weights = 2.0 * (shape.n_layers * layer + d * shape.vocab)
-    kv = 2.0 * 2 * shape.n_layers * shape.n_kv_heads * hd * (prefix - 1 + k)
+    attn = d * (shape.n_q_heads + 2 * shape.n_kv_heads) * hd + shape.n_q_heads * hd * d
+    if shape.n_experts:   # expected distinct experts touched by k rows x top_k uniform picks
+        distinct = shape.n_experts * (1.0 - (1.0 - shape.top_k / shape.n_experts) ** k)
+        ffn = d * shape.n_experts + distinct * 3 * d * shape.d_ff_expert
+    else:
+        ffn = 3 * d * shape.d_ff
+    weights = 2.0 * (shape.n_layers * (attn + ffn) + d * shape.vocab)
+    kv = 2.0 * 2 * shape.n_layers * shape.n_kv_heads * hd * (prefix - 1 + k) * batch
     return weights, kv
 
 
@@ -66,11 +71,33 @@ def load_random_model(eng, model, shape, seed):
     eng.load_tensor(model, "embed", -1, -1, rnd(*shape.tensor_shape("embed")))
     eng.load_tensor(model, "lm_head", -1, -1, rnd(*shape.tensor_shape("lm_head")))
     for l in range(shape.n_layers):
-        for name in ("wq", "wk", "wv", "wo", "wg", "wu", "wd"):
+        for name in ("wq", "wk", "wv", "wo"):
             eng.load_tensor(model, name, l, -1, rnd(*shape.tensor_shape(name)))
+        if shape.n_experts:
+            eng.load_tensor(model, "router", l, -1, rnd(*shape.tensor_shape("router")))
+        for e in (range(shape.n_experts) if shape.n_experts else [-1]):
+            for name in ("wg", "wu", "wd"):
+                eng.load_tensor(model, name, l, e, rnd(*shape.tensor_shape(name)))
 
 
-def cpu_baseline(cfg, k, prefix, e_ncommit):
+def fill_random_caches(eng, shape_by_model, lens):
+    """Stand-in cache contents N(0,1) bf16 for prefixes too long to prefill inside a benchmark run."""
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(di.KV_SEED)
+    for model, shape in shape_by_model.items():
+        lay = eng.get_kv_layout(model)
+        kv = eng.kv_tensor(model)
+        L, B, H, hd, S = shape.n_layers, eng.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
+        K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
+        Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, hd, S)
+        for l in range(L):
+            for b, n in enumerate(lens):
+                K[l, b, :, :n, :] = torch.randn(H, n, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+                Vt[l, b, :, :, :n] = torch.randn(H, hd, n, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+
+
+def cpu_baseline(cfg, k, prefix, e_ncommit, batch=1):
     """The oracle, as it stands, timed on this host on a bounded sample of the workload."""
     from threadpoolctl import threadpool_info
     from oracle import deer_oracle as O
@@ -80,7 +107,7 @@ def cpu_baseline(cfg, k, prefix, e_ncommit):
         cache = {}
 
         def get(name, layer=-1, expert=-1):
-            key = (name, layer)
+            key = (name, layer, expert)
             if key not in cache:
                 cache[key] = di.weight_f32(shape, seed, name, layer, expert, threads=cores)
             return cache[key]
@@ -126,13 +153,13 @@ def cpu_baseline(cfg, k, prefix, e_ncommit):
     t_acc = time.perf_counter() - t0
     per_t = max((t2 - t1) / max(lb - la, 1), 1e-9)
     per_d = max((d2 - d1) / max(min(lb, d.n_layers) - la, 1), 1e-9)
-    full = (t1 - la * per_t) + t.n_layers * per_t + (d1 - la * per_d) + d.n_layers * per_d + t_acc
+    full = batch * ((t1 - la * per_t) + t.n_layers * per_t + (d1 - la * per_d) + d.n_layers * per_d + t_acc)
     return {
         "value": e_ncommit / full, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
         "sample": (f"one draft+verify+accept iteration of the numpy fp32 oracle at the workload's widths, vocab, "
                    f"prefix {prefix} (seeded KV fill) and k={k}, run with {la} and {lb} layers of each model, median of "
                    f"{reps} (target {t1:.2f}s/{t2:.2f}s, drafter {d1:.2f}s/{d2:.2f}s) and extrapolated linearly to "
-                   f"{t.n_layers}+{d.n_layers} layers: {full:.1f}s per iteration"),
+                   f"{t.n_layers}+{d.n_layers} layers and {batch} sequence(s): {full:.1f}s per iteration"),
         "iteration_s": full,
     }
 
@@ -158,17 +185,24 @@ def main():
     from paper_2512_15176_amd import DeerEngine, binding
 
     cfg = di.CONFIGS[args.config]
-    t, d, k, prefix = cfg["target"], cfg["drafter"], cfg["k"], cfg["prefix"]
+    t, d, k, prefix, B = cfg["target"], cfg["drafter"], cfg["k"], cfg["prefix"], cfg["batch"]
+    T = float(cfg["T"][0])
+    long_prefix = prefix * B > 8192          # a real prefill of these would dominate the run
+    if long_prefix:
+        args.steps, args.warmup = min(args.steps, 10), min(args.warmup, 2)
     max_seq = (prefix + (args.steps + args.warmup + 8) * k + k + 63) // 64 * 64
-    eng = DeerEngine(t, d, 1, max_seq, k, di.mask_token_id(t.vocab), -1, False)
+    eng = DeerEngine(t, d, B, max_seq, k, di.mask_token_id(t.vocab), -1, False)
     load_random_model(eng, binding.DEER_TARGET, t, di.TARGET_SEED)
     load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
     prompt = di.prompt_ids(t.vocab, prefix)
     t0 = time.perf_counter()
-    if args.skip_prefill:
-        eng.set_prefilled([prefix], [int(prompt[-1])])
+    if long_prefix:
+        fill_random_caches(eng, {binding.DEER_TARGET: t, binding.DEER_DRAFTER: d}, [prefix] * B)
+        eng.set_prefilled([prefix] * B, [int(prompt[-1])] * B)
+    elif args.skip_prefill:
+        eng.set_prefilled([prefix] * B, [int(prompt[-1])] * B)
     else:
-        eng.prefill([prompt])
+        eng.prefill([prompt] * B)
     prefill_s = time.perf_counter() - t0
     if args.copy_probe:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -180,13 +214,13 @@ def main():
     def step(events=None):
         if events:
             events[0].record()
-        dr = eng.draft_block(k, 0.0, 0)
+        dr = eng.draft_block(k, T, di.SAMPLING_SEED)
         if events:
             events[1].record()
-        eng.verify_block(k, 0.0, dr)
+        eng.verify_block(k, T, dr)
         if events:
             events[2].record()
-        out = eng.accept_and_commit(k, 0.0, 0)
+        out = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
         if events:
             events[3].record()
         return out
@@ -199,7 +233,8 @@ def main():
     t0 = time.perf_counter()
     for i in range(args.steps):
         acc, _, _ = step(evs[i])
-        acc_hist[acc[0]] += 1
+        for a in acc:
+            acc_hist[a] += 1
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall / args.steps * 1e3
@@ -213,38 +248,42 @@ def main():
     g_ms = g_bytes = a_ms = a_bytes = 0.0
     g_n = a_n = 0
     for _ in range(n_prof):
-        dr = eng.draft_block(k, 0.0, 0)
+        dr = eng.draft_block(k, T, di.SAMPLING_SEED)
         eng.synchronize()
         eng.debug_profile(True)   # drop the drafter's launches: keep verify only
-        eng.verify_block(k, 0.0, dr)
+        eng.verify_block(k, T, dr)
         r0, r1 = eng.debug_profile_read(0), eng.debug_profile_read(1)
         g_ms, g_n, g_bytes = g_ms + r0[0], g_n + r0[1], g_bytes + r0[2]
         a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
-        eng.accept_and_commit(k, 0.0, 0)
+        eng.accept_and_commit(k, T, di.SAMPLING_SEED)
     eng.debug_profile(False)
+    wbytes, kvbytes = verify_bytes(t, prefix, k, B)
 
-    wbytes, kvbytes = verify_bytes(t, prefix, k)
     rho8, en8 = trunc_geom(k, k / 4)
     rho24, en24 = trunc_geom(k, 3 * k / 4)
     iter_ms = td + tv + ta
     gemm_gbs = g_bytes / (g_ms * 1e-3) / 1e9
+    gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
+    if t.n_experts:   # grouped expert GEMMs touch a data-dependent set of experts: use the pass-level figure
+        gemm_gbs = (wbytes + kvbytes) / (tv * 1e-3) / 1e9
+        gemm_label = "verify pass, all kernels (expected distinct experts)"
     out = {
         "metric": "committed tokens/s per draft-verify step, 8B shape k=32; verify HBM GB/s vs peak",
-        "value": en8 / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": B * en8 / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.config}: target {t.n_layers}L d={t.d_model}, drafter {d.n_layers}L d={d.d_model}, "
-                               f"batch 1, prefix {prefix}, k={k}, T=0, random-init bf16 weights",
-                   "accepted_length_law": f"truncated geometric, mean {k // 4} (value) / {3 * k // 4}",
+                               f"batch {B}, prefix {prefix}, k={k}, T={T:g}, random-init bf16 weights",
+                   "accepted_length_law": f"truncated geometric on the accepted length, mean {k // 4} (value) / {3 * k // 4}",
                    "expected_committed_per_step": [en8, en24]},
-        "tokens_per_s_mean_accept_8": en8 / (ms_per_step * 1e-3),
-        "tokens_per_s_mean_accept_24": en24 / (ms_per_step * 1e-3),
+        "tokens_per_s_mean_accept_8": B * en8 / (ms_per_step * 1e-3),
+        "tokens_per_s_mean_accept_24": B * en24 / (ms_per_step * 1e-3),
         "draft_ms": float(td), "verify_ms": float(tv), "accept_ms": float(ta), "event_iter_ms": float(iter_ms),
         "prefill_s": prefill_s,
         "measured_accept_hist": {str(i): int(c) for i, c in enumerate(acc_hist) if c},
         "verify_pass": {"algorithmic_bytes": wbytes + kvbytes, "GBs": (wbytes + kvbytes) / (tv * 1e-3) / 1e9,
                         "frac_of_hbm_peak": (wbytes + kvbytes) / (tv * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"bound": "hbm", "kernel": "k_gemm (weight-streaming GEMM, verify pass)", "achieved": gemm_gbs,
+        "roofline": {"bound": "hbm", "kernel": gemm_label, "achieved": gemm_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": None,
                      "launches": int(g_n), "avg_launch_us": g_ms / max(g_n, 1) * 1e3,
                      "bytes_per_launch": g_bytes / max(g_n, 1)},
@@ -252,7 +291,7 @@ def main():
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, k, prefix, en8)
+        out["cpu_baseline"] = cpu_baseline(cfg, k, prefix, B * en8, B)
     eng.close()
     print(json.dumps(out))
 
