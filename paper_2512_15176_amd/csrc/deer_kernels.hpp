@@ -399,29 +399,47 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
 }
 
 // O-proj / down-proj epilogue: h += y; new fragment planes of h; per-group sum of squares.
-// `tile` is overwritten with the new h values.
-__device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, int cg, int t) {
+// `hreg` holds the old h values of this thread's elements e = threadIdx.x + 512*i (row e>>7, column e&127),
+// loaded by resid_prefetch() before the tile was ready.  `tile` is overwritten with the new h values.
+__device__ __forceinline__ void resid_prefetch(const GemmArgs &a, float (&hreg)[8], int cg, int t) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int e = threadIdx.x + 512 * i;
+        hreg[i] = a.h[(size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127)];
+    }
+}
+
+__device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float *scratch, const float (&hreg)[8], int cg, int t) {
     const int N = a.N;
-    for (int e = threadIdx.x; e < 32 * CG; e += blockDim.x) {
-        int row = e >> 7, col = e & 127;
-        size_t gi = (size_t)(t * 32 + row) * N + cg * CG + col;
-        float v = a.h[gi] + tile[row * RED_STRIDE + col];
-        a.h[gi] = v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int e = threadIdx.x + 512 * i;
+        const int row = e >> 7, col = e & 127;
+        const float v = hreg[i] + tile[row * RED_STRIDE + col];
+        a.h[(size_t)(t * 32 + row) * N + cg * CG + col] = v;
         tile[row * RED_STRIDE + col] = v;
     }
     __syncthreads();
-    for (int item = threadIdx.x; item < 512; item += blockDim.x) {
-        int row = item & 31, oct = item >> 5;
+    {   // 512 (row, octet) items, one per thread; lanes l and l^32 of a wave hold two octets of the same row
+        const int row = threadIdx.x & 31, oct = threadIdx.x >> 5;
+        const float *tp = tile + row * RED_STRIDE + oct * 8;
         uint4 hi, lo;
-        pack8_split(tile + row * RED_STRIDE + oct * 8, hi, lo);
+        pack8_split(tp, hi, lo);
         size_t v = (size_t)t * (N / 16) * 64 + frag_vec(row, cg * 16 + oct);
         a.xhi_out[v] = hi;
         a.xlo_out[v] = lo;
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss += tp[e] * tp[e];
+        ss += __shfl_xor(ss, 32);
+        if ((threadIdx.x & 63) < 32) scratch[(threadIdx.x >> 6) * 32 + row] = ss;   // [8 waves][32 rows]
     }
+    __syncthreads();
     if (threadIdx.x < 32) {
-        float s = 0.f;
-        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
-        a.ssq_out[(size_t)(t * 32 + threadIdx.x) * (N / CG) + cg] = s;
+        float s2 = 0.f;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) s2 += scratch[w * 32 + threadIdx.x];   // fixed order
+        a.ssq_out[(size_t)(t * 32 + threadIdx.x) * (N / CG) + cg] = s2;
     }
 }
 
@@ -540,7 +558,8 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
 }
 
 template <int EPI>
-__device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, int cg, int ct) {
+__device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, float *scratch,
+                                             const float (&hreg)[8], int cg, int ct) {
     // caller has synchronised after filling `tile`
     const int t = a.mt0 + ct * a.mt_stride;
     if (EPI != EPI_RESID) {
@@ -548,18 +567,70 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, flo
         __syncthreads();
     }
     if (EPI == EPI_QKV) epi_qkv(a, tile, rstd, cg, t);
-    else if (EPI == EPI_RESID) epi_resid(a, tile, cg, t);
+    else if (EPI == EPI_RESID) epi_resid(a, tile, scratch, hreg, cg, t);
     else if (EPI == EPI_SWIGLU) epi_swiglu(a, tile, rstd, cg, t);
     else if (EPI == EPI_ROUTER) epi_router(a, tile, rstd, t);
     else epi_lmhead(a, tile, rstd, cg, ct, t);
 }
 
+// Sum of the 8 waves' accumulators (one 32 x 128 tile each, MFMA register layout) in the fixed order
+// ((w0+w4) + (w1+w5 ... see below), result as a row-major tile (stride RED_STRIDE) in `tile`.
+// Round A: waves 4..7 park their registers in LDS as 16-byte vectors in register order (conflict-free),
+// waves 0..3 add them (w += w+4).  Round B: waves 1..3 park, wave 0 adds them in order 1, 2, 3 and
+// writes the tile.  `red` holds 4 * 4096 floats.  Ends with a barrier.
+__device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *red, float *tile, int w, int lane) {
+    float4 *red4 = (float4 *)red;
+    if (w >= 4) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                red4[((w - 4) * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+    }
+    __syncthreads();
+    if (w < 4) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = red4[(w * 16 + nb * 4 + q) * 64 + lane];
+                acc[nb][4 * q] += v.x; acc[nb][4 * q + 1] += v.y; acc[nb][4 * q + 2] += v.z; acc[nb][4 * q + 3] += v.w;
+            }
+    }
+    __syncthreads();
+    if (w >= 1 && w < 4) {
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                red4[((w - 1) * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+    }
+    __syncthreads();
+    if (w == 0) {
+        const int half = lane >> 5, cl = lane & 31;
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float4 v = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+#pragma unroll
+                for (int ww = 0; ww < 3; ++ww) {
+                    const float4 u = red4[(ww * 16 + nb * 4 + q) * 64 + lane];
+                    v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
+                }
+                float *tp = tile + (8 * q + 4 * half) * RED_STRIDE + nb * 32 + cl;   // rows 8q + 4*half + 0..3
+                tp[0] = v.x; tp[RED_STRIDE] = v.y; tp[2 * RED_STRIDE] = v.z; tp[3 * RED_STRIDE] = v.w;
+            }
+    }
+    __syncthreads();
+}
+
 template <int MT, int EPI>
 __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
-    __shared__ float red[4 * 32 * 128];   // wave-reduction scratch; the finished tile lives at red + 4096
+    __shared__ float red[4 * 32 * 128];          // wave-reduction scratch (64 KB)
+    __shared__ float tile[32 * RED_STRIDE];      // the finished 32 x 128 tile, row-major
     __shared__ float s_rstd[32];
     __shared__ int s_last;
-    float *tile = red + 32 * 128;         // stride RED_STRIDE
     const int cg = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int N = a.N, KS = a.KS, S = a.S;
@@ -622,44 +693,21 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
         }
     }
 
-    // fixed-order tree over the 8 waves: ((w0+w4)+(w2+w6)) + ((w1+w5)+(w3+w7))
-    const int half = lane >> 5, cl = lane & 31;
+    // sum the 8 waves, then either finish (S == 1) or hand the partial tile over
+    float hreg[8];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        if (mt > 0) __syncthreads();
-#pragma unroll
-        for (int round = 0; round < 3; ++round) {
-            const int hi_lo = 4 >> round;   // waves [hi_lo, 2*hi_lo) store, waves [0, hi_lo) add
-            if (w >= hi_lo && w < 2 * hi_lo) {
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        red[((w - hi_lo) * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl] = acc[mt][nb][r];
-            }
-            __syncthreads();
-            if (w < hi_lo) {
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        acc[mt][nb][r] += red[(w * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl];
-            }
-            __syncthreads();
-        }
-        if (w == 0) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) tile[mfma_row(r, half) * RED_STRIDE + nb * 32 + cl] = acc[mt][nb][r];
-        }
-        __syncthreads();
         const int ct = z * MT + mt;
+        if (mt > 0) __syncthreads();
+        if (EPI == EPI_RESID && S == 1) resid_prefetch(a, hreg, cg, a.mt0 + ct * a.mt_stride);
+        reduce_waves_to_tile(acc[mt], red, tile, w, lane);
         if (S == 1) {
-            run_epilogue<EPI>(a, tile, s_rstd, cg, ct);
+            run_epilogue<EPI>(a, tile, s_rstd, red, hreg, cg, ct);
         } else {
             float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
-            for (int e = threadIdx.x; e < 32 * 64; e += 512) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = threadIdx.x + 512 * i;
                 const int row = e >> 6, c2 = (e & 63) * 2;
                 const float *tp = tile + row * RED_STRIDE + c2;
                 st_agent2(out + (size_t)row * N + c2, tp[0], tp[1]);
@@ -674,27 +722,37 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
     for (int mt = 0; mt < MT; ++mt) {
         const int ct = z * MT + mt;
         if (mt > 0) __syncthreads();
+        if (EPI == EPI_RESID) resid_prefetch(a, hreg, cg, a.mt0 + ct * a.mt_stride);
         const size_t sstride = (size_t)a.rows_total * N;
-        for (int e = threadIdx.x; e < 32 * 64; e += 512) {
-            const int row = e >> 6, c2 = (e & 63) * 2;
-            const float *p = a.part + ((size_t)ct * 32 + row) * N + (size_t)cg * CG + c2;
-            float2 v = make_float2(0.f, 0.f);
-            int ss = 0;
-            for (; ss + 4 <= S; ss += 4) {
-                float2 p0 = ld_agent2(p + (size_t)ss * sstride), p1 = ld_agent2(p + (size_t)(ss + 1) * sstride);
-                float2 p2 = ld_agent2(p + (size_t)(ss + 2) * sstride), p3 = ld_agent2(p + (size_t)(ss + 3) * sstride);
-                v.x = (((v.x + p0.x) + p1.x) + p2.x) + p3.x;
-                v.y = (((v.y + p0.y) + p1.y) + p2.y) + p3.y;
-            }
-            for (; ss < S; ++ss) {
-                float2 p0 = ld_agent2(p + (size_t)ss * sstride);
-                v.x += p0.x; v.y += p0.y;
-            }
-            tile[row * RED_STRIDE + c2] = v.x;
-            tile[row * RED_STRIDE + c2 + 1] = v.y;
+        const float *p[4];
+        float2 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + 512 * i;
+            p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
+            v[i] = make_float2(0.f, 0.f);
+        }
+        for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 4 elements of loads in flight, summed in order
+            float2 pv[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pv[u][i] = ld_agent2(p[i] + (size_t)min(s0 + u, S - 1) * sstride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { v[i].x += pv[u][i].x; v[i].y += pv[u][i].y; }
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + 512 * i;
+            float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
+            tp[0] = v[i].x; tp[1] = v[i].y;
         }
         __syncthreads();
-        run_epilogue<EPI>(a, tile, s_rstd, cg, ct);
+        run_epilogue<EPI>(a, tile, s_rstd, red, hreg, cg, ct);
     }
 }
 
@@ -737,9 +795,9 @@ struct MoeArgs {
 template <int MODE>
 __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
     __shared__ float red[4 * 32 * 128];
+    __shared__ float tile[32 * RED_STRIDE];
     __shared__ float s_rstd[32];
     __shared__ int s_row[32], s_slot[32];
-    float *tile = red + 32 * 128;
     const int cg = blockIdx.x, ex = blockIdx.y, chunk = blockIdx.z;
     const int n = a.cnt[ex] - chunk * 32;
     if (n <= 0) return;
@@ -804,30 +862,7 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
             }
         }
     }
-#pragma unroll
-    for (int round = 0; round < 3; ++round) {
-        const int hi_lo = 4 >> round;
-        if (w >= hi_lo && w < 2 * hi_lo) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) red[((w - hi_lo) * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl] = acc[nb][r];
-        }
-        __syncthreads();
-        if (w < hi_lo) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[nb][r] += red[(w * 32 + mfma_row(r, half)) * 128 + nb * 32 + cl];
-        }
-        __syncthreads();
-    }
-    if (w == 0) {
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tile[mfma_row(r, half) * RED_STRIDE + nb * 32 + cl] = acc[nb][r];
-    }
+    reduce_waves_to_tile(acc, red, tile, w, lane);
     if (MODE == MOE_GATEUP && threadIdx.x < 32) {
         float sc = 0.f;
         const int r = s_row[threadIdx.x];
