@@ -135,6 +135,44 @@ __device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag)
     return *s_flag != 0;
 }
 
+// Accessors for data that crosses workgroups INSIDE one kernel (the persistent pass kernel).  COH = true:
+// agent-scope accesses, coherent across the XCDs' separate L2s; COH = false: plain accesses (producer
+// and consumer are separated by a kernel boundary).
+template <bool COH> __device__ __forceinline__ float ldf(const float *p) {
+    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return *p;
+}
+template <bool COH> __device__ __forceinline__ void stf(float *p, float v) {
+    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool COH> __device__ __forceinline__ void sti(int *p, int v) {
+    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool COH> __device__ __forceinline__ uint4 ld16(const uint4 *p) {
+    if (COH) {
+        const unsigned long long *q = (const unsigned long long *)p;
+        unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
+    }
+    return *p;
+}
+template <bool COH> __device__ __forceinline__ void st16(uint4 *p, uint4 v) {
+    if (COH) {
+        unsigned long long *q = (unsigned long long *)p;
+        __hip_atomic_store(q, ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(q + 1, ((unsigned long long)v.w << 32) | v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *p = v;
+    }
+}
+template <bool COH> __device__ __forceinline__ void st_u16(uint16_t *p, uint16_t v) {
+    if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+
 // (value, index) max with lowest index on ties
 __device__ __forceinline__ void argmax_merge(float &v, int &i, float v2, int i2) {
     if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
@@ -341,16 +379,18 @@ struct GemmArgs {
 };
 
 // rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
-__device__ __forceinline__ void tile_rstd(const float *__restrict__ ssq, float *rstd, int grow0, int ncg, int d, float eps) {
+template <bool COH>
+__device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int grow0, int ncg, int d, float eps) {
     if (threadIdx.x < 32) {
         const float *p = ssq + (size_t)(grow0 + threadIdx.x) * ncg;
         float s = 0.f;
-        for (int g = 0; g < ncg; ++g) s += p[g];
+        for (int g = 0; g < ncg; ++g) s += ldf<COH>(p + g);
         rstd[threadIdx.x] = rsqrtf(s / (float)d + eps);
     }
 }
 
 // QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
+template <bool COH>
 __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
     const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
     const int half_hd = hd >> 1;
@@ -381,17 +421,17 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
             uint4 hi, lo;
             pack8_split(v, hi, lo);
             size_t vec = ((size_t)(t * Hq + head) * (hd / 16)) * 64 + frag_vec(row, i0 >> 3);
-            a.qhi[vec] = hi;
-            a.qlo[vec] = lo;
+            st16<COH>(a.qhi + vec, hi);
+            st16<COH>(a.qlo + vec, lo);
         } else {
             const int slot = a.rm.slot[grow];
             if (slot >= 0) {
                 size_t base = (size_t)b * a.kv.seq_stride + (size_t)head * a.kv.head_stride;
                 if (kind == 1) {
-                    *(uint4 *)(a.kv.k + base + (size_t)slot * hd + i0) = pack8(v);
+                    st16<COH>((uint4 *)(a.kv.k + base + (size_t)slot * hd + i0), pack8(v));
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) a.kv.vt[base + (size_t)(i0 + e) * a.kv.max_seq + slot] = (uint16_t)f2bf(v[e]);
+                    for (int e = 0; e < 8; ++e) st_u16<COH>(a.kv.vt + base + (size_t)(i0 + e) * a.kv.max_seq + slot, (uint16_t)f2bf(v[e]));
                 }
             }
         }
@@ -401,14 +441,16 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
 // O-proj / down-proj epilogue: h += y; new fragment planes of h; per-group sum of squares.
 // `hreg` holds the old h values of this thread's elements e = threadIdx.x + 512*i (row e>>7, column e&127),
 // loaded by resid_prefetch() before the tile was ready.  `tile` is overwritten with the new h values.
+template <bool COH>
 __device__ __forceinline__ void resid_prefetch(const GemmArgs &a, float (&hreg)[8], int cg, int t) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int e = threadIdx.x + 512 * i;
-        hreg[i] = a.h[(size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127)];
+        hreg[i] = ldf<COH>(a.h + (size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127));
     }
 }
 
+template <bool COH>
 __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float *scratch, const float (&hreg)[8], int cg, int t) {
     const int N = a.N;
 #pragma unroll
@@ -416,7 +458,7 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         const int e = threadIdx.x + 512 * i;
         const int row = e >> 7, col = e & 127;
         const float v = hreg[i] + tile[row * RED_STRIDE + col];
-        a.h[(size_t)(t * 32 + row) * N + cg * CG + col] = v;
+        stf<COH>(a.h + (size_t)(t * 32 + row) * N + cg * CG + col, v);
         tile[row * RED_STRIDE + col] = v;
     }
     __syncthreads();
@@ -426,8 +468,8 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         uint4 hi, lo;
         pack8_split(tp, hi, lo);
         size_t v = (size_t)t * (N / 16) * 64 + frag_vec(row, cg * 16 + oct);
-        a.xhi_out[v] = hi;
-        a.xlo_out[v] = lo;
+        st16<COH>(a.xhi_out + v, hi);
+        st16<COH>(a.xlo_out + v, lo);
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss += tp[e] * tp[e];
@@ -439,11 +481,12 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         float s2 = 0.f;
 #pragma unroll
         for (int w = 0; w < 8; ++w) s2 += scratch[w * 32 + threadIdx.x];   // fixed order
-        a.ssq_out[(size_t)(t * 32 + threadIdx.x) * (N / CG) + cg] = s2;
+        stf<COH>(a.ssq_out + (size_t)(t * 32 + threadIdx.x) * (N / CG) + cg, s2);
     }
 }
 
 // gate/up epilogue: group = 64 gate + 64 up channels -> SiLU(g) * u, fragment planes over F
+template <bool COH>
 __device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
     for (int item = threadIdx.x; item < 256; item += blockDim.x) {
         const int row = item & 31, oct = item >> 5;   // 8 octets of 8 channels
@@ -457,13 +500,14 @@ __device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile,
         uint4 hi, lo;
         pack8_split(v, hi, lo);
         size_t vec = (size_t)t * (a.F / 16) * 64 + frag_vec(row, cg * 8 + oct);
-        a.ahi[vec] = hi;
-        a.alo[vec] = lo;
+        st16<COH>(a.ahi + vec, hi);
+        st16<COH>(a.alo + vec, lo);
     }
 }
 
 // LM-head epilogue: RMSNorm scale, optional logits store, per-(row, group) argmax / sumexp / Gumbel-max.
 // LM rows are the first k rows of the tile; lm_row = ct*k + i.
+template <bool COH>
 __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile, const float *rstd, int cg, int ct, int t) {
     if (threadIdx.x >= 256) return;
     const int V = a.N, k = a.k;
@@ -506,9 +550,8 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
 #pragma unroll
     for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
     if (live && sub == 0) {
-        RowStat s;
-        s.m = m; s.idx = idx; s.sumexp = se; s.gm = gm; s.gidx = gidx;
-        a.stat[((size_t)ct * k + row) * a.ncg_v + cg] = s;
+        RowStat *sp = a.stat + ((size_t)ct * k + row) * a.ncg_v + cg;
+        stf<COH>(&sp->m, m); sti<COH>(&sp->idx, idx); stf<COH>(&sp->sumexp, se); stf<COH>(&sp->gm, gm); sti<COH>(&sp->gidx, gidx);
     }
 }
 
@@ -557,24 +600,24 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
     }
 }
 
-template <int EPI>
+template <int EPI, bool COH>
 __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, float *scratch,
                                              const float (&hreg)[8], int cg, int ct) {
     // caller has synchronised after filling `tile`
     const int t = a.mt0 + ct * a.mt_stride;
     if (EPI != EPI_RESID) {
-        tile_rstd(a.ssq_in, rstd, t * 32, a.ncg_in, a.d_in, a.eps);
+        tile_rstd<COH>(a.ssq_in, rstd, t * 32, a.ncg_in, a.d_in, a.eps);
         __syncthreads();
     }
-    if (EPI == EPI_QKV) epi_qkv(a, tile, rstd, cg, t);
-    else if (EPI == EPI_RESID) epi_resid(a, tile, scratch, hreg, cg, t);
-    else if (EPI == EPI_SWIGLU) epi_swiglu(a, tile, rstd, cg, t);
+    if (EPI == EPI_QKV) epi_qkv<COH>(a, tile, rstd, cg, t);
+    else if (EPI == EPI_RESID) epi_resid<COH>(a, tile, scratch, hreg, cg, t);
+    else if (EPI == EPI_SWIGLU) epi_swiglu<COH>(a, tile, rstd, cg, t);
     else if (EPI == EPI_ROUTER) epi_router(a, tile, rstd, t);
-    else epi_lmhead(a, tile, rstd, cg, ct, t);
+    else epi_lmhead<COH>(a, tile, rstd, cg, ct, t);
 }
 
-// Sum of the 8 waves' accumulators (one 32 x 128 tile each, MFMA register layout) in the fixed order
-// ((w0+w4) + (w1+w5 ... see below), result as a row-major tile (stride RED_STRIDE) in `tile`.
+// Sum of the 8 waves' accumulators (one 32 x 128 tile each, MFMA register layout) in a fixed order,
+// result as a row-major tile (stride RED_STRIDE) in `tile`.
 // Round A: waves 4..7 park their registers in LDS as 16-byte vectors in register order (conflict-free),
 // waves 0..3 add them (w += w+4).  Round B: waves 1..3 park, wave 0 adds them in order 1, 2, 3 and
 // writes the tile.  `red` holds 4 * 4096 floats.  Ends with a barrier.
@@ -625,13 +668,63 @@ __device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *re
     __syncthreads();
 }
 
-template <int MT, int EPI>
-__global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
-    __shared__ float red[4 * 32 * 128];          // wave-reduction scratch (64 KB)
-    __shared__ float tile[32 * RED_STRIDE];      // the finished 32 x 128 tile, row-major
-    __shared__ float s_rstd[32];
-    __shared__ int s_last;
-    const int cg = blockIdx.x, s = blockIdx.y, z = blockIdx.z;
+struct GemmSmem {
+    float red[4 * 32 * 128];          // wave-reduction scratch (64 KB)
+    float tile[32 * RED_STRIDE];      // the finished 32 x 128 tile, row-major
+    float rstd[32];
+    int last;
+};
+
+// Sums the S partial tiles of column group cg (row-tile group z) in order s = 0..S-1 and runs the epilogue.
+template <int MT, int EPI, bool COH>
+__device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int cg, int z) {
+    float *tile = sm.tile;
+    const int N = a.N, S = a.S;
+    float hreg[8];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int ct = z * MT + mt;
+        if (mt > 0) __syncthreads();
+        if (EPI == EPI_RESID) resid_prefetch<COH>(a, hreg, cg, a.mt0 + ct * a.mt_stride);
+        const size_t sstride = (size_t)a.rows_total * N;
+        const float *p[4];
+        float2 v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + 512 * i;
+            p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
+            v[i] = make_float2(0.f, 0.f);
+        }
+        for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 4 elements of loads in flight, summed in order
+            float2 pv[8][4];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pv[u][i] = ld_agent2(p[i] + (size_t)min(s0 + u, S - 1) * sstride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < S) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { v[i].x += pv[u][i].x; v[i].y += pv[u][i].y; }
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int e = threadIdx.x + 512 * i;
+            float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
+            tp[0] = v[i].x; tp[1] = v[i].y;
+        }
+        __syncthreads();
+        run_epilogue<EPI, COH>(a, tile, sm.rstd, sm.red, hreg, cg, ct);
+    }
+}
+
+// One work item of the weight-streaming GEMM: column group cg, K split s, row-tile group z.
+// DEFER = false: with S > 1 the block that arrives last at the group's counter finishes the group;
+// DEFER = true: the partial tile is left for a later gemm_finish (after a grid-wide barrier).
+template <int MT, int EPI, bool COH, bool DEFER>
+__device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int cg, int s, int z, int ncg) {
+    float *red = sm.red, *tile = sm.tile, *s_rstd = sm.rstd;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int N = a.N, KS = a.KS, S = a.S;
     const int slices = S * 8, sl = s * 8 + w;
@@ -667,7 +760,7 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)ks * 64]; xlb[dd][mt] = xl[mt][(size_t)ks * 64]; }
+            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)ks * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)ks * 64); }
         }
     }
     for (int kb = ks0; kb < ks1; kb += D) {
@@ -687,7 +780,7 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)kn * 64]; xlb[dd][mt] = xl[mt][(size_t)kn * 64]; }
+                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)kn * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)kn * 64); }
                 }
             }
         }
@@ -699,10 +792,10 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
     for (int mt = 0; mt < MT; ++mt) {
         const int ct = z * MT + mt;
         if (mt > 0) __syncthreads();
-        if (EPI == EPI_RESID && S == 1) resid_prefetch(a, hreg, cg, a.mt0 + ct * a.mt_stride);
+        if (EPI == EPI_RESID && S == 1) resid_prefetch<COH>(a, hreg, cg, a.mt0 + ct * a.mt_stride);
         reduce_waves_to_tile(acc[mt], red, tile, w, lane);
         if (S == 1) {
-            run_epilogue<EPI>(a, tile, s_rstd, red, hreg, cg, ct);
+            run_epilogue<EPI, COH>(a, tile, s_rstd, red, hreg, cg, ct);
         } else {
             float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
 #pragma unroll
@@ -714,46 +807,16 @@ __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
             }
         }
     }
-    if (S == 1) return;
-
+    if (S == 1 || DEFER) return;
     // the block that arrives last at this column group's counter sums all partials and finishes
-    if (!arrive_last(a.counters + (size_t)z * gridDim.x + cg, S, &s_last)) return;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int ct = z * MT + mt;
-        if (mt > 0) __syncthreads();
-        if (EPI == EPI_RESID) resid_prefetch(a, hreg, cg, a.mt0 + ct * a.mt_stride);
-        const size_t sstride = (size_t)a.rows_total * N;
-        const float *p[4];
-        float2 v[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = threadIdx.x + 512 * i;
-            p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
-            v[i] = make_float2(0.f, 0.f);
-        }
-        for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 4 elements of loads in flight, summed in order
-            float2 pv[8][4];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pv[u][i] = ld_agent2(p[i] + (size_t)min(s0 + u, S - 1) * sstride);
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (s0 + u < S) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) { v[i].x += pv[u][i].x; v[i].y += pv[u][i].y; }
-                }
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = threadIdx.x + 512 * i;
-            float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
-            tp[0] = v[i].x; tp[1] = v[i].y;
-        }
-        __syncthreads();
-        run_epilogue<EPI>(a, tile, s_rstd, red, hreg, cg, ct);
-    }
+    if (!arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last)) return;
+    gemm_finish<MT, EPI, COH>(a, sm, cg, z);
+}
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
+    __shared__ GemmSmem sm;
+    gemm_block<MT, EPI, false, false>(a, sm, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1012,7 +1075,7 @@ struct AttnPartial {   // per (tile, head, split): O in register layout [HD/32][
     static constexpr int FLOATS = 32 * HD + 64;
 };
 
-template <int HD>
+template <int HD, bool COH>
 __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int t, int head, int Hq, int lane,
                                                 uint4 *__restrict__ xhi, uint4 *__restrict__ xlo, int tt0 = 0,
                                                 int ntt = HD / 32) {
@@ -1041,28 +1104,26 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
                 uint4 hi, lo;
                 pack8_split(v, hi, lo);
                 size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
-                xhi[vec] = hi;
-                xlo[vec] = lo;
+                st16<COH>(xhi + vec, hi);
+                st16<COH>(xlo + vec, lo);
             }
         }
     }
 }
 
-template <int HD>
-__global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
-                                              const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
-                                              size_t seq_stride, size_t head_stride, int max_seq,
-                                              const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
-                                              float *__restrict__ part, int Hq, int Hkv, int NS, float scale_log2e,
-                                              uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+// One (kv_head, key-range split, pass tile) work item, executed by a group of 4 waves (w = wave in group).
+template <int HD, bool COH>
+__device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
+                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
+                                           int max_seq, const int *__restrict__ tile_seq,
+                                           const int *__restrict__ row_limit, float *part, int Hq, int Hkv, int NS,
+                                           float scale_log2e, uint4 *xhi, uint4 *xlo, int kvh, int split, int t, int w,
+                                           int lane) {
     constexpr int KSQ = HD / 16;   // k-steps of the score contraction
     constexpr int HT = HD / 32;    // 32-row tiles of O^T
     constexpr int PF = AttnPartial<HD>::FLOATS;
     const int G = Hq / Hkv;
-    const int kvh = blockIdx.x % Hkv;
-    const int split = blockIdx.x / Hkv;
-    const int t = blockIdx.y;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, qrow = lane & 31;
+    const int half = lane >> 5, qrow = lane & 31;
     const int b = tile_seq[t];
     const int lim = row_limit[t * 32 + qrow];
     int maxlim = lim, minlim = lim;
@@ -1084,7 +1145,7 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
         {
             const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
+            for (int s = 0; s < KSQ; ++s) { qh[s] = ld16<COH>(Qhi + qb + (size_t)s * 64); ql[s] = ld16<COH>(Qlo + qb + (size_t)s * 64); }
         }
         f32x16 oacc[HT];
 #pragma unroll
@@ -1203,34 +1264,50 @@ __global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, con
         }
         const float l_tot = l_run + __shfl_xor(l_run, 32);
         if (NS == 1) {
-            attn_write_frag<HD>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
+            attn_write_frag<HD, COH>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
         } else {
             float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
                 for (int r2 = 0; r2 < 8; ++r2)
-                    *(float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2) = make_float2(oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-            if (half == 0) *(float2 *)(pp + 32 * HD + 2 * qrow) = make_float2(m_run, l_tot);
+                    if (COH) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+                    else *(float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2) = make_float2(oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+            if (half == 0) {
+                if (COH) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
+                else *(float2 *)(pp + 32 * HD + 2 * qrow) = make_float2(m_run, l_tot);
+            }
         }
     }
 }
 
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
+                                              const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
+                                              size_t seq_stride, size_t head_stride, int max_seq,
+                                              const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
+                                              float *__restrict__ part, int Hq, int Hkv, int NS, float scale_log2e,
+                                              uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+    attn_group<HD, false>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, max_seq, tile_seq, row_limit, part, Hq, Hkv, NS,
+                          scale_log2e, xhi, xlo, blockIdx.x % Hkv, blockIdx.x / Hkv, blockIdx.y, threadIdx.x >> 6,
+                          threadIdx.x & 63);
+}
+
 // Merges the NS key-range partials of block attention in order s = 0..NS-1, normalises, and writes the
 // O-projection's input fragments.  grid: x = query head, y = pass tile; wave w merges O^T tile tt = w.
-template <int HD>
-__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part, int NS, int Hq, float scale_log2e,
-                                                    uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+// One wave merges O^T tile tt of one (tile, head).
+template <int HD, bool COH>
+__device__ __forceinline__ void attn_merge_wave(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi,
+                                                uint4 *xlo, int head, int t, int tt, int lane) {
     constexpr int PF = AttnPartial<HD>::FLOATS;
-    const int head = blockIdx.x, t = blockIdx.y;
-    const int tt = threadIdx.x >> 6, lane = threadIdx.x & 63, qrow = lane & 31;
-    if (tt >= HD / 32) return;
+    const int qrow = lane & 31;
     const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
+    auto ld2 = [](const float *p) { return COH ? ld_agent2(p) : *(const float2 *)p; };
     float M = -INFINITY;
     for (int s0 = 0; s0 < NS; s0 += 8) {
         float mv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = p0[(size_t)min(s0 + u, NS - 1) * PF + 32 * HD + 2 * qrow];
+        for (int u = 0; u < 8; ++u) mv[u] = ld2(p0 + (size_t)min(s0 + u, NS - 1) * PF + 32 * HD + 2 * qrow).x;
 #pragma unroll
         for (int u = 0; u < 8; ++u) M = fmaxf(M, mv[u]);
     }
@@ -1243,9 +1320,9 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const float *pp = p0 + (size_t)min(s0 + u, NS - 1) * PF;
-            ml[u] = *(const float2 *)(pp + 32 * HD + 2 * qrow);
+            ml[u] = ld2(pp + 32 * HD + 2 * qrow);
 #pragma unroll
-            for (int r2 = 0; r2 < 8; ++r2) v[u][r2] = *(const float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2);
+            for (int r2 = 0; r2 < 8; ++r2) v[u][r2] = ld2(pp + ((tt * 8 + r2) * 64 + lane) * 2);
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -1255,7 +1332,17 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
             for (int r2 = 0; r2 < 8; ++r2) { o[0][2 * r2] += f * v[u][r2].x; o[0][2 * r2 + 1] += f * v[u][r2].y; }
         }
     }
-    attn_write_frag<HD>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo, tt, 1);
+    attn_write_frag<HD, COH>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo, tt, 1);
+}
+
+// Merges the NS key-range partials of block attention in order s = 0..NS-1, normalises, and writes the
+// O-projection's input fragments.  grid: x = query head, y = pass tile; wave w merges O^T tile tt = w.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part, int NS, int Hq, float scale_log2e,
+                                                    uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+    const int tt = threadIdx.x >> 6;
+    if (tt >= HD / 32) return;
+    attn_merge_wave<HD, false>(part, NS, Hq, scale_log2e, xhi, xlo, blockIdx.x, blockIdx.y, tt, threadIdx.x & 63);
 }
 
 // ------------------------------------------------------------------------------------------
