@@ -245,14 +245,15 @@ def main():
     # per-launch timing of the dominant kernel (weight-streaming GEMM) inside verify passes
     eng.debug_profile(True)
     n_prof = 3
-    g_ms = g_bytes = a_ms = a_bytes = 0.0
-    g_n = a_n = 0
+    g_ms = g_bytes = a_ms = a_bytes = p_ms = p_bytes = 0.0
+    g_n = a_n = p_n = 0
     for _ in range(n_prof):
         dr = eng.draft_block(k, T, di.SAMPLING_SEED)
         eng.synchronize()
         eng.debug_profile(True)   # drop the drafter's launches: keep verify only
         eng.verify_block(k, T, dr)
-        r0, r1 = eng.debug_profile_read(0), eng.debug_profile_read(1)
+        r0, r1, r2 = eng.debug_profile_read(0), eng.debug_profile_read(1), eng.debug_profile_read(2)
+        p_ms, p_n, p_bytes = p_ms + r2[0], p_n + r2[1], p_bytes + r2[2]
         g_ms, g_n, g_bytes = g_ms + r0[0], g_n + r0[1], g_bytes + r0[2]
         a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
         eng.accept_and_commit(k, T, di.SAMPLING_SEED)
@@ -262,8 +263,12 @@ def main():
     rho8, en8 = trunc_geom(k, k / 4)
     rho24, en24 = trunc_geom(k, 3 * k / 4)
     iter_ms = td + tv + ta
-    gemm_gbs = g_bytes / (g_ms * 1e-3) / 1e9
-    gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
+    if p_n:   # the verify pass ran as one persistent kernel: that kernel is the dominant one
+        g_ms, g_n, g_bytes = p_ms, p_n, p_bytes
+        gemm_label = "k_pass (persistent verify pass: all layers' GEMMs, block attention, LM head)"
+    else:
+        gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
+    gemm_gbs = g_bytes / max(g_ms * 1e-3, 1e-12) / 1e9
     if t.n_experts:   # grouped expert GEMMs touch a data-dependent set of experts: use the pass-level figure
         gemm_gbs = (wbytes + kvbytes) / (tv * 1e-3) / 1e9
         gemm_label = "verify pass, all kernels (expected distinct experts)"

@@ -158,12 +158,22 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_f
 
 /* Per-launch timing for the benchmark.  While enabled, every launch of the weight-streaming GEMM
  * (kernel_class 0) and of the block-attention kernel (kernel_class 1) is bracketed by HIP events
- * on the context's stream.  deer_debug_profile(c, on) waits for the stream, switches recording
- * and forgets earlier records; deer_debug_profile_read waits for the stream and returns, for one
- * class, the summed event time (ms), the number of launches, and their algorithmic bytes (weight
- * bytes of each GEMM; K and V rows visible to each attention launch). */
+ * on the context's stream, and so is every launch of the persistent pass kernel (kernel_class 2),
+ * which runs a whole pass of a dense model at batch 1.  deer_debug_profile(c, mode) waits for the
+ * stream, switches recording (0 off, 1 on, 2 on with every pass run as separate kernels so that
+ * classes 0 and 1 are populated) and forgets earlier records; deer_debug_profile_read waits for the
+ * stream and returns, for one class, the summed event time (ms), the number of launches, and their
+ * algorithmic bytes (weight bytes of each GEMM; K and V rows visible to each attention launch; both,
+ * over all layers and the LM head, for a pass kernel). */
 int deer_debug_profile(deer_ctx *c, int enable);
 int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes);
+
+/* Timeline of the persistent pass kernel (dense models at batch 1 run a whole pass as one kernel).
+ * Waits for the stream; if stamps_host is not NULL copies the stamps of the last recorded pass into it
+ * ([*blocks][*stamps_per_block] ticks of the 100 MHz device clock, two per phase of the pass: input ready,
+ * own work stored; 0 = not reached); then switches recording for the following passes on or off.
+ * Pass stamps_host = NULL first to learn the two sizes. */
+int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block);
 
 /* Current committed length j per sequence (host mirror). */
 int deer_get_lengths(const deer_ctx *c, int32_t *len_host);

@@ -17,7 +17,7 @@ STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACIT
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
-           "deer_debug_profile_read"]
+           "deer_debug_profile_read", "deer_debug_pass_timeline"]
 
 
 class DeerError(RuntimeError):
@@ -134,6 +134,7 @@ class DeerEngine:
         if rc:
             raise DeerError(rc, self.lib.deer_last_error(None).decode())
         self.ctx = ctx
+        self._timeline_on = False
         self.batch = 0
         self._draft = torch.zeros(max_batch * 32, dtype=torch.int32, device=self.device)
 
@@ -235,6 +236,22 @@ class DeerEngine:
         ms, n, by = C.c_double(), C.c_int64(), C.c_double()
         self._check(self.lib.deer_debug_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(by)))
         return ms.value, n.value, by.value
+
+    def debug_pass_timeline(self, enable, read=True):
+        """Stamps [blocks][stamps_per_block] (uint64 ticks of the 100 MHz device clock) of the last recorded
+        pass kernel, or None; then switches recording on or off for the following passes."""
+        nb, ns = C.c_int32(), C.c_int32()
+        fn = self.lib.deer_debug_pass_timeline
+        fn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        if not read:
+            self._check(fn(self.ctx, int(enable), None, C.byref(nb), C.byref(ns)))
+            self._timeline_on = bool(enable)
+            return None
+        self._check(fn(self.ctx, int(self._timeline_on), None, C.byref(nb), C.byref(ns)))
+        out = np.zeros((max(nb.value, 1), ns.value), dtype=np.uint64)
+        self._check(fn(self.ctx, int(enable), out.ctypes.data if nb.value > 0 else None, C.byref(nb), C.byref(ns)))
+        self._timeline_on = bool(enable)
+        return out if nb.value > 0 else None
 
     def get_lengths(self):
         out = np.zeros(self.batch, dtype=np.int32)

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libdeer.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "deer_api.hip")]
-HEADERS = [os.path.join(PKG_DIR, "csrc", "deer_kernels.hpp"), os.path.join(ROOT, "include", "deer.h")]
+HEADERS = [os.path.join(PKG_DIR, "csrc", "deer_kernels.hpp"), os.path.join(PKG_DIR, "csrc", "deer_pass.hpp"), os.path.join(ROOT, "include", "deer.h")]
 
 
 def hipcc_path() -> str:
@@ -23,6 +23,7 @@ def build_library(verbose: bool = False) -> str:
         # packed fp32 instructions are kept off for all device code
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
+        *os.environ.get("DEER_EXTRA_FLAGS", "").split(),
         "-o", LIB_PATH, *SOURCES,
     ]
     if verbose:

@@ -1,6 +1,7 @@
 // Host side of libdeer: context, buffer carving, call-order state machine, kernel launches.
 // The C ABI is declared in include/deer.h.  Nothing here allocates device memory.
 #include "deer_kernels.hpp"
+#include "deer_pass.hpp"
 
 #include <algorithm>
 #include <cmath>
@@ -20,6 +21,7 @@ namespace {
 
 thread_local std::string g_init_error;
 
+constexpr int PASS_MAX_BLOCKS = 512;   // workgroups of the persistent pass kernel (one per compute unit)
 constexpr int MAX_NS = 32;          // key-range splits of block attention
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
@@ -60,6 +62,10 @@ struct Work {   // carved from the workspace
     int *gemm_cnt = nullptr, *attn_cnt = nullptr;   // arrival counters, zero between kernels
     size_t cnt_bytes = 0; char *cnt_base = nullptr;
     double *theta[2] = {nullptr, nullptr};
+    // persistent pass kernel: per-layer activation fragments (dense models, two tiles) and its barrier words
+    uint4 *pass_x = nullptr; size_t pass_x_vecs = 0;
+    unsigned *pass_sync = nullptr;
+    unsigned long long *pass_stamps = nullptr;   // [PASS_MAX_BLOCKS][PASS_STAMPS], written on request
     size_t bytes = 0;
 };
 
@@ -80,6 +86,11 @@ struct deer_ctx {
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
     std::string err;
+    // persistent pass kernel
+    int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
+    bool pass_used = false;          // a pass kernel has run since the error flag was last read
+    bool pass_stamps_on = false;     // deer_debug_pass_timeline: the next pass kernels record their timeline
+    bool prof_split = false;         // deer_debug_profile(2): time per operation (separate kernels)
     // optional per-launch timing (deer_debug_profile)
     bool prof_on = false;
     struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
@@ -228,6 +239,14 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
         w.attn_cnt = w.gemm_cnt ? w.gemm_cnt + ng : nullptr;
         w.cnt_bytes = (ng + na) * 4;
     }
+    for (const deer_model_cfg *mc : {&t, &d}) {
+        if (mc->n_experts) continue;
+        const size_t v = (size_t)(mc->n_layers + 1) * pass_x_layer_vecs(mc->d_model, mc->n_q_heads * mc->head_dim, mc->d_ff, 2);
+        w.pass_x_vecs = std::max(w.pass_x_vecs, v);
+    }
+    w.pass_x = (uint4 *)take(w.pass_x_vecs * 16);
+    w.pass_sync = (unsigned *)take(PASS_SYNC_WORDS * 4);
+    w.pass_stamps = (unsigned long long *)take((size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8);
     w.bytes = off;
 }
 
@@ -299,12 +318,132 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     return DEER_OK;
 }
 
+__global__ void k_pass_reset(unsigned *sync) {   // arrival counter and release flags back to zero; the error flag stays
+    if (threadIdx.x <= PASS_NF) sync[threadIdx.x * PASS_SYNC_STRIDE] = 0u;
+}
+
+// K splits of a GEMM phase of the persistent kernel: as many equal items as fit the resident workgroups.
+int pass_split(int N, int KS, int nb, int max_items_per_block) {
+    const int ncg = N / CG;
+    int S = std::max(1, nb * max_items_per_block / ncg);
+    S = std::min(S, std::max(1, KS / 16));               // at least 2 k-steps per wave
+    S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
+    return std::max(S, 1);
+}
+
+template <int HD, int MT>
+hipError_t launch_pass(const PassArgs &pa, int blocks, hipStream_t s) {
+    void *args[] = {(void *)&pa};
+    return hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_pass<HD, MT>), dim3(blocks), dim3(512), args, 0, s);
+}
+
+template <int HD, int MT>
+int pass_occupancy() {
+    int per_cu = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_pass<HD, MT>, 512, 0) != hipSuccess) return 0;
+    return per_cu;
+}
+
+bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
+    static const bool enabled = !(getenv("DEER_PERSISTENT") && atoi(getenv("DEER_PERSISTENT")) == 0);
+    if (!enabled || c->pass_blocks < 1 || c->prof_split) return false;
+    if (m.c.n_experts || ntiles > 2 || (lm.on && lm.n_tiles != 1)) return false;
+    // the QKV phase gives every workgroup at most one item (its tail does not request the next item's weights)
+    return m.n_qkv / CG <= c->pass_blocks;
+}
+
+// The same pass as run_pass, as one cooperative launch (dense model, at most two tiles).
+int run_pass_persistent(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total) {
+    ModelRT &m = c->m[model];
+    Work &w = c->wk;
+    const deer_model_cfg &mc = m.c;
+    const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG, nb = c->pass_blocks;
+    hipStream_t s = c->stream;
+    PassArgs pa{};
+    pa.L = mc.n_layers; pa.d = d; pa.Hq = mc.n_q_heads; pa.Hkv = mc.n_kv_heads; pa.hd = hd; pa.F = m.F; pa.V = mc.vocab;
+    pa.n_qkv = m.n_qkv; pa.kattn = m.kattn; pa.eps = mc.rms_eps;
+    pa.lw0 = m.w + m.off_layers; pa.layer_bytes = m.layer_bytes;
+    pa.lo_qkv = m.lo_qkv; pa.lo_o = m.lo_o; pa.lo_gu = m.lo_gu; pa.lo_d = m.lo_d;
+    pa.w_lm = m.w + m.off_lm;
+    pa.kv_k = m.kv + m.kv_k_base; pa.kv_v = m.kv + m.kv_v_base;
+    pa.kv_layer_stride = m.kv_layer_stride; pa.kv_seq_stride = m.kv_seq_stride; pa.kv_head_stride = m.kv_head_stride;
+    pa.max_seq = c->p.max_seq;
+    pa.rm = w.rm; pa.cs = w.cs; pa.h = w.h; pa.ssq = w.ssq; pa.part = w.part; pa.opart = w.opart; pa.counters = w.gemm_cnt;
+    pa.xbase = w.pass_x; pa.x_layer = pass_x_layer_vecs(d, m.kattn, m.F, ntiles);
+    pa.ntiles = ntiles;
+    pa.S_qkv = pass_split(m.n_qkv, d / 16, nb, 1);
+    pa.S_o = pass_split(d, m.kattn / 16, nb, 1);
+    pa.S_gu = pass_split(2 * m.F, d / 16, nb, 1);
+    pa.u_gu = 0;
+    {   // a wide gate/up matrix (more than half as many column groups as workgroups) is cut into equal
+        // consecutive shares instead; a column group then has at most (KS / u) + 2 pieces
+        static const bool stream_gu = !(getenv("DEER_PASS_GU_SHARES") && atoi(getenv("DEER_PASS_GU_SHARES")) == 0);
+        const int ncg = 2 * m.F / CG, KS = d / 16;
+        const int u = ((ncg * KS + nb - 1) / nb + 7) / 8 * 8;
+        const size_t max_np = (size_t)KS / u + 2;
+        if (stream_gu && ncg > nb / 2 && u >= 16 && max_np * 2 * m.F <= PART_COLS) pa.u_gu = u;
+    }
+    pa.S_d = pass_split(d, m.F / 16, nb, 1);
+    const int nkt = (max_limit + 31) / 32;
+    static const int ns_target = getenv("DEER_PASS_ATTN_ITEMS") ? atoi(getenv("DEER_PASS_ATTN_ITEMS")) : 256;
+    int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
+    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
+    pa.NS = NS;
+    pa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
+    pa.lm_on = lm.on ? 1 : 0; pa.lm_mt0 = lm.mt0; pa.lm_stride = lm.mt_stride; pa.lm_tiles = lm.n_tiles; pa.k = lm.k;
+    pa.T = lm.T; pa.seed = lm.seed;
+    pa.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
+    pa.stat = w.stat; pa.res = w.res[model];
+    pa.sync = w.pass_sync; pa.spin_limit = 200000u;
+    pa.stamps = c->pass_stamps_on ? w.pass_stamps : nullptr;
+
+    // layer 0's input fragments, RoPE table, barrier counters
+    hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
+                       w.pass_x, w.pass_x + (size_t)ntiles * plane_vecs(d), w.ssq, d, ncg_d);
+    LAUNCHCHK(c, "k_embed");
+    {
+        int n = rows * (hd / 2);
+        hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, w.rm.pos, m.theta, w.cs, hd / 2, rows);
+        LAUNCHCHK(c, "k_rope_table");
+    }
+    hipLaunchKernelGGL(k_pass_reset, dim3(1), dim3(64), 0, s, w.pass_sync);
+    LAUNCHCHK(c, "k_pass_reset");
+    double bytes = (double)mc.n_layers * ((double)m.n_qkv * d + (double)m.kattn * d + 3.0 * m.F * d) * 2.0 +
+                   (lm.on ? (double)mc.vocab * d * 2.0 : 0.0) +
+                   (double)mc.n_layers * kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;
+    hipError_t e;
+    {
+        ProfScope ps(c, 2, bytes);
+        if (hd == 128) e = ntiles == 1 ? launch_pass<128, 1>(pa, nb, s) : launch_pass<128, 2>(pa, nb, s);
+        else if (hd == 64) e = ntiles == 1 ? launch_pass<64, 1>(pa, nb, s) : launch_pass<64, 2>(pa, nb, s);
+        else e = ntiles == 1 ? launch_pass<32, 1>(pa, nb, s) : launch_pass<32, 2>(pa, nb, s);
+    }
+    if (e != hipSuccess) return fail(c, DEER_EHIP, "cooperative launch of the pass kernel: %s", hipGetErrorString(e));
+    c->pass_used = true;
+    return DEER_OK;
+}
+
+// After a stream synchronisation: did a pass kernel give up waiting at its grid barrier?
+int check_pass_error(deer_ctx *c) {
+    if (!c->pass_used) return DEER_OK;
+    unsigned flag = 0;
+    HIPCHK(c, hipMemcpyAsync(&flag, c->wk.pass_sync + pass_err_word(), 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->pass_used = false;
+    if (flag) {
+        (void)hipMemsetAsync(c->wk.pass_sync + pass_err_word(), 0, 4, c->stream);
+        return fail(c, DEER_EHIP, "the pass kernel's grid barrier timed out; results of the last pass are invalid");
+    }
+    return DEER_OK;
+}
+
 // One forward pass of `model` over the rows described by the row metadata (ntiles tiles).
 int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total = 0.0) {
     ModelRT &m = c->m[model];
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
     const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG;
+    if (pass_eligible(c, m, ntiles, lm)) return run_pass_persistent(c, model, ntiles, max_limit, lm, kv_keys_total);
     hipStream_t s = c->stream;
     hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
                        w.xa_hi, w.xa_lo, w.ssq, d, ncg_d);
@@ -483,8 +622,19 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
     }
     e = hipMemsetAsync(c->wk.cnt_base, 0, c->wk.cnt_bytes, c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
+    e = hipMemsetAsync(c->wk.pass_sync, 0, PASS_SYNC_WORDS * 4, c->stream);
+    if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e)); }
+    {   // the persistent pass kernel needs a cooperative launch with every workgroup resident
+        int coop = 0, cus = 0;
+        (void)hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, p->device);
+        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
+        int occ = std::min({pass_occupancy<128, 1>(), pass_occupancy<128, 2>(), pass_occupancy<64, 1>(), pass_occupancy<64, 2>(),
+                            pass_occupancy<32, 1>(), pass_occupancy<32, 2>()});
+        c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
+        (void)hipGetLastError();
+    }
     *out = c;
     return DEER_OK;
 }
@@ -567,6 +717,7 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
             }
         }
         HIPCHK(c, hipStreamSynchronize(c->stream));   // w.ids is reused by the next sequence
+        if (int rc = check_pass_error(c)) return rc;
         pend[b] = ids[off + n - 1];
         off += n;
     }
@@ -652,6 +803,7 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
     HIPCHK(c, hipMemcpyAsync(ncom, w.ao.n_committed, B * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(committed, w.ao.committed, (size_t)B * k * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (int rc = check_pass_error(c)) return rc;
     for (int b = 0; b < B; ++b) {
         c->h_len[b] += ncom[b];
         c->h_ing_n[b] = ncom[b];
@@ -680,6 +832,7 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
     if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
     HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (int rc = check_pass_error(c)) return rc;
     return DEER_OK;
 }
 
@@ -687,6 +840,7 @@ int deer_debug_profile(deer_ctx *c, int enable) {
     if (!c) return DEER_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prof_on = enable != 0;
+    c->prof_split = enable == 2;
     c->prof.clear();
     c->ev_used = 0;
     return DEER_OK;
@@ -702,6 +856,19 @@ int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int
         HIPCHK(c, hipEventElapsedTime(&ms, r.a, r.b));
         *total_ms += ms; *launches += 1; *bytes += r.bytes;
     }
+    return DEER_OK;
+}
+
+int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block) {
+    if (!c) return DEER_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (blocks) *blocks = c->pass_blocks;
+    if (stamps_per_block) *stamps_per_block = PASS_STAMPS;
+    if (stamps_host && c->pass_blocks > 0)
+        HIPCHK(c, hipMemcpy(stamps_host, c->wk.pass_stamps, (size_t)c->pass_blocks * PASS_STAMPS * 8, hipMemcpyDeviceToHost));
+    if (enable && !c->pass_stamps_on)
+        HIPCHK(c, hipMemsetAsync(c->wk.pass_stamps, 0, (size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8, c->stream));
+    c->pass_stamps_on = enable != 0;
     return DEER_OK;
 }
 

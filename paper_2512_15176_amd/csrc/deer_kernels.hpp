@@ -87,6 +87,15 @@ template <int N>
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void tie(u32x4 &r) { asm volatile("" : "+v"(r)); }
 
+// The thread index as a value the optimiser cannot trace back to the hardware register.  Lane-dependent
+// indices and addresses derived from it are recomputed where they are used instead of being hoisted to the
+// top of a long kernel and kept in registers (or spilled) across all of its phases.
+__device__ __forceinline__ int opaque_tid() {
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
 // Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
 __device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -123,7 +132,9 @@ __device__ __forceinline__ float2 ld_agent2(const float *p) {
 // Called by every thread after its partial stores: waits for them, then one thread counts the block
 // in.  Returns true in every thread of the block that arrived last (counter reset for the next use).
 __device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // drains this thread's stores
+    // The thread's agent-scope stores must have been performed before the block is counted in.  A
+    // workgroup-scope fence does not wait for vector memory, so the wait is explicit.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         int old = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -381,21 +392,23 @@ struct GemmArgs {
 // rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
 template <bool COH>
 __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int grow0, int ncg, int d, float eps) {
-    if (threadIdx.x < 32) {
-        const float *p = ssq + (size_t)(grow0 + threadIdx.x) * ncg;
+    const int tidx = opaque_tid();
+    if (tidx < 32) {
+        const float *p = ssq + (size_t)(grow0 + tidx) * ncg;
         float s = 0.f;
         for (int g = 0; g < ncg; ++g) s += ldf<COH>(p + g);
-        rstd[threadIdx.x] = rsqrtf(s / (float)d + eps);
+        rstd[tidx] = rsqrtf(s / (float)d + eps);
     }
 }
 
 // QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
 template <bool COH>
 __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
+    const int tidx = opaque_tid();
     const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
     const int half_hd = hd >> 1;
     const int b = a.rm.tile_seq[t];
-    for (int item = threadIdx.x; item < 512; item += blockDim.x) {
+    for (int item = tidx; item < 512; item += blockDim.x) {
         const int row = item & 31, oct = item >> 5;
         const int grow = t * 32 + row;
         const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
@@ -443,19 +456,21 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
 // loaded by resid_prefetch() before the tile was ready.  `tile` is overwritten with the new h values.
 template <bool COH>
 __device__ __forceinline__ void resid_prefetch(const GemmArgs &a, float (&hreg)[8], int cg, int t) {
+    const int tidx = opaque_tid();
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int e = threadIdx.x + 512 * i;
+        const int e = tidx + 512 * i;
         hreg[i] = ldf<COH>(a.h + (size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127));
     }
 }
 
 template <bool COH>
 __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float *scratch, const float (&hreg)[8], int cg, int t) {
+    const int tidx = opaque_tid();
     const int N = a.N;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int e = threadIdx.x + 512 * i;
+        const int e = tidx + 512 * i;
         const int row = e >> 7, col = e & 127;
         const float v = hreg[i] + tile[row * RED_STRIDE + col];
         stf<COH>(a.h + (size_t)(t * 32 + row) * N + cg * CG + col, v);
@@ -463,7 +478,7 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
     }
     __syncthreads();
     {   // 512 (row, octet) items, one per thread; lanes l and l^32 of a wave hold two octets of the same row
-        const int row = threadIdx.x & 31, oct = threadIdx.x >> 5;
+        const int row = tidx & 31, oct = tidx >> 5;
         const float *tp = tile + row * RED_STRIDE + oct * 8;
         uint4 hi, lo;
         pack8_split(tp, hi, lo);
@@ -474,21 +489,22 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss += tp[e] * tp[e];
         ss += __shfl_xor(ss, 32);
-        if ((threadIdx.x & 63) < 32) scratch[(threadIdx.x >> 6) * 32 + row] = ss;   // [8 waves][32 rows]
+        if ((tidx & 63) < 32) scratch[(tidx >> 6) * 32 + row] = ss;   // [8 waves][32 rows]
     }
     __syncthreads();
-    if (threadIdx.x < 32) {
+    if (tidx < 32) {
         float s2 = 0.f;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) s2 += scratch[w * 32 + threadIdx.x];   // fixed order
-        stf<COH>(a.ssq_out + (size_t)(t * 32 + threadIdx.x) * (N / CG) + cg, s2);
+        for (int w = 0; w < 8; ++w) s2 += scratch[w * 32 + tidx];   // fixed order
+        stf<COH>(a.ssq_out + (size_t)(t * 32 + tidx) * (N / CG) + cg, s2);
     }
 }
 
 // gate/up epilogue: group = 64 gate + 64 up channels -> SiLU(g) * u, fragment planes over F
 template <bool COH>
 __device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
-    for (int item = threadIdx.x; item < 256; item += blockDim.x) {
+    const int tidx = opaque_tid();
+    for (int item = tidx; item < 256; item += blockDim.x) {
         const int row = item & 31, oct = item >> 5;   // 8 octets of 8 channels
         float v[8];
 #pragma unroll
@@ -509,10 +525,11 @@ __device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile,
 // LM rows are the first k rows of the tile; lm_row = ct*k + i.
 template <bool COH>
 __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile, const float *rstd, int cg, int ct, int t) {
-    if (threadIdx.x >= 256) return;
+    const int tidx = opaque_tid();
+    if (tidx >= 256) return;
     const int V = a.N, k = a.k;
     const float T = a.T;
-    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;   // 8 threads per row, 16 columns each
+    const int row = tidx >> 3, sub = tidx & 7;   // 8 threads per row, 16 columns each
     const bool live = row < k;
     float m = -INFINITY, gm = -INFINITY, se = 0.f;
     int idx = 0x7fffffff, gidx = 0x7fffffff;
@@ -558,8 +575,9 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
 // router epilogue: logits over the experts -> softmax -> top_k (lowest index on ties) -> weights
 // renormalised to sum 1.  8 threads per row, 16 experts each.
 __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile, const float *rstd, int t) {
-    if (threadIdx.x >= 256) return;
-    const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;
+    const int tidx = opaque_tid();
+    if (tidx >= 256) return;
+    const int row = tidx >> 3, sub = tidx & 7;
     const int grow = t * 32 + row;
     float z[16];
     float m = -INFINITY;
@@ -616,60 +634,40 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, flo
     else epi_lmhead<COH>(a, tile, rstd, cg, ct, t);
 }
 
-// Sum of the 8 waves' accumulators (one 32 x 128 tile each, MFMA register layout) in a fixed order,
-// result as a row-major tile (stride RED_STRIDE) in `tile`.
-// Round A: waves 4..7 park their registers in LDS as 16-byte vectors in register order (conflict-free),
-// waves 0..3 add them (w += w+4).  Round B: waves 1..3 park, wave 0 adds them in order 1, 2, 3 and
-// writes the tile.  `red` holds 4 * 4096 floats.  Ends with a barrier.
+// Sum of the 8 waves' accumulators (one 32 x 128 tile each, MFMA register layout) in the fixed order
+// w = 0..7, result as a row-major tile (stride RED_STRIDE) in `tile`.
+// Every wave parks its 16 register quads in LDS as 16-byte vectors [wave][quad][lane] (conflict-free);
+// after one barrier wave w sums quads w and w + 8 over the eight copies (16 independent reads in
+// flight per lane) and writes its 8 rows x 64 columns of the tile.  `red` holds 8 * 4096 floats.
+// Ends with a barrier.
 __device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *red, float *tile, int w, int lane) {
     float4 *red4 = (float4 *)red;
-    if (w >= 4) {
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+    for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                red4[((w - 4) * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-    }
+        for (int q = 0; q < 4; ++q)
+            red4[(w * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
     __syncthreads();
-    if (w < 4) {
+    const int half = lane >> 5, cl = lane & 31;
+    float4 v[2][8];
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = red4[(w * 16 + nb * 4 + q) * 64 + lane];
-                acc[nb][4 * q] += v.x; acc[nb][4 * q + 1] += v.y; acc[nb][4 * q + 2] += v.z; acc[nb][4 * q + 3] += v.w;
-            }
-    }
-    __syncthreads();
-    if (w >= 1 && w < 4) {
+        for (int ww = 0; ww < 8; ++ww) v[j][ww] = red4[(ww * 16 + w + 8 * j) * 64 + lane];
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+    for (int j = 0; j < 2; ++j) {
+        float4 sum = v[j][0];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                red4[((w - 1) * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-    }
-    __syncthreads();
-    if (w == 0) {
-        const int half = lane >> 5, cl = lane & 31;
-#pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float4 v = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-#pragma unroll
-                for (int ww = 0; ww < 3; ++ww) {
-                    const float4 u = red4[(ww * 16 + nb * 4 + q) * 64 + lane];
-                    v.x += u.x; v.y += u.y; v.z += u.z; v.w += u.w;
-                }
-                float *tp = tile + (8 * q + 4 * half) * RED_STRIDE + nb * 32 + cl;   // rows 8q + 4*half + 0..3
-                tp[0] = v.x; tp[RED_STRIDE] = v.y; tp[2 * RED_STRIDE] = v.z; tp[3 * RED_STRIDE] = v.w;
-            }
+        for (int ww = 1; ww < 8; ++ww) { sum.x += v[j][ww].x; sum.y += v[j][ww].y; sum.z += v[j][ww].z; sum.w += v[j][ww].w; }
+        const int slot = w + 8 * j, nb = slot >> 2, q = slot & 3;
+        float *tp = tile + (8 * q + 4 * half) * RED_STRIDE + nb * 32 + cl;   // rows 8q + 4*half + 0..3
+        tp[0] = sum.x; tp[RED_STRIDE] = sum.y; tp[2 * RED_STRIDE] = sum.z; tp[3 * RED_STRIDE] = sum.w;
     }
     __syncthreads();
 }
 
 struct GemmSmem {
-    float red[4 * 32 * 128];          // wave-reduction scratch (64 KB)
+    float red[8 * 32 * 128];          // wave-reduction scratch (128 KB)
     float tile[32 * RED_STRIDE];      // the finished 32 x 128 tile, row-major
     float rstd[32];
     int last;
@@ -678,6 +676,7 @@ struct GemmSmem {
 // Sums the S partial tiles of column group cg (row-tile group z) in order s = 0..S-1 and runs the epilogue.
 template <int MT, int EPI, bool COH>
 __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int cg, int z) {
+    const int tidx = opaque_tid();
     float *tile = sm.tile;
     const int N = a.N, S = a.S;
     float hreg[8];
@@ -691,7 +690,7 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
         float2 v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int e = threadIdx.x + 512 * i;
+            const int e = tidx + 512 * i;
             p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
             v[i] = make_float2(0.f, 0.f);
         }
@@ -710,7 +709,7 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int e = threadIdx.x + 512 * i;
+            const int e = tidx + 512 * i;
             float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
             tp[0] = v[i].x; tp[1] = v[i].y;
         }
@@ -724,8 +723,9 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
 // DEFER = true: the partial tile is left for a later gemm_finish (after a grid-wide barrier).
 template <int MT, int EPI, bool COH, bool DEFER>
 __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int cg, int s, int z, int ncg) {
+    const int tidx = opaque_tid();
     float *red = sm.red, *tile = sm.tile, *s_rstd = sm.rstd;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int w = tidx >> 6, lane = tidx & 63;
     const int N = a.N, KS = a.KS, S = a.S;
     const int slices = S * 8, sl = s * 8 + w;
     const int per = (KS + slices - 1) / slices;
@@ -800,7 +800,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
             float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const int e = threadIdx.x + 512 * i;
+                const int e = tidx + 512 * i;
                 const int row = e >> 6, c2 = (e & 63) * 2;
                 const float *tp = tile + row * RED_STRIDE + c2;
                 st_agent2(out + (size_t)row * N + c2, tp[0], tp[1]);
@@ -857,7 +857,7 @@ struct MoeArgs {
 // grid: x = column group, y = expert, z = chunk of 32 pairs.  Same streaming loop and wave tree as k_gemm.
 template <int MODE>
 __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
-    __shared__ float red[4 * 32 * 128];
+    __shared__ float red[8 * 32 * 128];
     __shared__ float tile[32 * RED_STRIDE];
     __shared__ float s_rstd[32];
     __shared__ int s_row[32], s_slot[32];
