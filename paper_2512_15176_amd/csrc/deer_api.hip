@@ -348,8 +348,8 @@ bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan
     static const bool enabled = !(getenv("DEER_PERSISTENT") && atoi(getenv("DEER_PERSISTENT")) == 0);
     if (!enabled || c->pass_blocks < 1 || c->prof_split) return false;
     if (m.c.n_experts || ntiles > 2 || (lm.on && lm.n_tiles != 1)) return false;
-    // the QKV phase gives every workgroup at most one item (its tail does not request the next item's weights)
-    return m.n_qkv / CG <= c->pass_blocks;
+    if (m.n_qkv / CG > c->pass_blocks) return false;
+    return m.c.d_model / CG <= 64;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
 }
 
 // The same pass as run_pass, as one cooperative launch (dense model, at most two tiles).

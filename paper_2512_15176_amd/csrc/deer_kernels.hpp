@@ -77,6 +77,14 @@ __device__ __forceinline__ f32x16 mfma32(u32x4 a, uint4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// A 16-byte load of data that is read exactly once per pass (weights, the prefix K/V rows): marked
+// non-temporal so that the stream does not push activations, partial sums and the kernel's own
+// instructions out of L2.
+__device__ __forceinline__ uint4 ld16_stream(const uint4 *p) {
+    const u32x4 v = __builtin_nontemporal_load((const u32x4 *)p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Hand-scheduled loads (used where the compiler's wait-count insertion would drain every outstanding
 // load at a loop header): the load is issued here and its result may only be read after wait_loads<N>()
 // (at most N younger loads still outstanding; loads return in order) followed by tie() on the register.
@@ -389,16 +397,18 @@ struct GemmArgs {
     int n_experts, top_k; int *route_e; float *route_w;
 };
 
-// rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS
+// rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS.  512 threads: 16 per
+// row, each sums the groups g = j, j + 16, .. in order, then a fixed butterfly over the 16 partial sums.
 template <bool COH>
 __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int grow0, int ncg, int d, float eps) {
     const int tidx = opaque_tid();
-    if (tidx < 32) {
-        const float *p = ssq + (size_t)(grow0 + tidx) * ncg;
-        float s = 0.f;
-        for (int g = 0; g < ncg; ++g) s += ldf<COH>(p + g);
-        rstd[tidx] = rsqrtf(s / (float)d + eps);
-    }
+    const int row = tidx >> 4, j = tidx & 15;
+    const float *p = ssq + (size_t)(grow0 + row) * ncg;
+    float s = 0.f;
+    for (int g = j; g < ncg; g += 16) s += ldf<COH>(p + g);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off);
+    if (j == 0) rstd[row] = rsqrtf(s / (float)d + eps);
 }
 
 // QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
@@ -618,12 +628,13 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
     }
 }
 
-template <int EPI, bool COH>
+// RSTD_READY: `rstd` already holds the tile's factors (tile_rstd ran before a barrier the caller has passed).
+template <int EPI, bool COH, bool RSTD_READY = false>
 __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, float *rstd, float *scratch,
                                              const float (&hreg)[8], int cg, int ct) {
     // caller has synchronised after filling `tile`
     const int t = a.mt0 + ct * a.mt_stride;
-    if (EPI != EPI_RESID) {
+    if (EPI != EPI_RESID && !RSTD_READY) {
         tile_rstd<COH>(a.ssq_in, rstd, t * 32, a.ncg_in, a.d_in, a.eps);
         __syncthreads();
     }
@@ -669,7 +680,7 @@ __device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *re
 struct GemmSmem {
     float red[8 * 32 * 128];          // wave-reduction scratch (128 KB)
     float tile[32 * RED_STRIDE];      // the finished 32 x 128 tile, row-major
-    float rstd[32];
+    float rstd[64];                   // RMSNorm factors of up to two row tiles
     int last;
 };
 
@@ -758,7 +769,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         int ks = ks0 + dd;
         if (ks < ks1) {
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)ks * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)ks * 64); }
         }
@@ -778,7 +789,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
                 int kn = ks + D;
                 if (kn < ks1) {
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)kn * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)kn * 64); }
                 }
@@ -901,7 +912,7 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
         int ks = ks0 + dd;
         if (ks < ks1) {
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
             xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
         }
     }
@@ -919,7 +930,7 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
                 int kn = ks + D;
                 if (kn < ks1) {
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
                     xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
                 }
             }

@@ -199,18 +199,43 @@ __device__ __forceinline__ void w_issue(uint4 (&wb)[D][4], const GemmDesc &g, co
     for (int dd = 0; dd < D; ++dd) {
         const int ks = min(ks0 + dd, g.KS - 1);
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+        for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
     }
+}
+
+// L2 prefetch of the k-steps that follow the D requested into registers: every lane requests one dword of a
+// distinct 128-byte line (64 lines = two k-steps of four column blocks per instruction) and never reads the
+// result.  The lines arrive in the L2 of this workgroup's XCD while the workgroup waits for the phase's
+// input.  The destination registers stay reserved until the wave has waited for all its vector memory
+// operations (touch_release).
+constexpr int PASS_TOUCH = 1;
+template <int D>
+__device__ __forceinline__ void w_touch(unsigned (&tr)[PASS_TOUCH], const GemmDesc &g, const Piece &pc, int w, int lane) {
+    int ks0, ks1;
+    wave_slice(pc, w, ks0, ks1);
+    const int c = lane >> 3;   // chunk of 1 KB: column block c & 3, k-step offset c >> 2
+#pragma unroll
+    for (int j = 0; j < PASS_TOUCH; ++j) {
+        const int ks = max(0, min(ks0 + D + 2 * j + (c >> 2), min(ks1, g.KS) - 1));
+        const char *q = (const char *)(g.W + ((size_t)(pc.cg * 4 + (c & 3)) * g.KS + ks) * 64) + (lane & 7) * 128;
+        asm volatile("global_load_dword %0, %1, off" : "=v"(tr[j]) : "v"(q) : "memory");
+    }
+}
+__device__ __forceinline__ void touch_release(unsigned (&tr)[PASS_TOUCH]) {
+    drain_vmem();
+#pragma unroll
+    for (int j = 0; j < PASS_TOUCH; ++j) asm volatile("" ::"v"(tr[j]));
 }
 
 // The GEMM code below exists once per kernel and serves every phase: the epilogue kind is a run-time
 // value.  (One copy per kind, as templates give, makes the kernel larger than the instruction cache, and
 // every phase of every layer then fetches its code from memory again.)
 __device__ __forceinline__ void pass_epilogue(int epi, const GemmArgs &a, GemmSmem &sm, const float (&hreg)[8], int cg, int ct) {
-    if (epi == EPI_QKV) run_epilogue<EPI_QKV, true>(a, sm.tile, sm.rstd, sm.red, hreg, cg, ct);
-    else if (epi == EPI_RESID) run_epilogue<EPI_RESID, true>(a, sm.tile, sm.rstd, sm.red, hreg, cg, ct);
-    else if (epi == EPI_SWIGLU) run_epilogue<EPI_SWIGLU, true>(a, sm.tile, sm.rstd, sm.red, hreg, cg, ct);
-    else run_epilogue<EPI_LMHEAD, true>(a, sm.tile, sm.rstd, sm.red, hreg, cg, ct);
+    float *rstd = sm.rstd + 32 * ct;   // filled at the start of the piece
+    if (epi == EPI_QKV) run_epilogue<EPI_QKV, true, true>(a, sm.tile, rstd, sm.red, hreg, cg, ct);
+    else if (epi == EPI_RESID) run_epilogue<EPI_RESID, true, true>(a, sm.tile, rstd, sm.red, hreg, cg, ct);
+    else if (epi == EPI_SWIGLU) run_epilogue<EPI_SWIGLU, true, true>(a, sm.tile, rstd, sm.red, hreg, cg, ct);
+    else run_epilogue<EPI_LMHEAD, true, true>(a, sm.tile, rstd, sm.red, hreg, cg, ct);
 }
 
 // Sums the S partial tiles of column group cg in order s = 0..S-1 and runs the epilogue (as gemm_finish).
@@ -268,6 +293,21 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
     const int N = a.N, KS = a.KS, S = pc.np, cg = pc.cg, s = pc.slot;
     int ks0, ks1;
     wave_slice(pc, w, ks0, ks1);
+    // The RMSNorm factors of the input rows only depend on the previous phase: their loads travel with the
+    // first activation loads instead of forming a round trip of their own in the epilogue.
+    // Requested here (at most 64 groups: 4 values per thread, 16 threads per row), summed after the k-loop.
+    float ssqv[MT][4];
+    if (epi != EPI_RESID) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const float *sp = a.ssq_in + (size_t)((a.mt0 + mt * a.mt_stride) * 32 + (tidx >> 4)) * a.ncg_in;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int gi = (tidx & 15) + 16 * i;
+                ssqv[mt][i] = ldf<true>(sp + min(gi, a.ncg_in - 1));
+            }
+        }
+    }
 
     f32x16 acc[MT][4];
 #pragma unroll
@@ -286,9 +326,11 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
         xh[mt] = a.Xhi + tl * KS * 64 + lane;
         xl[mt] = a.Xlo + tl * KS * 64 + lane;
     }
-    uint4 xhb[D][MT], xlb[D][MT];
+    // W fragments run D k-steps ahead (HBM latency), activation fragments DX k-steps ahead (L2 latency)
+    constexpr int DX = (D < 4) ? D : 4;
+    uint4 xhb[DX][MT], xlb[DX][MT];
 #pragma unroll
-    for (int dd = 0; dd < D; ++dd)
+    for (int dd = 0; dd < DX; ++dd)
         if (ks0 + dd < ks1) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)(ks0 + dd) * 64]; xlb[dd][mt] = xl[mt][(size_t)(ks0 + dd) * 64]; }
@@ -302,15 +344,17 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb) {
-                        acc[mt][nb] = mfma32(xhb[dd][mt], wb[dd][nb], acc[mt][nb]);
-                        acc[mt][nb] = mfma32(xlb[dd][mt], wb[dd][nb], acc[mt][nb]);
+                        acc[mt][nb] = mfma32(xhb[dd % DX][mt], wb[dd][nb], acc[mt][nb]);
+                        acc[mt][nb] = mfma32(xlb[dd % DX][mt], wb[dd][nb], acc[mt][nb]);
                     }
-                const int kn = ks + D;
+                const int kn = ks + D, kx = ks + DX;
                 if (kn < ks1) {
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
+                }
+                if (kx < ks1) {
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)kn * 64]; xlb[dd][mt] = xl[mt][(size_t)kn * 64]; }
+                    for (int mt = 0; mt < MT; ++mt) { xhb[dd % DX][mt] = xh[mt][(size_t)kx * 64]; xlb[dd % DX][mt] = xl[mt][(size_t)kx * 64]; }
                 }
             }
         }
@@ -318,8 +362,19 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
 
     fstamp(p, ftag + 1);
 
-    __syncthreads();   // the previous item's epilogue has finished with the tile and reduction scratch
+    __syncthreads();   // the previous piece's epilogue has finished with the tile, the scratch and sm.rstd
     fstamp(p, ftag + 5);
+    if (epi != EPI_RESID) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float sq = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sq += ((tidx & 15) + 16 * i < a.ncg_in) ? ssqv[mt][i] : 0.f;
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) sq += __shfl_xor(sq, off);
+            if ((tidx & 15) == 0) sm.rstd[32 * mt + (tidx >> 4)] = rsqrtf(sq / (float)a.d_in + a.eps);
+        }
+    }
     float hreg[8];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -351,20 +406,36 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
     }
 }
 
-// ---- block attention item for a 4-wave group -------------------------------------------------------
-// Same mathematics and MFMA layouts as attn_group, arranged for two waves per SIMD (256 registers):
-// Q fragments sit in the wave's LDS slice, and K and V fragments use one buffer each, refilled as soon as
-// the contraction that reads them has been issued (K of the next tile travels during softmax and P V,
-// V of the next tile during the next tile's K Q^T); the second wave of the SIMD fills the remaining gaps.
+// ---- block attention item for a whole workgroup ---------------------------------------------------------
+// Same mathematics and MFMA layouts as attn_group (S^T = K Q^T, O^T = V^T P^T, permuted key order, online
+// softmax in fp32, Q and P as (hi, lo) bf16 pairs), arranged for the persistent kernel:
+//  - one (tile, kv head, key-range split) item per workgroup; wave w serves query head (w & 3) of the GQA
+//    group on the tiles of parity (w >> 2) of each staged chunk, so two waves per SIMD overlap each other;
+//  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested all at once by the eight waves
+//    (one memory round trip per chunk, every fragment fetched once per workgroup instead of once per query
+//    head) and staged in LDS in fragment order; Q fragments stay in registers;
+//  - the two key parities of a head are combined through LDS, then the result goes to the output
+//    projection's input (NS == 1) or to an un-normalised partial (M, L, O) for the merge phase.
+constexpr int ATT_CH = 4;   // tiles per staged chunk
+struct AttnSmem {
+    uint4 kv[ATT_CH * 16 * 64];   // [tile][fragment: K k-steps, then V (tile, half) pairs][lane]; 64 KB at head_dim 128
+    uint4 q[4 * 16 * 64];         // Q fragments of the 4 heads of a round: [head][hi k-steps | lo k-steps][lane]
+    float2 ml[4 * 64];            // parked (m, l) of the odd-parity waves
+};
+
 template <int HD>
-__device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
+__device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
                                           int max_seq, const int *__restrict__ tile_seq,
                                           const int *__restrict__ row_limit, float *part, int Hq, int Hkv, int NS,
-                                          float scale_log2e, uint4 *xhi, uint4 *xlo, uint4 *qs, int kvh, int split, int t,
-                                          int w, int lane) {
-    constexpr int KSQ = HD / 16, HT = HD / 32;
+                                          float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t) {
+    constexpr int KSQ = HD / 16, HT = HD / 32, FPT = KSQ + 2 * HT;   // fragments per tile
+    constexpr int LPW = ATT_CH * FPT / 8;                            // staging loads per wave and chunk
     constexpr int PF = AttnPartial<HD>::FLOATS;
+    fstamp(p, 45);
+    const int tidx = opaque_tid();
+    const int w = tidx >> 6, lane = tidx & 63;
+    const int g = w & 3, par = w >> 2;
     const int G = Hq / Hkv;
     const int half = lane >> 5, qrow = lane & 31;
     const int b = tile_seq[t];
@@ -380,117 +451,222 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
     const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
     const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
-    const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);
+    const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);   // operand row -> key
 
-    for (int g = w; g < G; g += 4) {
-        const int head = kvh * G + g;
-        {
+    for (int g0 = 0; g0 < G; g0 += 4) {
+        const bool active = g0 + g < G;
+        const int head = kvh * G + min(g0 + g, G - 1);
+        // Q fragments of the wave's head: the even-parity wave requests them and passes a copy to the odd-parity
+        // wave through LDS (a workgroup's load rate is the scarce resource of this phase).
+        uint4 qh[KSQ], ql[KSQ];
+        if (par == 0) {
             const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) { qs[s * 64 + lane] = Qhi[qb + (size_t)s * 64]; qs[(KSQ + s) * 64 + lane] = Qlo[qb + (size_t)s * 64]; }
+            for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
         }
+        bool q_shared = false;
         f32x16 oacc[HT];
 #pragma unroll
         for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
-        u32x4 kf[KSQ], vf[HT][2];
-        auto load_k = [&](int kt) {
-            const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
+        fstamp(p, 46);
+
+        for (int c0 = kt0; c0 < kt1; c0 += ATT_CH) {
+            const int ntile = min(ATT_CH, kt1 - c0);
+            fstamp(p, 47);
+            __syncthreads();   // the previous chunk (or head round, or item) has been read
+            fstamp(p, 40);
+            {   // stage: fragment f = w + 8 * i of the chunk; tiles past the range repeat the last one (unused)
+                uint4 st[LPW];
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) load16_async(kf[s], kp + s * 16);
-        };
-        auto load_v = [&](int kt) {
+                for (int i = 0; i < LPW; ++i) {
+                    const int f = w + 8 * i, tl = f / FPT, fi = f % FPT;
+                    const int kt = c0 + min(tl, ntile - 1);
+                    const uint16_t *src;
+                    if (fi < KSQ) src = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8 + fi * 16;
+                    else src = Vp + (size_t)(((fi - KSQ) >> 1) * 32 + qrow) * max_seq + kt * 32 + 16 * half + 8 * ((fi - KSQ) & 1);
+                    st[i] = ld16_stream((const uint4 *)src);
+                }
 #pragma unroll
-            for (int tt = 0; tt < HT; ++tt) {
-                const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
-                load16_async(vf[tt][0], vp);
-                load16_async(vf[tt][1], vp + 8);
+                for (int i = 0; i < LPW; ++i) as.kv[(w + 8 * i) * 64 + lane] = st[i];
+                if (!q_shared && par == 0) {
+#pragma unroll
+                    for (int s = 0; s < KSQ; ++s) { as.q[(g * 2 * KSQ + s) * 64 + lane] = qh[s]; as.q[(g * 2 * KSQ + KSQ + s) * 64 + lane] = ql[s]; }
+                }
             }
-        };
-        if (kt0 < kt1) {
-            const int last = kt1 - 1;   // the repeated request of the last tile is a cache hit and is not used
-            drain_vmem();               // only hand-counted loads are outstanding from here on
-            load_k(kt0);
-            load_v(kt0);
-            for (int kt = kt0; kt < kt1; ++kt) {
-                int qoff = lane;
-                asm volatile("" : "+v"(qoff));   // keeps the Q reads inside the loop (not hoisted into registers)
-                wait_loads<2 * HT>();            // K(kt) has arrived; V(kt) may still travel
+            __syncthreads();
+            if (!q_shared && par == 1) {
 #pragma unroll
-                for (int s = 0; s < KSQ; ++s) tie(kf[s]);
-                f32x16 sacc;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-                for (int s = 0; s < KSQ; ++s) {
-                    sacc = mfma32(kf[s], qs[s * 64 + qoff], sacc);
-                    sacc = mfma32(kf[s], qs[(KSQ + s) * 64 + qoff], sacc);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                load_k(min(kt + 1, last));
-                __builtin_amdgcn_sched_barrier(0);
-                const int key0 = kt * 32 + 16 * half;
-                if (kt * 32 + 32 > minlim) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (key0 + r >= lim) sacc[r] = -INFINITY;
-                }
-                float mx = sacc[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run, mx);
-                float pr[16];
-                if (m_new == -INFINITY) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) pr[r] = 0.f;
-                } else {
-                    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
-                    const float mb = m_new * scale_log2e;
-                    float ls = 0.f;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
-                    l_run = l_run * alpha + ls;
-                    m_run = m_new;
-                    if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {
-#pragma unroll
-                        for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
-                    }
-                }
-                uint4 ph[2], pl[2];
-                pack8_split(pr, ph[0], pl[0]);
-                pack8_split(pr + 8, ph[1], pl[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                wait_loads<KSQ>();               // V(kt) has arrived; K(kt+1) may still travel
-#pragma unroll
-                for (int tt = 0; tt < HT; ++tt) { tie(vf[tt][0]); tie(vf[tt][1]); }
-#pragma unroll
-                for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                    for (int s2 = 0; s2 < 2; ++s2) {
-                        oacc[tt] = mfma32(vf[tt][s2], ph[s2], oacc[tt]);
-                        oacc[tt] = mfma32(vf[tt][s2], pl[s2], oacc[tt]);
-                    }
-                __builtin_amdgcn_sched_barrier(0);
-                load_v(min(kt + 1, last));
-                __builtin_amdgcn_sched_barrier(0);
+                for (int s = 0; s < KSQ; ++s) { qh[s] = as.q[(g * 2 * KSQ + s) * 64 + lane]; ql[s] = as.q[(g * 2 * KSQ + KSQ + s) * 64 + lane]; }
             }
-            wait_loads<0>();
+            q_shared = true;
+            fstamp(p, 41);
+            if (active) {
+                for (int tl = par; tl < ntile; tl += 2) {
+                    const int kt = c0 + tl;
+                    const uint4 *fr = as.kv + (size_t)(tl * FPT) * 64 + lane;
+                    f32x16 sacc;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+                    for (int s = 0; s < KSQ; ++s) {
+                        const uint4 kf = fr[s * 64];
+                        sacc = mfma32(kf, qh[s], sacc);
+                        sacc = mfma32(kf, ql[s], sacc);
+                    }
+                    // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
+                    const int key0 = kt * 32 + 16 * half;
+                    if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (key0 + r >= lim) sacc[r] = -INFINITY;
+                    }
+                    float mx = sacc[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    const float m_new = fmaxf(m_run, mx);
+                    float pr[16];
+                    if (m_new == -INFINITY) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) pr[r] = 0.f;
+                    } else {
+                        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                        const float mb = m_new * scale_log2e;
+                        float ls = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
+                        l_run = l_run * alpha + ls;
+                        m_run = m_new;
+                        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+#pragma unroll
+                            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+                        }
+                    }
+                    uint4 ph[2], pl[2];
+                    pack8_split(pr, ph[0], pl[0]);
+                    pack8_split(pr + 8, ph[1], pl[1]);
+#pragma unroll
+                    for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
+                            oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
+                            oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+                        }
+                }
+            }
         }
-        const float l_tot = l_run + __shfl_xor(l_run, 32);
-        if (NS == 1) {
-            attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
-        } else {
-            float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+        // combine the two key parities of each head: odd-parity waves park (m, l, O), even-parity waves merge
+        fstamp(p, 42);
+        __syncthreads();
+        fstamp(p, 43);
+        float4 *ox = (float4 *)as.kv;
+        if (par == 1) {
+            as.ml[g * 64 + lane] = make_float2(m_run, l_run);
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-            if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
+                for (int q = 0; q < 4; ++q)
+                    ox[((g * HT + tt) * 4 + q) * 64 + lane] = make_float4(oacc[tt][4 * q], oacc[tt][4 * q + 1], oacc[tt][4 * q + 2], oacc[tt][4 * q + 3]);
+        }
+        __syncthreads();
+        if (par == 0 && active) {
+            const float2 o_ml = as.ml[g * 64 + lane];
+            const float M = fmaxf(m_run, o_ml.x);
+            const float f0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * scale_log2e);
+            const float f1 = (o_ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((o_ml.x - M) * scale_log2e);
+            l_run = f0 * l_run + f1 * o_ml.y;
+            m_run = M;
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = ox[((g * HT + tt) * 4 + q) * 64 + lane];
+                    oacc[tt][4 * q] = f0 * oacc[tt][4 * q] + f1 * v.x;
+                    oacc[tt][4 * q + 1] = f0 * oacc[tt][4 * q + 1] + f1 * v.y;
+                    oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
+                    oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
+                }
+            const float l_tot = l_run + __shfl_xor(l_run, 32);
+            if (NS == 1) {
+                attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
+            } else {
+                float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+#pragma unroll
+                for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                    for (int r2 = 0; r2 < 8; ++r2) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+                if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
+            }
+        }
+        fstamp(p, 44);
+    }
+}
+
+// Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
+// of O^T tile tt.  All (M, L) pairs are requested at once, then the partial outputs 16 splits at a time, so a
+// merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
+template <int HD>
+__device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
+                                                int head, int t, int tt, int hh, int lane) {
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    const int half = lane >> 5, qrow = lane & 31;
+    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
+    float f[32];
+    float M = -INFINITY, L = 0.f;
+    {
+        float2 ml[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) ml[s] = ld_agent2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            f[s] = (s >= NS || ml[s].x == -INFINITY) ? 0.f : exp2f((ml[s].x - M) * scale_log2e);
+            L += f[s] * ml[s].y;
+        }
+    }
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int s0 = 0; s0 < 32; s0 += 16) {
+        if (s0 < NS) {
+            float2 v[16][4];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+#pragma unroll
+                for (int r2 = 0; r2 < 4; ++r2)
+                    v[u][r2] = ld_agent2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2);
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+#pragma unroll
+                for (int r2 = 0; r2 < 4; ++r2) { o[2 * r2] += f[s0 + u] * v[u][r2].x; o[2 * r2 + 1] += f[s0 + u] * v[u][r2].y; }
+        }
+    }
+    // registers 8*hh .. 8*hh+7 of tile tt: octets q = 2*hh and 2*hh + 1 (see attn_write_frag)
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const int KS = Hq * HD / 16;
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+        const int q = 2 * hh + qq;
+        float mine[4], other[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = __shfl_xor(mine[e], 32); }
+        if ((q & 1) == half) {
+            float v8[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v8[e] = half ? other[e] : mine[e]; v8[4 + e] = half ? mine[e] : other[e]; }
+            uint4 hi, lo;
+            pack8_split(v8, hi, lo);
+            const size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
+            st16<true>(xhi + vec, hi);
+            st16<true>(xlo + vec, lo);
         }
     }
 }
@@ -540,7 +716,7 @@ __device__ __forceinline__ void rowstat_row(const RowStat *stat, int ncg_v, floa
 
 union PassSmem {
     GemmSmem g;
-    uint4 q[8 * 2 * 8 * 64];   // attention: [wave][hi | lo][k-step <= 8][lane]  (128 KB at head_dim 128)
+    AttnSmem at;
 };
 
 template <int MT, int D>
@@ -554,7 +730,10 @@ __device__ __forceinline__ void gemm_phase(const PassArgs &p, GemmArgs &a, int e
     PieceIter it = piece_begin(g);
     Piece pc = piece_valid(it) ? piece_at(g, it) : Piece{0, 0, min(g.KS, 8), 0, 1};
     w_issue<D>(wb, g, pc, w, lane);
+    unsigned touched[PASS_TOUCH];
+    w_touch<D>(touched, g, pc, w, lane);
     bar_wait(p, epoch);   // the phase's input is complete
+    touch_release(touched);
     stamp(p, ns);
     while (piece_valid(it)) {
         gemm_item<MT, D>(p, a, epi, sm, pc, wb);
@@ -569,9 +748,12 @@ template <int HD, int MT>
 __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
     __shared__ __attribute__((aligned(16))) PassSmem smem;
     GemmSmem &sm = smem.g;
-    constexpr int D = (MT == 1) ? 4 : 2;
+    constexpr int D = (MT == 1) ? 4 : 2;   // weight k-steps in flight per wave
     unsigned epoch = 0;
     int ns = 0;
+#ifdef DEER_PASS_FINE
+    if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)blockIdx.x * PASS_STAMPS + 500] = 1000 + (__builtin_amdgcn_s_getreg((4 - 1) << 11 | 20) & 15);
+#endif
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ntiles = p.ntiles, d = p.d, ncg_d = d / CG;
     GemmArgs base{};
@@ -614,27 +796,27 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
         gemm_phase<MT, D>(p, a, epi, sm, phase_desc(p, l, ph), epoch, ns);
         if (ph != 0 || l == p.L) continue;
 
-        // block attention: two 4-wave groups per workgroup, each on its own (tile, kv head, split) item
+        // block attention: one (tile, kv head, key-range split) item per workgroup at a time
         bar_wait(p, epoch);
         stamp(p, ns);
-        const int grp = w >> 2, n_items = ntiles * p.Hkv * p.NS;
-        uint4 *qs = smem.q + (size_t)w * (2 * 8 * 64);
-        for (int it = grp * gridDim.x + blockIdx.x; it < n_items; it += 2 * gridDim.x) {
+        const int n_items = ntiles * p.Hkv * p.NS;
+        for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
             const int kvh = it % p.Hkv, split = (it / p.Hkv) % p.NS, t = it / (p.Hkv * p.NS);
-            attn_item<HD>(x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, p.rm.tile_seq, p.rm.limit,
-                          p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, qs, kvh, split, t, w & 3, lane);
+            attn_item<HD>(p, x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, p.rm.tile_seq, p.rm.limit,
+                          p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t);
         }
         drain_vmem();
         stamp(p, ns);
         bar_arrive(p, epoch);
         if (p.NS > 1) {
             constexpr int HT = HD / 32;
-            const int n = ntiles * p.Hq * HT;
+            const int n = ntiles * p.Hq * HT * 2;
             bar_wait(p, epoch);
             stamp(p, ns);
-            for (int it = w * gridDim.x + blockIdx.x; it < n; it += 8 * gridDim.x)
-                attn_merge_wave<HD, true>(p.opart, p.NS, p.Hq, p.scale_log2e, x.x1h, x.x1l, (it / HT) % p.Hq,
-                                          it / (HT * p.Hq), it % HT, lane);
+            for (int it = w * gridDim.x + blockIdx.x; it < n; it += 8 * gridDim.x) {
+                const int hh = it & 1, tt = (it >> 1) % HT, head = (it / (2 * HT)) % p.Hq, t = it / (2 * HT * p.Hq);
+                attn_merge_item<HD>(p.opart, p.NS, p.Hq, p.scale_log2e, x.x1h, x.x1l, head, t, tt, hh, lane);
+            }
             drain_vmem();
             stamp(p, ns);
             bar_arrive(p, epoch);
