@@ -168,6 +168,12 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_f
 int deer_debug_profile(deer_ctx *c, int enable);
 int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes);
 
+/* How a forward pass is launched: 0 = one kernel per operation, 1 = one persistent kernel per pass wherever
+ * it applies (dense model, batch 1), 2 = chosen by model size (the default; the environment variable
+ * DEER_PERSISTENT sets the initial value).  Both paths compute the same pass; tests compare them.  Waits
+ * for the stream. */
+int deer_debug_pass_mode(deer_ctx *c, int mode);
+
 /* Timeline of the persistent pass kernel (dense models at batch 1 run a whole pass as one kernel).
  * Waits for the stream; if stamps_host is not NULL copies the stamps of the last recorded pass into it
  * ([*blocks][*stamps_per_block] ticks of the 100 MHz device clock, two per phase of the pass: input ready,

@@ -17,7 +17,7 @@ STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACIT
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
-           "deer_debug_profile_read", "deer_debug_pass_timeline"]
+           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode"]
 
 
 class DeerError(RuntimeError):
@@ -236,6 +236,11 @@ class DeerEngine:
         ms, n, by = C.c_double(), C.c_int64(), C.c_double()
         self._check(self.lib.deer_debug_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(by)))
         return ms.value, n.value, by.value
+
+    def debug_pass_mode(self, mode):
+        """0: one kernel per operation; 1: persistent pass kernel wherever it applies; 2: by model size."""
+        self.lib.deer_debug_pass_mode.argtypes = [C.c_void_p, C.c_int]
+        self._check(self.lib.deer_debug_pass_mode(self.ctx, int(mode)))
 
     def debug_pass_timeline(self, enable, read=True):
         """Stamps [blocks][stamps_per_block] (uint64 ticks of the 100 MHz device clock) of the last recorded

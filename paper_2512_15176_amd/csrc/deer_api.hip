@@ -88,6 +88,7 @@ struct deer_ctx {
     std::string err;
     // persistent pass kernel
     int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
+    int pass_mode = 2;               // 0: one kernel per operation, 1: persistent kernel where possible, 2: by model size
     bool pass_used = false;          // a pass kernel has run since the error flag was last read
     bool pass_stamps_on = false;     // deer_debug_pass_timeline: the next pass kernels record their timeline
     bool prof_split = false;         // deer_debug_profile(2): time per operation (separate kernels)
@@ -320,15 +321,7 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
 
 __global__ void k_pass_reset(unsigned *sync) {   // arrival counter and release flags back to zero; the error flag stays
     if (threadIdx.x <= PASS_NF) sync[threadIdx.x * PASS_SYNC_STRIDE] = 0u;
-}
-
-// K splits of a GEMM phase of the persistent kernel: as many equal items as fit the resident workgroups.
-int pass_split(int N, int KS, int nb, int max_items_per_block) {
-    const int ncg = N / CG;
-    int S = std::max(1, nb * max_items_per_block / ncg);
-    S = std::min(S, std::max(1, KS / 16));               // at least 2 k-steps per wave
-    S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
-    return std::max(S, 1);
+    if (threadIdx.x == 0) sync[pass_xcd_word()] = 0u;
 }
 
 template <int HD, int MT>
@@ -344,12 +337,16 @@ int pass_occupancy() {
     return per_cu;
 }
 
+// Which passes run as the persistent kernel.  Measured on MI355X (batch 1, k = 32, prefix 4096): an 8B-shaped
+// target pass takes 4.95 ms as one persistent kernel against 5.10 ms as one kernel per operation; the 0.5B
+// drafter (30 MB of weights per layer, latency-bound) takes 2.84 ms against 2.77 ms.  mode 2 (the default)
+// therefore picks the persistent kernel for layers of at least 128 MB; 0 and 1 force either path.
 bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
-    static const bool enabled = !(getenv("DEER_PERSISTENT") && atoi(getenv("DEER_PERSISTENT")) == 0);
-    if (!enabled || c->pass_blocks < 1 || c->prof_split) return false;
+    if (c->pass_mode == 0 || c->pass_blocks < 1 || c->prof_split) return false;
     if (m.c.n_experts || ntiles > 2 || (lm.on && lm.n_tiles != 1)) return false;
-    if (m.n_qkv / CG > c->pass_blocks) return false;
-    return m.c.d_model / CG <= 64;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
+    if (m.c.d_model / CG > 64) return false;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
+    if (c->pass_mode == 1) return true;
+    return m.layer_bytes >= ((size_t)128 << 20);
 }
 
 // The same pass as run_pass, as one cooperative launch (dense model, at most two tiles).
@@ -370,20 +367,31 @@ int run_pass_persistent(deer_ctx *c, int model, int ntiles, int max_limit, const
     pa.max_seq = c->p.max_seq;
     pa.rm = w.rm; pa.cs = w.cs; pa.h = w.h; pa.ssq = w.ssq; pa.part = w.part; pa.opart = w.opart; pa.counters = w.gemm_cnt;
     pa.xbase = w.pass_x; pa.x_layer = pass_x_layer_vecs(d, m.kattn, m.F, ntiles);
-    pa.ntiles = ntiles;
-    pa.S_qkv = pass_split(m.n_qkv, d / 16, nb, 1);
-    pa.S_o = pass_split(d, m.kattn / 16, nb, 1);
-    pa.S_gu = pass_split(2 * m.F, d / 16, nb, 1);
-    pa.u_gu = 0;
+    pa.ntiles = ntiles; pa.nb = nb;
+    // K splits: as many as give every workgroup of a group (an XCD: an eighth of the grid) one piece
+    auto split = [&](int N, int KS) {
+        const int ncgl = (N / CG + 7) / 8;
+        int S = std::max(1, (nb / 8) / ncgl);
+        S = std::min(S, std::max(1, KS / 16));               // at least 2 k-steps per wave
+        S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
+        return std::max(S, 1);
+    };
+    pa.S_qkv = split(m.n_qkv, d / 16);
+    pa.S_o = split(d, m.kattn / 16);
+    pa.S_gu = split(2 * m.F, d / 16);
+    pa.S_d = split(d, m.F / 16);
     {   // a wide gate/up matrix (more than half as many column groups as workgroups) is cut into equal
-        // consecutive shares instead; a column group then has at most (KS / u) + 2 pieces
+        // consecutive shares instead; a column group then has at most KS / u + 2 pieces
         static const bool stream_gu = !(getenv("DEER_PASS_GU_SHARES") && atoi(getenv("DEER_PASS_GU_SHARES")) == 0);
         const int ncg = 2 * m.F / CG, KS = d / 16;
-        const int u = ((ncg * KS + nb - 1) / nb + 7) / 8 * 8;
-        const size_t max_np = (size_t)KS / u + 2;
-        if (stream_gu && ncg > nb / 2 && u >= 16 && max_np * 2 * m.F <= PART_COLS) pa.u_gu = u;
+        const int u = (ncg * KS / nb) / 8 * 8;   // a lower bound of the share under either grouping
+        pa.stream_gu = (stream_gu && ncg > nb / 2 && u >= 16 && ((size_t)KS / u + 2) * 2 * m.F <= PART_COLS) ? 1 : 0;
     }
-    pa.S_d = pass_split(d, m.F / 16, nb, 1);
+    // bits: 1 split-K partials and counters, 2 residual stream, 4 attention partials
+    // Off by default: measured, the grouping by XCD gains nothing on the 8B target (4.95 ms either way) and
+    // costs the small drafter 0.45 ms (its few column groups and kv heads leave most XCDs without work).
+    static const int allow_near = getenv("DEER_PASS_XCD_LOCAL") ? atoi(getenv("DEER_PASS_XCD_LOCAL")) : 0;
+    pa.allow_near = allow_near;
     const int nkt = (max_limit + 31) / 32;
     static const int ns_target = getenv("DEER_PASS_ATTN_ITEMS") ? atoi(getenv("DEER_PASS_ATTN_ITEMS")) : 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
@@ -633,6 +641,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         int occ = std::min({pass_occupancy<128, 1>(), pass_occupancy<128, 2>(), pass_occupancy<64, 1>(), pass_occupancy<64, 2>(),
                             pass_occupancy<32, 1>(), pass_occupancy<32, 2>()});
         c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
+        if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = std::max(0, std::min(2, atoi(e)));
         (void)hipGetLastError();
     }
     *out = c;
@@ -869,6 +878,14 @@ int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int
     if (enable && !c->pass_stamps_on)
         HIPCHK(c, hipMemsetAsync(c->wk.pass_stamps, 0, (size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8, c->stream));
     c->pass_stamps_on = enable != 0;
+    return DEER_OK;
+}
+
+int deer_debug_pass_mode(deer_ctx *c, int mode) {
+    if (!c) return DEER_EINVAL;
+    if (mode < 0 || mode > 2) return fail(c, DEER_EINVAL, "pass mode must be 0, 1 or 2");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    c->pass_mode = mode;
     return DEER_OK;
 }
 

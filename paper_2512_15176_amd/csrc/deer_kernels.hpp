@@ -104,6 +104,14 @@ __device__ __forceinline__ int opaque_tid() {
     return t;
 }
 
+// Butterfly exchange with lane (lane ^ off).  The lane index is derived where it is used (see opaque_tid),
+// never from a value computed once at the top of the kernel; blocks are whole wavefronts, so the low six
+// bits of the thread index are the lane.
+__device__ __forceinline__ int shx(int v, int off) {
+    return __builtin_amdgcn_ds_bpermute(((opaque_tid() & 63) ^ off) << 2, v);
+}
+__device__ __forceinline__ float shx(float v, int off) { return __int_as_float(shx(__float_as_int(v), off)); }
+
 // Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
 __device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -137,9 +145,20 @@ __device__ __forceinline__ float2 ld_agent2(const float *p) {
     unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_float2(__uint_as_float((unsigned)(u & 0xffffffffu)), __uint_as_float((unsigned)(u >> 32)));
 }
+// The same exchange between workgroups that are known to sit on ONE XCD (the persistent pass kernel places
+// them).  Only the LOADS change: a workgroup-scope load skips the per-CU cache and is served by that XCD's
+// L2, where the agent-scope (write-through) stores of the other workgroups of the XCD have passed, instead
+// of going to memory.  Stores and counters stay agent-scope: the completion of a narrower-scope store does
+// not say that it has reached L2.  `near` selects the loads at run time.
+__device__ __forceinline__ float2 ld_near2(const float *p) {
+    unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return make_float2(__uint_as_float((unsigned)(u & 0xffffffffu)), __uint_as_float((unsigned)(u >> 32)));
+}
+__device__ __forceinline__ float2 ld_x2(const float *p, bool near) { return near ? ld_near2(p) : ld_agent2(p); }
+
 // Called by every thread after its partial stores: waits for them, then one thread counts the block
 // in.  Returns true in every thread of the block that arrived last (counter reset for the next use).
-__device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag) {
+__device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag, bool near = false) {
     // The thread's agent-scope stores must have been performed before the block is counted in.  A
     // workgroup-scope fence does not wait for vector memory, so the wait is explicit.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -151,6 +170,7 @@ __device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag)
         *s_flag = last;
     }
     __syncthreads();
+    if (near) asm volatile("buffer_inv sc0" ::: "memory");   // no older copy of the partials in this CU's cache
     return *s_flag != 0;
 }
 
@@ -389,6 +409,7 @@ struct GemmArgs {
     const float2 *cs; RowMeta rm; uint4 *qhi, *qlo; KvView kv; int Hq, Hkv, hd;
     // RESID: h += y, new fragments and sums of squares of h
     float *h; uint4 *xhi_out, *xlo_out; float *ssq_out;
+    int near, h_near;   // coherent mode only: split-K partials and arrival counters / h stay inside one XCD's L2
     // SWIGLU: activation fragments over F channels
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
@@ -407,7 +428,7 @@ __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int gro
     float s = 0.f;
     for (int g = j; g < ncg; g += 16) s += ldf<COH>(p + g);
 #pragma unroll
-    for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off);
+    for (int off = 1; off < 16; off <<= 1) s += shx(s, off);
     if (j == 0) rstd[row] = rsqrtf(s / (float)d + eps);
 }
 
@@ -418,7 +439,7 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
     const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
     const int half_hd = hd >> 1;
     const int b = a.rm.tile_seq[t];
-    for (int item = tidx; item < 512; item += blockDim.x) {
+    for (int item = tidx; item < 512; item += 512) {   // GEMM workgroups have 512 threads
         const int row = item & 31, oct = item >> 5;
         const int grow = t * 32 + row;
         const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
@@ -470,7 +491,8 @@ __device__ __forceinline__ void resid_prefetch(const GemmArgs &a, float (&hreg)[
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int e = tidx + 512 * i;
-        hreg[i] = ldf<COH>(a.h + (size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127));
+        const float *hp = a.h + (size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127);
+        hreg[i] = (COH && a.h_near) ? __hip_atomic_load(hp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : ldf<COH>(hp);
     }
 }
 
@@ -483,7 +505,8 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         const int e = tidx + 512 * i;
         const int row = e >> 7, col = e & 127;
         const float v = hreg[i] + tile[row * RED_STRIDE + col];
-        stf<COH>(a.h + (size_t)(t * 32 + row) * N + cg * CG + col, v);
+        float *hp = a.h + (size_t)(t * 32 + row) * N + cg * CG + col;
+        stf<COH>(hp, v);
         tile[row * RED_STRIDE + col] = v;
     }
     __syncthreads();
@@ -498,7 +521,7 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) ss += tp[e] * tp[e];
-        ss += __shfl_xor(ss, 32);
+        ss += shx(ss, 32);
         if ((tidx & 63) < 32) scratch[(tidx >> 6) * 32 + row] = ss;   // [8 waves][32 rows]
     }
     __syncthreads();
@@ -514,7 +537,7 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
 template <bool COH>
 __device__ __forceinline__ void epi_swiglu(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
     const int tidx = opaque_tid();
-    for (int item = tidx; item < 256; item += blockDim.x) {
+    for (int item = tidx; item < 256; item += 512) {
         const int row = item & 31, oct = item >> 5;   // 8 octets of 8 channels
         float v[8];
 #pragma unroll
@@ -565,9 +588,9 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
     }
 #pragma unroll
     for (int off = 1; off < 8; off <<= 1) {
-        float m2 = __shfl_xor(m, off); int i2 = __shfl_xor(idx, off);
+        float m2 = shx(m, off); int i2 = shx(idx, off);
         argmax_merge(m, idx, m2, i2);
-        float g2 = __shfl_xor(gm, off); int gi2 = __shfl_xor(gidx, off);
+        float g2 = shx(gm, off); int gi2 = shx(gidx, off);
         argmax_merge(gm, gidx, g2, gi2);
     }
     if (live && T > 0.f) {
@@ -575,7 +598,7 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
         for (int e = 0; e < 16; ++e) se += expf((z[e] - m) * invT);
     }
 #pragma unroll
-    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
+    for (int off = 1; off < 8; off <<= 1) se += shx(se, off);
     if (live && sub == 0) {
         RowStat *sp = a.stat + ((size_t)ct * k + row) * a.ncg_v + cg;
         stf<COH>(&sp->m, m); sti<COH>(&sp->idx, idx); stf<COH>(&sp->sumexp, se); stf<COH>(&sp->gm, gm); sti<COH>(&sp->gidx, gidx);
@@ -598,12 +621,12 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
         m = fmaxf(m, z[e]);
     }
 #pragma unroll
-    for (int off = 1; off < 8; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
+    for (int off = 1; off < 8; off <<= 1) m = fmaxf(m, shx(m, off));
     float se = 0.f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) { z[e] = expf(z[e] - m); se += z[e]; }   // exp(-inf) = 0 for padding
 #pragma unroll
-    for (int off = 1; off < 8; off <<= 1) se += __shfl_xor(se, off);
+    for (int off = 1; off < 8; off <<= 1) se += shx(se, off);
     float wsel[8]; int esel[8];
     float wsum = 0.f;
     for (int j = 0; j < a.top_k; ++j) {
@@ -612,7 +635,7 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
         for (int e = 0; e < 16; ++e) argmax_merge(bv, bi, z[e], sub * 16 + e);
 #pragma unroll
         for (int off = 1; off < 8; off <<= 1) {
-            float v2 = __shfl_xor(bv, off); int i2 = __shfl_xor(bi, off);
+            float v2 = shx(bv, off); int i2 = shx(bi, off);
             argmax_merge(bv, bi, v2, i2);
         }
 #pragma unroll
@@ -1105,7 +1128,7 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 mine[e] = o[ti][4 * q + e] * inv;
-                other[e] = __shfl_xor(mine[e], 32);
+                other[e] = shx(mine[e], 32);
             }
             // octet (tt, q): dims 32*tt + 8*q + 0..7 = half-0 lane's 4 values then half-1 lane's 4 values
             if ((q & 1) == half) {
@@ -1140,8 +1163,8 @@ __device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, c
     int maxlim = lim, minlim = lim;
 #pragma unroll
     for (int off = 1; off < 32; off <<= 1) {
-        maxlim = max(maxlim, __shfl_xor(maxlim, off));
-        minlim = min(minlim, __shfl_xor(minlim, off));
+        maxlim = max(maxlim, shx(maxlim, off));
+        minlim = min(minlim, shx(minlim, off));
     }
     const int nkt = (maxlim + 31) >> 5;
     const int per = (nkt + NS - 1) / NS;
@@ -1201,7 +1224,7 @@ __device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, c
             float mx = sacc[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = fmaxf(mx, shx(mx, 32));
             const float m_new = fmaxf(m_run, mx);
             float p[16];
             if (m_new == -INFINITY) {
@@ -1273,7 +1296,7 @@ __device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, c
             }
             wait_loads<0>();
         }
-        const float l_tot = l_run + __shfl_xor(l_run, 32);
+        const float l_tot = l_run + shx(l_run, 32);
         if (NS == 1) {
             attn_write_frag<HD, COH>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
         } else {

@@ -32,9 +32,10 @@ namespace deer {
 // queue the arrivals behind hundreds of polls of the same line), and the error flag.
 constexpr int PASS_NF = 8;
 constexpr int PASS_SYNC_STRIDE = 1024;                              // words
-constexpr int PASS_SYNC_WORDS = (PASS_NF + 2) * PASS_SYNC_STRIDE;
+constexpr int PASS_SYNC_WORDS = (PASS_NF + 3) * PASS_SYNC_STRIDE;
 __host__ __device__ __forceinline__ int pass_flag_word(int f) { return (1 + f) * PASS_SYNC_STRIDE; }
 __host__ __device__ __forceinline__ int pass_err_word() { return (1 + PASS_NF) * PASS_SYNC_STRIDE; }
+__host__ __device__ __forceinline__ int pass_xcd_word() { return (2 + PASS_NF) * PASS_SYNC_STRIDE; }   // placement check failed
 
 struct PassArgs {
     // model
@@ -48,8 +49,12 @@ struct PassArgs {
     float *h, *ssq, *part, *opart; int *counters;
     uint4 *xbase; size_t x_layer;     // per-layer activation fragments, (L + 1) layers of x_layer vectors
     // plan
+    int nb;                                  // workgroups of the launch (the kernel never reads the launch
+                                             // dimensions back from the dispatch arguments: that is a load from
+                                             // the argument segment each time, on the critical path of a barrier)
     int ntiles, S_qkv, S_o, S_gu, S_d, NS;   // S > 0: that many equal K splits per column group;
-    int u_gu;                                // > 0: the gate/up phase gives every workgroup u_gu consecutive k-steps instead
+    int stream_gu;                           // 1: the gate/up phase gives every workgroup an equal run of consecutive k-steps instead
+    int allow_near;                          // 1: exchange inside an XCD's L2 where the placement check allows it
     float scale_log2e;
     int lm_on, lm_mt0, lm_stride, lm_tiles, k; float T; uint64_t seed;
     float *logits; RowStat *stat; RowResult *res;
@@ -90,16 +95,24 @@ __device__ __forceinline__ LayerX layer_x(const PassArgs &p, int l) {
     return x;
 }
 
+// A uniform value the optimiser cannot trace: divisions by it are expanded where they stand.  (The reciprocal
+// of a loop-invariant divisor is otherwise computed once at the top of the kernel, in a vector register that
+// lives through the whole kernel, is spilled, and is reloaded from scratch memory at every use.)
+__device__ __forceinline__ int opaque_s(int v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+
 __device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Every thread has drained its stores of the phase (drain_vmem) before the workgroup is counted in.  The
 // workgroup that completes the count releases the others by writing the epoch into the flag copies.
-__device__ __forceinline__ void bar_arrive(const PassArgs &p, unsigned &epoch) {
+__device__ __forceinline__ void bar_arrive(const PassArgs &p, unsigned &epoch, int nb) {
     ++epoch;
     __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned old = __hip_atomic_fetch_add(p.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (old + 1u == epoch * gridDim.x) {
+        if (old + 1u == epoch * (unsigned)nb) {
 #pragma unroll
             for (int f = 0; f < PASS_NF; ++f)
                 __hip_atomic_store(p.sync + pass_flag_word(f), epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -116,68 +129,91 @@ __device__ __forceinline__ void bar_wait(const PassArgs &p, unsigned epoch) {
         unsigned polls = 0;
         if (!__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
             while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
-                __builtin_amdgcn_s_sleep(2);
+                __builtin_amdgcn_s_sleep(1);
                 if (++polls > p.spin_limit) { __hip_atomic_store(err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); break; }
                 if ((polls & 63u) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) break;
             }
         }
     }
     __syncthreads();
+    asm volatile("buffer_inv sc0" ::: "memory");   // drop this CU's cached copies of lines other workgroups rewrite
 }
 
 // ---- the sequence of GEMM items of one workgroup ------------------------------------------------
-struct GemmDesc { const uint4 *W; int KS, S, ncg, u; };   // u > 0: contiguous shares of u k-steps (S unused)
+struct GemmDesc { const uint4 *W; int KS, S, ncg, stream; };   // stream: equal consecutive shares (S unused)
 __device__ __forceinline__ GemmDesc phase_desc(const PassArgs &p, int l, int ph) {
     GemmDesc g;
     if (l >= p.L) {
-        g.W = (const uint4 *)p.w_lm; g.KS = p.d / 16; g.S = 1; g.u = 0; g.ncg = p.lm_on ? p.V / CG : 0;
+        g.W = (const uint4 *)p.w_lm; g.KS = p.d / 16; g.S = 1; g.stream = 0; g.ncg = p.lm_on ? p.V / CG : 0;
         return g;
     }
     const char *lw = p.lw0 + (size_t)l * p.layer_bytes;
-    g.u = 0;
+    g.stream = 0;
     if (ph == 0) { g.W = (const uint4 *)(lw + p.lo_qkv); g.KS = p.d / 16; g.S = p.S_qkv; g.ncg = p.n_qkv / CG; }
     else if (ph == 1) { g.W = (const uint4 *)(lw + p.lo_o); g.KS = p.kattn / 16; g.S = p.S_o; g.ncg = p.d / CG; }
-    else if (ph == 2) { g.W = (const uint4 *)(lw + p.lo_gu); g.KS = p.d / 16; g.S = p.S_gu; g.u = p.u_gu; g.ncg = 2 * p.F / CG; }
+    else if (ph == 2) { g.W = (const uint4 *)(lw + p.lo_gu); g.KS = p.d / 16; g.S = p.S_gu; g.stream = p.stream_gu; g.ncg = 2 * p.F / CG; }
     else { g.W = (const uint4 *)(lw + p.lo_d); g.KS = p.F / 16; g.S = p.S_d; g.ncg = p.d / CG; }
     return g;
 }
+// The workgroups form G groups of R; a group owns the column groups cg = gi (mod G) of every GEMM phase, the
+// kv heads kvh = gi (mod G) of attention, and everything its members exchange with each other.  With the
+// placement check passed, a group is the 32 workgroups of one XCD (G = 8, workgroup b sits on XCD b % 8) and
+// that exchange stays in the XCD's L2; otherwise there is one group of all workgroups and the exchange goes
+// through memory.
+struct Grouping { int G, gi, R, r, nb; bool near; };
+__device__ __forceinline__ Grouping make_grouping(bool near, int nb) {
+    Grouping gr;
+    gr.near = near;
+    gr.nb = nb;
+    if (near) { gr.G = 8; gr.gi = blockIdx.x & 7; gr.R = nb >> 3; gr.r = blockIdx.x >> 3; }
+    else { gr.G = 1; gr.gi = 0; gr.R = nb; gr.r = blockIdx.x; }
+    return gr;
+}
+
 // A piece of GEMM work: k-steps [kb, ke) of column group cg; it is the slot-th of np pieces of that group.
-// Two ways to cut a phase into pieces:
-//  - S equal K splits per column group; piece index it = cg + ncg * s, striped over the workgroups;
-//  - consecutive shares: the phase's ncg * KS k-steps are numbered column group by column group and
-//    workgroup b takes [b * u, (b + 1) * u), cut at column-group boundaries.  Every workgroup streams the
+// Two ways to cut a group's share of a phase into pieces:
+//  - S equal K splits per column group; piece index j = cgl + ncgl * s, striped over the group's workgroups;
+//  - consecutive shares: the k-steps of the group's column groups are numbered column group by column group
+//    and member r takes [r * u, (r + 1) * u), cut at column-group boundaries.  Every workgroup streams the
 //    same number of bytes whatever the number of column groups.
 struct Piece { int cg, kb, ke, slot, np; };
-struct PieceIter { int pos, end; };
-__device__ __forceinline__ PieceIter piece_begin(const GemmDesc &g) {
+struct PieceIter { int pos, end, ncgl, u; };
+__device__ __forceinline__ PieceIter piece_begin(const GemmDesc &g, const Grouping &gr) {
     PieceIter it;
-    if (g.u > 0) { it.pos = blockIdx.x * g.u; it.end = min(g.ncg * g.KS, it.pos + g.u); }
-    else { it.pos = blockIdx.x; it.end = g.ncg * g.S; }
+    const int G = opaque_s(gr.G), R = opaque_s(gr.R);
+    it.ncgl = (g.ncg - gr.gi + G - 1) / G;          // this group's column groups: cg = cgl * G + gi
+    const int ncgl_max = (g.ncg + G - 1) / G;
+    it.u = ((ncgl_max * g.KS + R - 1) / R + 7) / 8 * 8;
+    if (g.stream) { it.pos = gr.r * it.u; it.end = min(it.ncgl * g.KS, it.pos + it.u); }
+    else { it.pos = gr.r; it.end = it.ncgl * g.S; }
     return it;
 }
 __device__ __forceinline__ bool piece_valid(const PieceIter &it) { return it.pos < it.end; }
-__device__ __forceinline__ Piece piece_at(const GemmDesc &g, const PieceIter &it) {
+__device__ __forceinline__ Piece piece_at(const GemmDesc &g, const Grouping &gr, const PieceIter &it) {
     Piece pc;
-    if (g.u > 0) {
-        pc.cg = it.pos / g.KS;
-        pc.kb = it.pos - pc.cg * g.KS;
-        pc.ke = min(g.KS, pc.kb + (it.end - it.pos));
-        const int first = (pc.cg * g.KS) / g.u, last = ((pc.cg + 1) * g.KS - 1) / g.u;
-        pc.slot = (int)blockIdx.x - first;
+    int cgl;
+    const int KS = opaque_s(g.KS), u = opaque_s(it.u), ncgl = opaque_s(it.ncgl);
+    if (g.stream) {
+        cgl = it.pos / KS;
+        pc.kb = it.pos - cgl * KS;
+        pc.ke = min(KS, pc.kb + (it.end - it.pos));
+        const int first = (cgl * KS) / u, last = ((cgl + 1) * KS - 1) / u;
+        pc.slot = gr.r - first;
         pc.np = last - first + 1;
     } else {
-        pc.cg = it.pos % g.ncg;
-        pc.slot = it.pos / g.ncg;
+        cgl = it.pos % ncgl;
+        pc.slot = it.pos / ncgl;
         pc.np = g.S;
-        const int per = (g.KS + g.S * 8 - 1) / (g.S * 8) * 8;
+        const int per = (KS + g.S * 8 - 1) / opaque_s(g.S * 8) * 8;
         pc.kb = min(g.KS, pc.slot * per);
         pc.ke = min(g.KS, pc.kb + per);
     }
+    pc.cg = cgl * gr.G + gr.gi;
     return pc;
 }
-__device__ __forceinline__ void piece_advance(const GemmDesc &g, PieceIter &it, const Piece &pc) {
-    if (g.u > 0) it.pos += pc.ke - pc.kb;
-    else it.pos += gridDim.x;
+__device__ __forceinline__ void piece_advance(const GemmDesc &g, const Grouping &gr, PieceIter &it, const Piece &pc) {
+    if (g.stream) it.pos += pc.ke - pc.kb;
+    else it.pos += gr.R;
 }
 // k-steps [ks0, ks1) of wave w inside a piece
 __device__ __forceinline__ void wave_slice(const Piece &pc, int w, int &ks0, int &ks1) {
@@ -201,30 +237,6 @@ __device__ __forceinline__ void w_issue(uint4 (&wb)[D][4], const GemmDesc &g, co
 #pragma unroll
         for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
     }
-}
-
-// L2 prefetch of the k-steps that follow the D requested into registers: every lane requests one dword of a
-// distinct 128-byte line (64 lines = two k-steps of four column blocks per instruction) and never reads the
-// result.  The lines arrive in the L2 of this workgroup's XCD while the workgroup waits for the phase's
-// input.  The destination registers stay reserved until the wave has waited for all its vector memory
-// operations (touch_release).
-constexpr int PASS_TOUCH = 1;
-template <int D>
-__device__ __forceinline__ void w_touch(unsigned (&tr)[PASS_TOUCH], const GemmDesc &g, const Piece &pc, int w, int lane) {
-    int ks0, ks1;
-    wave_slice(pc, w, ks0, ks1);
-    const int c = lane >> 3;   // chunk of 1 KB: column block c & 3, k-step offset c >> 2
-#pragma unroll
-    for (int j = 0; j < PASS_TOUCH; ++j) {
-        const int ks = max(0, min(ks0 + D + 2 * j + (c >> 2), min(ks1, g.KS) - 1));
-        const char *q = (const char *)(g.W + ((size_t)(pc.cg * 4 + (c & 3)) * g.KS + ks) * 64) + (lane & 7) * 128;
-        asm volatile("global_load_dword %0, %1, off" : "=v"(tr[j]) : "v"(q) : "memory");
-    }
-}
-__device__ __forceinline__ void touch_release(unsigned (&tr)[PASS_TOUCH]) {
-    drain_vmem();
-#pragma unroll
-    for (int j = 0; j < PASS_TOUCH; ++j) asm volatile("" ::"v"(tr[j]));
 }
 
 // The GEMM code below exists once per kernel and serves every phase: the epilogue kind is a run-time
@@ -263,7 +275,7 @@ __device__ __forceinline__ void pass_finish(int epi, const GemmArgs &a, GemmSmem
 #pragma unroll
             for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pv[u][i] = ld_agent2(pp[i] + (size_t)min(s0 + u, S - 1) * sstride);
+                for (int i = 0; i < 4; ++i) pv[u][i] = ld_x2(pp[i] + (size_t)min(s0 + u, S - 1) * sstride, a.near != 0);
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < S) {
@@ -371,7 +383,7 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
 #pragma unroll
             for (int i = 0; i < 4; ++i) sq += ((tidx & 15) + 16 * i < a.ncg_in) ? ssqv[mt][i] : 0.f;
 #pragma unroll
-            for (int off = 1; off < 16; off <<= 1) sq += __shfl_xor(sq, off);
+            for (int off = 1; off < 16; off <<= 1) sq += shx(sq, off);
             if ((tidx & 15) == 0) sm.rstd[32 * mt + (tidx >> 4)] = rsqrtf(sq / (float)a.d_in + a.eps);
         }
     }
@@ -400,7 +412,7 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
     if (S == 1) {
         drain_vmem();   // the epilogue's stores are performed before the workgroup arrives at the barrier
     } else {
-        const bool last = arrive_last(a.counters + cg, S, &sm.last);   // drains this thread's stores first
+        const bool last = arrive_last(a.counters + cg, S, &sm.last, a.near != 0);   // drains this thread's stores first
         fstamp(p, ftag + 3);
         if (last) { pass_finish<MT>(epi, a, sm, cg, S); drain_vmem(); fstamp(p, ftag + 4); }
     }
@@ -426,9 +438,8 @@ struct AttnSmem {
 template <int HD>
 __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
-                                          int max_seq, const int *__restrict__ tile_seq,
-                                          const int *__restrict__ row_limit, float *part, int Hq, int Hkv, int NS,
-                                          float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t) {
+                                          int max_seq, int b, int lim, float *part, int Hq, int Hkv, int NS,
+                                          float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t, bool near) {
     constexpr int KSQ = HD / 16, HT = HD / 32, FPT = KSQ + 2 * HT;   // fragments per tile
     constexpr int LPW = ATT_CH * FPT / 8;                            // staging loads per wave and chunk
     constexpr int PF = AttnPartial<HD>::FLOATS;
@@ -436,18 +447,17 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
     const int tidx = opaque_tid();
     const int w = tidx >> 6, lane = tidx & 63;
     const int g = w & 3, par = w >> 2;
-    const int G = Hq / Hkv;
+    const int G = Hq / opaque_s(Hkv);
     const int half = lane >> 5, qrow = lane & 31;
-    const int b = tile_seq[t];
-    const int lim = row_limit[t * 32 + qrow];
+    // b: the tile's sequence; lim: the key limit of this lane's query row (both read once at kernel start)
     int maxlim = lim, minlim = lim;
 #pragma unroll
     for (int off = 1; off < 32; off <<= 1) {
-        maxlim = max(maxlim, __shfl_xor(maxlim, off));
-        minlim = min(minlim, __shfl_xor(minlim, off));
+        maxlim = max(maxlim, shx(maxlim, off));
+        minlim = min(minlim, shx(minlim, off));
     }
     const int nkt = (maxlim + 31) >> 5;
-    const int per = (nkt + NS - 1) / NS;
+    const int per = (nkt + NS - 1) / opaque_s(NS);
     const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
     const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
@@ -471,7 +481,7 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
-        fstamp(p, 46);
+        // (stamp 46 removed)
 
         for (int c0 = kt0; c0 < kt1; c0 += ATT_CH) {
             const int ntile = min(ATT_CH, kt1 - c0);
@@ -526,7 +536,7 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
                     float mx = sacc[0];
 #pragma unroll
                     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-                    mx = fmaxf(mx, __shfl_xor(mx, 32));
+                    mx = fmaxf(mx, shx(mx, 32));
                     const float m_new = fmaxf(m_run, mx);
                     float pr[16];
                     if (m_new == -INFINITY) {
@@ -592,7 +602,7 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
                     oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
                     oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
                 }
-            const float l_tot = l_run + __shfl_xor(l_run, 32);
+            const float l_tot = l_run + shx(l_run, 32);
             if (NS == 1) {
                 attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
             } else {
@@ -613,7 +623,7 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
 // merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
 template <int HD>
 __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
-                                                int head, int t, int tt, int hh, int lane) {
+                                                int head, int t, int tt, int hh, int lane, bool near) {
     constexpr int PF = AttnPartial<HD>::FLOATS;
     const int half = lane >> 5, qrow = lane & 31;
     const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
@@ -622,7 +632,7 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
     {
         float2 ml[32];
 #pragma unroll
-        for (int s = 0; s < 32; ++s) ml[s] = ld_agent2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow);
+        for (int s = 0; s < 32; ++s) ml[s] = ld_x2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow, near);
 #pragma unroll
         for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
 #pragma unroll
@@ -642,7 +652,7 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
             for (int u = 0; u < 16; ++u)
 #pragma unroll
                 for (int r2 = 0; r2 < 4; ++r2)
-                    v[u][r2] = ld_agent2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2);
+                    v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
 #pragma unroll
             for (int u = 0; u < 16; ++u)
 #pragma unroll
@@ -657,7 +667,7 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
         const int q = 2 * hh + qq;
         float mine[4], other[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = __shfl_xor(mine[e], 32); }
+        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = shx(mine[e], 32); }
         if ((q & 1) == half) {
             float v8[8];
 #pragma unroll
@@ -721,27 +731,25 @@ union PassSmem {
 
 template <int MT, int D>
 __device__ __forceinline__ void gemm_phase(const PassArgs &p, GemmArgs &a, int epi, GemmSmem &sm, const GemmDesc &g,
-                                           unsigned &epoch, int &ns) {
-    a.W = g.W; a.KS = g.KS; a.S = g.S; a.N = g.ncg * CG;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+                                           const Grouping &gr, unsigned &epoch, int &ns) {
+    a.W = g.W; a.KS = g.KS; a.S = g.S; a.N = g.ncg * CG; a.near = (gr.near && (p.allow_near & 1)) ? 1 : 0; a.h_near = (gr.near && (p.allow_near & 2)) ? 1 : 0;
+    const int tidx = opaque_tid();
+    const int w = tidx >> 6, lane = tidx & 63;
     // The first piece's first weights travel while the previous phase's dependency chain resolves; a workgroup
     // without a piece makes a harmless in-range request so that wb is defined on every path.
     uint4 wb[D][4];
-    PieceIter it = piece_begin(g);
-    Piece pc = piece_valid(it) ? piece_at(g, it) : Piece{0, 0, min(g.KS, 8), 0, 1};
+    PieceIter it = piece_begin(g, gr);
+    Piece pc = piece_valid(it) ? piece_at(g, gr, it) : Piece{0, 0, min(g.KS, 8), 0, 1};
     w_issue<D>(wb, g, pc, w, lane);
-    unsigned touched[PASS_TOUCH];
-    w_touch<D>(touched, g, pc, w, lane);
     bar_wait(p, epoch);   // the phase's input is complete
-    touch_release(touched);
     stamp(p, ns);
     while (piece_valid(it)) {
         gemm_item<MT, D>(p, a, epi, sm, pc, wb);
-        piece_advance(g, it, pc);
-        if (piece_valid(it)) { pc = piece_at(g, it); w_issue<D>(wb, g, pc, w, lane); }
+        piece_advance(g, gr, it, pc);
+        if (piece_valid(it)) { pc = piece_at(g, gr, it); w_issue<D>(wb, g, pc, w, lane); }
     }
     stamp(p, ns);
-    bar_arrive(p, epoch);
+    bar_arrive(p, epoch, gr.nb);
 }
 
 template <int HD, int MT>
@@ -754,8 +762,14 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
 #ifdef DEER_PASS_FINE
     if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)blockIdx.x * PASS_STAMPS + 500] = 1000 + (__builtin_amdgcn_s_getreg((4 - 1) << 11 | 20) & 15);
 #endif
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ntiles = p.ntiles, d = p.d, ncg_d = d / CG;
+    // constants of the pass that the attention phase of every layer needs: per tile its sequence and per
+    // query row its key limit.  Kept in LDS: registers that live through the whole kernel end up in scratch
+    // memory, and a reload from there is a full memory round trip on the critical path of a phase.
+    __shared__ int s_lim[64], s_seq[2];
+    if (threadIdx.x < 64) s_lim[threadIdx.x] = p.rm.limit[min((int)threadIdx.x, ntiles * 32 - 1)];
+    if (threadIdx.x < 2) s_seq[threadIdx.x] = p.rm.tile_seq[min((int)threadIdx.x, ntiles - 1)];
+    __syncthreads();
     GemmArgs base{};
     base.part = p.part; base.counters = p.counters;
     base.mt0 = 0; base.mt_stride = 1; base.rows_total = ntiles * 32;
@@ -764,6 +778,21 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
     base.Hq = p.Hq; base.Hkv = p.Hkv; base.hd = p.hd;
     base.h = p.h; base.ssq_out = p.ssq; base.F = p.F;
 
+
+    // Placement check: the in-XCD exchange needs workgroup b on XCD b % 8, eight XCDs with equally many
+    // workgroups.  Every workgroup compares its XCC id; one barrier later all of them know the verdict.
+    bool near = false;
+    const int nb = opaque_s(p.nb);
+    if (p.allow_near && (nb & 7) == 0) {
+        const unsigned xcc = __builtin_amdgcn_s_getreg((4 - 1) << 11 | 20) & 15u;   // HW_REG_XCC_ID, 4 bits
+        if (xcc != (blockIdx.x & 7u) && threadIdx.x == 0)
+            __hip_atomic_store(p.sync + pass_xcd_word(), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        drain_vmem();
+        bar_arrive(p, epoch, nb);
+        bar_wait(p, epoch);
+        near = __hip_atomic_load(p.sync + pass_xcd_word(), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
+    }
+    const Grouping gr = make_grouping(near, nb);
 
     // all GEMM phases of all layers run through the one copy of the GEMM code in this loop
     const int n_phases = 4 * p.L + ((MT == 1 && p.lm_on) ? 1 : 0);
@@ -793,33 +822,40 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
             epi = EPI_RESID;
             a.Xhi = x.x3h; a.Xlo = x.x3l; a.xhi_out = xn.x0h; a.xlo_out = xn.x0l;
         }
-        gemm_phase<MT, D>(p, a, epi, sm, phase_desc(p, l, ph), epoch, ns);
+        gemm_phase<MT, D>(p, a, epi, sm, phase_desc(p, l, ph), gr, epoch, ns);
         if (ph != 0 || l == p.L) continue;
 
         // block attention: one (tile, kv head, key-range split) item per workgroup at a time
         bar_wait(p, epoch);
         stamp(p, ns);
-        const int n_items = ntiles * p.Hkv * p.NS;
-        for (int it = blockIdx.x; it < n_items; it += gridDim.x) {
-            const int kvh = it % p.Hkv, split = (it / p.Hkv) % p.NS, t = it / (p.Hkv * p.NS);
-            attn_item<HD>(p, x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, p.rm.tile_seq, p.rm.limit,
-                          p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t);
+        // a group's items: (tile, its kv heads kvh = kvl * G + gi, split); all splits of a kv head stay in the group
+        const int nkvl = (p.Hkv - gr.gi + gr.G - 1) / opaque_s(gr.G);
+        const int n_items = ntiles * nkvl * p.NS;
+        for (int j = gr.r; j < n_items; j += gr.R) {
+            const int NSo = opaque_s(p.NS), nkvo = opaque_s(nkvl);
+            const int split = j % NSo, kvh = ((j / NSo) % nkvo) * gr.G + gr.gi, t = j / (NSo * nkvo);
+            attn_item<HD>(p, x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, s_seq[t],
+                          s_lim[t * 32 + (opaque_tid() & 31)], p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t, gr.near && (p.allow_near & 4));
         }
         drain_vmem();
         stamp(p, ns);
-        bar_arrive(p, epoch);
+        bar_arrive(p, epoch, nb);
         if (p.NS > 1) {
             constexpr int HT = HD / 32;
-            const int n = ntiles * p.Hq * HT * 2;
+            const int Gq = p.Hq / opaque_s(p.Hkv);
+            const int n = ntiles * nkvl * Gq * HT * 2;
             bar_wait(p, epoch);
             stamp(p, ns);
-            for (int it = w * gridDim.x + blockIdx.x; it < n; it += 8 * gridDim.x) {
-                const int hh = it & 1, tt = (it >> 1) % HT, head = (it / (2 * HT)) % p.Hq, t = it / (2 * HT * p.Hq);
-                attn_merge_item<HD>(p.opart, p.NS, p.Hq, p.scale_log2e, x.x1h, x.x1l, head, t, tt, hh, lane);
+            const int mt_ = opaque_tid(), w = mt_ >> 6, lane = mt_ & 63;
+            for (int j = w * gr.R + gr.r; j < n; j += 8 * gr.R) {
+                const int Gqo = opaque_s(Gq), nkvo = opaque_s(nkvl);
+                const int hh = j & 1, tt = (j >> 1) % HT, gq = (j / (2 * HT)) % Gqo;
+                const int kvh = ((j / (2 * HT * Gqo)) % nkvo) * gr.G + gr.gi, t = j / (2 * HT * Gqo * nkvo);
+                attn_merge_item<HD>(p.opart, p.NS, p.Hq, p.scale_log2e, x.x1h, x.x1l, kvh * Gq + gq, t, tt, hh, lane, gr.near && (p.allow_near & 4));
             }
             drain_vmem();
             stamp(p, ns);
-            bar_arrive(p, epoch);
+            bar_arrive(p, epoch, nb);
         }
     }
     if (p.lm_on) {
@@ -829,11 +865,11 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
             a.Xhi = x.x0h; a.Xlo = x.x0l;
             a.mt0 = p.lm_mt0; a.mt_stride = p.lm_stride;
             a.k = p.k; a.T = p.T; a.seed = p.seed; a.stat = p.stat; a.ncg_v = p.V / CG; a.logits = p.logits;
-            gemm_phase<1, D>(p, a, EPI_LMHEAD, sm, phase_desc(p, p.L, 0), epoch, ns);
+            gemm_phase<1, D>(p, a, EPI_LMHEAD, sm, phase_desc(p, p.L, 0), gr, epoch, ns);
         }
         bar_wait(p, epoch);
         stamp(p, ns);
-        for (int row = blockIdx.x; row < p.lm_tiles * p.k; row += gridDim.x)
+        for (int row = blockIdx.x; row < p.lm_tiles * p.k; row += nb)
             rowstat_row(p.stat, p.V / CG, p.T, p.res, row, sm.red);
         stamp(p, ns);
     }
