@@ -23,7 +23,6 @@ def build_library(verbose: bool = False) -> str:
         # packed fp32 instructions are kept off for all device code
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
-        *os.environ.get("DEER_EXTRA_FLAGS", "").split(),
         "-o", LIB_PATH, *SOURCES,
     ]
     if verbose:

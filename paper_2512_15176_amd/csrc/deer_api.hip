@@ -90,6 +90,7 @@ struct deer_ctx {
     int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
     int pass_mode = 2;               // 0: one kernel per operation, 1: persistent kernel where possible, 2: by model size
     bool pass_used = false;          // a pass kernel has run since the error flag was last read
+    unsigned pass_flag_host = 0;     // host copy of the kernel's error flag
     bool pass_stamps_on = false;     // deer_debug_pass_timeline: the next pass kernels record their timeline
     bool prof_split = false;         // deer_debug_profile(2): time per operation (separate kernels)
     // optional per-launch timing (deer_debug_profile)
@@ -431,14 +432,18 @@ int run_pass_persistent(deer_ctx *c, int model, int ntiles, int max_limit, const
     return DEER_OK;
 }
 
-// After a stream synchronisation: did a pass kernel give up waiting at its grid barrier?
-int check_pass_error(deer_ctx *c) {
+// Did a pass kernel give up waiting at its grid barrier?  pass_error_fetch enqueues the copy of the flag
+// (before a stream synchronisation the caller does anyway), pass_error_check looks at it afterwards.
+int pass_error_fetch(deer_ctx *c) {
+    c->pass_flag_host = 0;
     if (!c->pass_used) return DEER_OK;
-    unsigned flag = 0;
-    HIPCHK(c, hipMemcpyAsync(&flag, c->wk.pass_sync + pass_err_word(), 4, hipMemcpyDeviceToHost, c->stream));
-    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpyAsync(&c->pass_flag_host, c->wk.pass_sync + pass_err_word(), 4, hipMemcpyDeviceToHost, c->stream));
+    return DEER_OK;
+}
+int pass_error_check(deer_ctx *c) {
+    if (!c->pass_used) return DEER_OK;
     c->pass_used = false;
-    if (flag) {
+    if (c->pass_flag_host) {
         (void)hipMemsetAsync(c->wk.pass_sync + pass_err_word(), 0, 4, c->stream);
         return fail(c, DEER_EHIP, "the pass kernel's grid barrier timed out; results of the last pass are invalid");
     }
@@ -725,8 +730,9 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
                 if (rc) return rc;
             }
         }
+        if (int rc = pass_error_fetch(c)) return rc;
         HIPCHK(c, hipStreamSynchronize(c->stream));   // w.ids is reused by the next sequence
-        if (int rc = check_pass_error(c)) return rc;
+        if (int rc = pass_error_check(c)) return rc;
         pend[b] = ids[off + n - 1];
         off += n;
     }
@@ -811,8 +817,9 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
     HIPCHK(c, hipMemcpyAsync(acc, w.ao.accept_len, B * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(ncom, w.ao.n_committed, B * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(committed, w.ao.committed, (size_t)B * k * 4, hipMemcpyDeviceToHost, c->stream));
+    if (int rc = pass_error_fetch(c)) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (int rc = check_pass_error(c)) return rc;
+    if (int rc = pass_error_check(c)) return rc;
     for (int b = 0; b < B; ++b) {
         c->h_len[b] += ncom[b];
         c->h_ing_n[b] = ncom[b];
@@ -840,8 +847,9 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
     const size_t n = (size_t)c->batch * c->cur_k * c->p.target.vocab;
     if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
     HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
+    if (int rc = pass_error_fetch(c)) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (int rc = check_pass_error(c)) return rc;
+    if (int rc = pass_error_check(c)) return rc;
     return DEER_OK;
 }
 

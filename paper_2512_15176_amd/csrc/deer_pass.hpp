@@ -69,13 +69,6 @@ __device__ __forceinline__ void stamp(const PassArgs &p, int &n) {
     if (p.stamps && threadIdx.x == 0 && n < PASS_STAMPS) p.stamps[(size_t)blockIdx.x * PASS_STAMPS + n] = wall_clock64();
     ++n;
 }
-#ifdef DEER_PASS_FINE
-__device__ __forceinline__ void fstamp(const PassArgs &p, int slot) {
-    if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)blockIdx.x * PASS_STAMPS + 440 + slot] = wall_clock64();
-}
-#else
-__device__ __forceinline__ void fstamp(const PassArgs &, int) {}
-#endif
 
 // vectors (16 bytes) per tile of a fragment plane over `width` channels
 __host__ __device__ __forceinline__ size_t plane_vecs(int width) { return (size_t)(width / 16) * 64; }
@@ -299,9 +292,7 @@ template <int MT, int D>
 __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, int epi, GemmSmem &sm, const Piece &pc,
                                           uint4 (&wb)[D][4]) {
     const int tidx = opaque_tid();
-    const int ftag = (epi == EPI_QKV ? 0 : epi == EPI_SWIGLU ? 2 : epi == EPI_LMHEAD ? 4 : 1) * 8 + (a.KS > 256 ? 8 : 0);
     const int w = tidx >> 6, lane = tidx & 63;
-    fstamp(p, ftag + 0);
     const int N = a.N, KS = a.KS, S = pc.np, cg = pc.cg, s = pc.slot;
     int ks0, ks1;
     wave_slice(pc, w, ks0, ks1);
@@ -372,10 +363,8 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
         }
     }
 
-    fstamp(p, ftag + 1);
 
     __syncthreads();   // the previous piece's epilogue has finished with the tile, the scratch and sm.rstd
-    fstamp(p, ftag + 5);
     if (epi != EPI_RESID) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
@@ -394,7 +383,6 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
         if (mt > 0) __syncthreads();
         if (epi == EPI_RESID && S == 1) resid_prefetch<true>(a, hreg, cg, a.mt0 + ct * a.mt_stride);
         reduce_waves_to_tile(acc[mt], sm.red, sm.tile, w, lane);
-        fstamp(p, ftag + 6);
         if (S == 1) {
             pass_epilogue(epi, a, sm, hreg, cg, ct);
         } else {
@@ -408,13 +396,11 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
             }
         }
     }
-    fstamp(p, ftag + 2);
     if (S == 1) {
         drain_vmem();   // the epilogue's stores are performed before the workgroup arrives at the barrier
     } else {
         const bool last = arrive_last(a.counters + cg, S, &sm.last, a.near != 0);   // drains this thread's stores first
-        fstamp(p, ftag + 3);
-        if (last) { pass_finish<MT>(epi, a, sm, cg, S); drain_vmem(); fstamp(p, ftag + 4); }
+        if (last) { pass_finish<MT>(epi, a, sm, cg, S); drain_vmem(); }
     }
 }
 
@@ -436,14 +422,13 @@ struct AttnSmem {
 };
 
 template <int HD>
-__device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
+__device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
                                           int max_seq, int b, int lim, float *part, int Hq, int Hkv, int NS,
                                           float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t, bool near) {
     constexpr int KSQ = HD / 16, HT = HD / 32, FPT = KSQ + 2 * HT;   // fragments per tile
     constexpr int LPW = ATT_CH * FPT / 8;                            // staging loads per wave and chunk
     constexpr int PF = AttnPartial<HD>::FLOATS;
-    fstamp(p, 45);
     const int tidx = opaque_tid();
     const int w = tidx >> 6, lane = tidx & 63;
     const int g = w & 3, par = w >> 2;
@@ -481,13 +466,10 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
-        // (stamp 46 removed)
 
         for (int c0 = kt0; c0 < kt1; c0 += ATT_CH) {
             const int ntile = min(ATT_CH, kt1 - c0);
-            fstamp(p, 47);
             __syncthreads();   // the previous chunk (or head round, or item) has been read
-            fstamp(p, 40);
             {   // stage: fragment f = w + 8 * i of the chunk; tiles past the range repeat the last one (unused)
                 uint4 st[LPW];
 #pragma unroll
@@ -512,7 +494,6 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
                 for (int s = 0; s < KSQ; ++s) { qh[s] = as.q[(g * 2 * KSQ + s) * 64 + lane]; ql[s] = as.q[(g * 2 * KSQ + KSQ + s) * 64 + lane]; }
             }
             q_shared = true;
-            fstamp(p, 41);
             if (active) {
                 for (int tl = par; tl < ntile; tl += 2) {
                     const int kt = c0 + tl;
@@ -572,9 +553,7 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
             }
         }
         // combine the two key parities of each head: odd-parity waves park (m, l, O), even-parity waves merge
-        fstamp(p, 42);
         __syncthreads();
-        fstamp(p, 43);
         float4 *ox = (float4 *)as.kv;
         if (par == 1) {
             as.ml[g * 64 + lane] = make_float2(m_run, l_run);
@@ -614,7 +593,6 @@ __device__ __forceinline__ void attn_item(const PassArgs &p, const uint4 *Qhi, c
                 if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
             }
         }
-        fstamp(p, 44);
     }
 }
 
@@ -759,9 +737,6 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
     constexpr int D = (MT == 1) ? 4 : 2;   // weight k-steps in flight per wave
     unsigned epoch = 0;
     int ns = 0;
-#ifdef DEER_PASS_FINE
-    if (p.stamps && threadIdx.x == 0) p.stamps[(size_t)blockIdx.x * PASS_STAMPS + 500] = 1000 + (__builtin_amdgcn_s_getreg((4 - 1) << 11 | 20) & 15);
-#endif
     const int ntiles = p.ntiles, d = p.d, ncg_d = d / CG;
     // constants of the pass that the attention phase of every layer needs: per tile its sequence and per
     // query row its key limit.  Kept in LDS: registers that live through the whole kernel end up in scratch
@@ -834,7 +809,7 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
         for (int j = gr.r; j < n_items; j += gr.R) {
             const int NSo = opaque_s(p.NS), nkvo = opaque_s(nkvl);
             const int split = j % NSo, kvh = ((j / NSo) % nkvo) * gr.G + gr.gi, t = j / (NSo * nkvo);
-            attn_item<HD>(p, x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, s_seq[t],
+            attn_item<HD>(x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, s_seq[t],
                           s_lim[t * 32 + (opaque_tid() & 31)], p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t, gr.near && (p.allow_near & 4));
         }
         drain_vmem();
