@@ -160,18 +160,18 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_f
  * (kernel_class 0) and of the block-attention kernel (kernel_class 1) is bracketed by HIP events
  * on the context's stream, and so is every launch of the persistent pass kernel (kernel_class 2),
  * which runs a whole pass of a dense model at batch 1.  deer_debug_profile(c, mode) waits for the
- * stream, switches recording (0 off, 1 on, 2 on with every pass run as separate kernels so that
- * classes 0 and 1 are populated) and forgets earlier records; deer_debug_profile_read waits for the
+ * stream, switches recording (0 off, 1 on, 2 on with every pass run as separate kernels whatever
+ * the launch mode, so that classes 0 and 1 are populated) and forgets earlier records; deer_debug_profile_read waits for the
  * stream and returns, for one class, the summed event time (ms), the number of launches, and their
  * algorithmic bytes (weight bytes of each GEMM; K and V rows visible to each attention launch; both,
  * over all layers and the LM head, for a pass kernel). */
 int deer_debug_profile(deer_ctx *c, int enable);
 int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes);
 
-/* How a forward pass is launched: 0 = one kernel per operation, 1 = one persistent kernel per pass wherever
- * it applies (dense model, batch 1), 2 = chosen by model size (the default; the environment variable
- * DEER_PERSISTENT sets the initial value).  Both paths compute the same pass; tests compare them.  Waits
- * for the stream. */
+/* How a forward pass is launched: 0 = one kernel per operation (the default), 1 = one persistent kernel per
+ * pass wherever it applies (dense model, batch 1).  The environment variable DEER_PERSISTENT sets the initial
+ * value.  Both modes compute the same pass with the same device functions; tests compare them.  Waits for
+ * the stream. */
 int deer_debug_pass_mode(deer_ctx *c, int mode);
 
 /* Timeline of the persistent pass kernel (dense models at batch 1 run a whole pass as one kernel).

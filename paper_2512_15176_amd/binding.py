@@ -238,7 +238,7 @@ class DeerEngine:
         return ms.value, n.value, by.value
 
     def debug_pass_mode(self, mode):
-        """0: one kernel per operation; 1: persistent pass kernel wherever it applies; 2: by model size."""
+        """0: one kernel per operation (default); 1: persistent pass kernel wherever it applies."""
         self.lib.deer_debug_pass_mode.argtypes = [C.c_void_p, C.c_int]
         self._check(self.lib.deer_debug_pass_mode(self.ctx, int(mode)))
 

@@ -88,7 +88,7 @@ struct deer_ctx {
     std::string err;
     // persistent pass kernel
     int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
-    int pass_mode = 2;               // 0: one kernel per operation, 1: persistent kernel where possible, 2: by model size
+    int pass_mode = 0;               // 0: one kernel per operation, 1: persistent kernel where possible
     bool pass_used = false;          // a pass kernel has run since the error flag was last read
     unsigned pass_flag_host = 0;     // host copy of the kernel's error flag
     bool pass_stamps_on = false;     // deer_debug_pass_timeline: the next pass kernels record their timeline
@@ -308,12 +308,13 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
     ProfScope ps(c, 1, kv_bytes);
     (void)G;
-    hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * NS, ntiles), dim3(256), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
+    hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * NS, ntiles), dim3(512), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                        m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart,
                        mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.xb_hi, w.xb_lo);
     LAUNCHCHK(c, "k_attn");
     if (NS > 1) {
-        hipLaunchKernelGGL(k_attn_merge<HD>, dim3(mc.n_q_heads, ntiles), dim3(256), 0, c->stream, w.opart, NS, mc.n_q_heads,
+        const int n_items = ntiles * mc.n_q_heads * (HD / 32) * 2;
+        hipLaunchKernelGGL(k_attn_merge<HD>, dim3((n_items + 3) / 4), dim3(256), 0, c->stream, w.opart, NS, mc.n_q_heads, n_items,
                            scale_log2e, w.xb_hi, w.xb_lo);
         LAUNCHCHK(c, "k_attn_merge");
     }
@@ -338,16 +339,14 @@ int pass_occupancy() {
     return per_cu;
 }
 
-// Which passes run as the persistent kernel.  Measured on MI355X (batch 1, k = 32, prefix 4096): an 8B-shaped
-// target pass takes 4.95 ms as one persistent kernel against 5.10 ms as one kernel per operation; the 0.5B
-// drafter (30 MB of weights per layer, latency-bound) takes 2.84 ms against 2.77 ms.  mode 2 (the default)
-// therefore picks the persistent kernel for layers of at least 128 MB; 0 and 1 force either path.
+// Which passes run as the persistent kernel: none unless asked for (deer_debug_pass_mode(1) or
+// DEER_PERSISTENT=1).  Measured on MI355X (batch 1, prefix 4096 / 1024): the 8B-shaped target pass takes
+// 4.90 ms as one persistent kernel against 4.67 ms as one kernel per operation, the 4B-shaped one 3.79 ms
+// against 3.90 ms, the 0.5B drafter 2.80 ms against 2.53 ms.
 bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
-    if (c->pass_mode == 0 || c->pass_blocks < 1 || c->prof_split) return false;
+    if (c->pass_mode != 1 || c->pass_blocks < 1 || c->prof_split) return false;
     if (m.c.n_experts || ntiles > 2 || (lm.on && lm.n_tiles != 1)) return false;
-    if (m.c.d_model / CG > 64) return false;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
-    if (c->pass_mode == 1) return true;
-    return m.layer_bytes >= ((size_t)128 << 20);
+    return m.c.d_model / CG <= 64;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
 }
 
 // The same pass as run_pass, as one cooperative launch (dense model, at most two tiles).
@@ -467,10 +466,11 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         LAUNCHCHK(c, "k_rope_table");
     }
     const int nkt = (max_limit + 31) / 32;
-    // key-range splits: aim at ~256 blocks; ntiles * NS never exceeds the partial buffer (max(64, tiles))
-    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 128;
+    // key-range splits: aim at one workgroup per compute unit; a split holds at least one staged chunk of 4 key
+    // tiles; ntiles * NS never exceeds the partial buffer (max(64, tiles))
+    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
-    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
+    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 3) / 4}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     GemmArgs base{};
@@ -646,7 +646,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         int occ = std::min({pass_occupancy<128, 1>(), pass_occupancy<128, 2>(), pass_occupancy<64, 1>(), pass_occupancy<64, 2>(),
                             pass_occupancy<32, 1>(), pass_occupancy<32, 2>()});
         c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
-        if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = std::max(0, std::min(2, atoi(e)));
+        if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = atoi(e) == 1 ? 1 : 0;
         (void)hipGetLastError();
     }
     *out = c;
@@ -891,7 +891,7 @@ int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int
 
 int deer_debug_pass_mode(deer_ctx *c, int mode) {
     if (!c) return DEER_EINVAL;
-    if (mode < 0 || mode > 2) return fail(c, DEER_EINVAL, "pass mode must be 0, 1 or 2");
+    if (mode < 0 || mode > 1) return fail(c, DEER_EINVAL, "pass mode must be 0 or 1");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->pass_mode = mode;
     return DEER_OK;

@@ -112,6 +112,16 @@ __device__ __forceinline__ int shx(int v, int off) {
 }
 __device__ __forceinline__ float shx(float v, int off) { return __int_as_float(shx(__float_as_int(v), off)); }
 
+// A uniform value the optimiser cannot trace: divisions by it are expanded where they stand.  (The reciprocal
+// of a loop-invariant divisor is otherwise computed once at the top of the kernel, in a vector register that
+// lives through the whole kernel, is spilled, and is reloaded from scratch memory at every use.)
+__device__ __forceinline__ int opaque_s(int v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+
+__device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Row of the 32x32 MFMA result held in register r of a lane in half `half` (= lane / 32).
 __device__ __forceinline__ int mfma_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
@@ -759,7 +769,7 @@ template <int MT, int EPI, bool COH, bool DEFER>
 __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int cg, int s, int z, int ncg) {
     const int tidx = opaque_tid();
     float *red = sm.red, *tile = sm.tile, *s_rstd = sm.rstd;
-    const int w = tidx >> 6, lane = tidx & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;   // the wave index as a scalar: scalar loop bounds
     const int N = a.N, KS = a.KS, S = a.S;
     const int slices = S * 8, sl = s * 8 + w;
     const int per = (KS + slices - 1) / slices;
@@ -898,7 +908,7 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
     const int cg = blockIdx.x, ex = blockIdx.y, chunk = blockIdx.z;
     const int n = a.cnt[ex] - chunk * 32;
     if (n <= 0) return;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, cl = lane & 31;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5, cl = lane & 31;
     const int KS = a.KS;
     if (threadIdx.x < 32) {
         const bool v = threadIdx.x < n;
@@ -1090,18 +1100,14 @@ __global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, i
 
 // ------------------------------------------------------------------------------------------
 // block attention for short query blocks over a long GQA cache.
-//   grid: x = kv_head + Hkv * split, y = pass tile (32 query rows of one sequence).
-//   A block owns one K/V head and one contiguous range of 32-key tiles; wave w serves query heads
-//   g = w, w+4, .. of that K/V head's group, so the waves of a block read the same K/V lines
-//   (one trip from L2 per block, not per query head).  Online softmax in fp32.
-//   S^T = K Q^T and O^T = V^T P^T: every MFMA operand is a contraction-contiguous 16-byte vector and
-//   the softmax row of a lane is its own column.  Key order inside a 32-key tile is permuted
-//   (operand row rho holds key 16*((rho/4)%2) + 4*(rho/8) + rho%4) so that a lane's 16 scores are
+//   Online softmax in fp32.  S^T = K Q^T and O^T = V^T P^T: every MFMA operand is a contraction-contiguous
+//   16-byte vector and the softmax row of a lane is its own column.  Key order inside a 32-key tile is
+//   permuted (operand row rho holds key 16*((rho/4)%2) + 4*(rho/8) + rho%4) so that a lane's 16 scores are
 //   16 consecutive keys.  Q and P enter as (hi, lo) bf16 pairs.
-//   With one key range (NS == 1) the result goes straight to the O-projection's input fragments;
-//   otherwise each (tile, head, split) leaves an un-normalised partial (M, L, O) in the MFMA register
-//   layout and k_attn_merge combines them (a merge inside this kernel would serialise NS dependent
-//   round trips to memory on one block).
+//   With one key range (NS == 1) the result goes straight to the O-projection's input fragments; otherwise
+//   each (tile, head, split) leaves an un-normalised partial (M, L, O) in the MFMA register layout and a
+//   separate merge combines them (a merge by the last split to finish would serialise NS dependent round
+//   trips to memory on one workgroup).
 // ------------------------------------------------------------------------------------------
 template <int HD>
 struct AttnPartial {   // per (tile, head, split): O in register layout [HD/32][8 reg pairs][64 lanes][2], then (M, L)[32]
@@ -1145,21 +1151,41 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
     }
 }
 
-// One (kv_head, key-range split, pass tile) work item, executed by a group of 4 waves (w = wave in group).
-template <int HD, bool COH>
-__device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
-                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
-                                           int max_seq, const int *__restrict__ tile_seq,
-                                           const int *__restrict__ row_limit, float *part, int Hq, int Hkv, int NS,
-                                           float scale_log2e, uint4 *xhi, uint4 *xlo, int kvh, int split, int t, int w,
-                                           int lane) {
-    constexpr int KSQ = HD / 16;   // k-steps of the score contraction
-    constexpr int HT = HD / 32;    // 32-row tiles of O^T
+// ------------------------------------------------------------------------------------------
+// Block attention item for a whole workgroup of 8 waves (both launch modes use it).
+//  - one (row tile, kv head, key-range split) item per workgroup; wave w serves query head (w & 3) of the
+//    GQA group on the key tiles of parity (w >> 2) of each staged chunk, so two waves per SIMD overlap;
+//  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested at once by the eight waves (one
+//    memory round trip per chunk, every fragment fetched once per workgroup instead of once per query head)
+//    and land in LDS in fragment order (direct-to-LDS loads); the next chunk travels into the other of two
+//    LDS buffers while the current chunk is multiplied;
+//  - Q fragments stay in registers; the even-parity wave of a head requests them and passes a copy to the
+//    odd-parity wave through the second LDS buffer before that buffer's first use;
+//  - the two key parities of a head are combined through LDS, then the result goes to the output
+//    projection's input (NS == 1) or to an un-normalised partial (M, L, O) for the merge.
+// Partials and outputs are written with agent-scope stores, so the item serves the persistent kernel
+// (consumers in the same kernel) and the per-operation path alike.  b: the tile's sequence; lim: the key
+// limit of this lane's query row.
+// ------------------------------------------------------------------------------------------
+constexpr int ATT_CH = 4;   // tiles per staged chunk
+struct AttnSmem {
+    uint4 buf[2][ATT_CH * 16 * 64];   // [tile][fragment: K k-steps, then V (tile, half) pairs][lane]; 2 x 64 KB
+    float2 ml[4 * 64];                // parked (m, l) of the odd-parity waves
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
+                                          const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
+                                          int max_seq, int b, int lim, float *part, int Hq, int Hkv, int NS,
+                                          float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t) {
+    constexpr int KSQ = HD / 16, HT = HD / 32, FPT = KSQ + 2 * HT;   // fragments per tile
+    constexpr int LPW = ATT_CH * FPT / 8;                            // staging loads per wave and chunk
     constexpr int PF = AttnPartial<HD>::FLOATS;
-    const int G = Hq / Hkv;
+    const int tidx = opaque_tid();
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;   // the wave index as a scalar
+    const int g = w & 3, par = w >> 2;
+    const int G = Hq / opaque_s(Hkv);
     const int half = lane >> 5, qrow = lane & 31;
-    const int b = tile_seq[t];
-    const int lim = row_limit[t * 32 + qrow];
     int maxlim = lim, minlim = lim;
 #pragma unroll
     for (int off = 1; off < 32; off <<= 1) {
@@ -1167,20 +1193,38 @@ __device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, c
         minlim = min(minlim, shx(minlim, off));
     }
     const int nkt = (maxlim + 31) >> 5;
-    const int per = (nkt + NS - 1) / NS;
+    const int per = (nkt + NS - 1) / opaque_s(NS);
     const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
+    const int nchunks = kt1 > kt0 ? (kt1 - kt0 + ATT_CH - 1) / ATT_CH : 0;
     const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);   // operand row -> key
 
-    for (int g = w; g < G; g += 4) {
-        const int head = kvh * G + g;
-        uint4 qh[KSQ], ql[KSQ];
-        {
-            const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
+    // Requests this wave's share of a chunk (fragment f = w + 8 * i) straight into LDS: a 16-byte
+    // direct-to-LDS load writes lane l's vector at (uniform base) + 16 * l, which is the fragment order, and
+    // needs no registers while it travels.  Tiles past the range repeat the last one (not used).
+    auto stage = [&](uint4 *dst, int c0) {
+        const int ntile = min(ATT_CH, kt1 - c0);
+        // lane offsets (elements) are rebuilt here from two small values, so that eight 64-bit addresses per
+        // lane do not live (spilled) across the whole item
+        int ko = keyperm * HD + half * 8, vo = qrow * max_seq + 16 * half;
+        asm volatile("" : "+v"(ko), "+v"(vo));
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) { qh[s] = ld16<COH>(Qhi + qb + (size_t)s * 64); ql[s] = ld16<COH>(Qlo + qb + (size_t)s * 64); }
+        for (int i = 0; i < LPW; ++i) {
+            const int f = w + 8 * i, tl = f / FPT, fi = f % FPT;
+            const int kt = c0 + min(tl, ntile - 1);
+            const uint16_t *src;
+            if (fi < KSQ) src = Kp + (ko + kt * 32 * HD + fi * 16);
+            else src = Vp + (vo + ((fi - KSQ) >> 1) * 32 * max_seq + kt * 32 + 8 * ((fi - KSQ) & 1));
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
+                                             (void __attribute__((address_space(3))) *)(dst + f * 64), 16, 0, 0);
         }
+    };
+    auto stage_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+
+    for (int g0 = 0; g0 < G; g0 += 4) {
+        const bool active = g0 + g < G;
+        const int head = kvh * G + min(g0 + g, G - 1);
         f32x16 oacc[HT];
 #pragma unroll
         for (int tt = 0; tt < HT; ++tt)
@@ -1188,195 +1232,222 @@ __device__ __forceinline__ void attn_group(const uint4 *Qhi, const uint4 *Qlo, c
             for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
         float m_run = -INFINITY, l_run = 0.f;
 
-        // K and V fragments of a 32-key tile are requested together, one tile ahead of their use
-        auto load_tile = [&](u32x4 (&kf)[KSQ], u32x4 (&vf)[HT][2], int kt) {
-            const uint16_t *kp = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8;
+        if (nchunks > 0) {
+            uint4 qh[KSQ], ql[KSQ];
+            __syncthreads();   // the previous head round or item has been read
+            stage(as.buf[0], kt0);
+            if (par == 0) {
+                const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) load16_async(kf[s], kp + s * 16);
+                for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
 #pragma unroll
-            for (int tt = 0; tt < HT; ++tt) {
-                const uint16_t *vp = Vp + (size_t)(tt * 32 + qrow) * max_seq + kt * 32 + 16 * half;
-                load16_async(vf[tt][0], vp);
-                load16_async(vf[tt][1], vp + 8);
+                for (int s = 0; s < KSQ; ++s) { as.buf[1][(g * 2 * KSQ + s) * 64 + lane] = qh[s]; as.buf[1][(g * 2 * KSQ + KSQ + s) * 64 + lane] = ql[s]; }
             }
-        };
-        auto compute_tile = [&](u32x4 (&kf)[KSQ], u32x4 (&vf)[HT][2], int kt) {
-            // the caller has waited for this tile's loads; tie its registers to that wait
+            stage_wait();
+            __syncthreads();
+            if (par == 1) {
 #pragma unroll
-            for (int s = 0; s < KSQ; ++s) tie(kf[s]);
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt) { tie(vf[tt][0]); tie(vf[tt][1]); }
-            f32x16 sacc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < KSQ; ++s) {
-                sacc = mfma32(kf[s], qh[s], sacc);
-                sacc = mfma32(kf[s], ql[s], sacc);
+                for (int s = 0; s < KSQ; ++s) { qh[s] = as.buf[1][(g * 2 * KSQ + s) * 64 + lane]; ql[s] = as.buf[1][(g * 2 * KSQ + KSQ + s) * 64 + lane]; }
             }
-            // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
-            const int key0 = kt * 32 + 16 * half;
-            if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
+            if (nchunks > 1) __syncthreads();   // Q has been taken out of the second buffer
+
+            for (int ci = 0; ci < nchunks; ++ci) {
+                const int c0 = kt0 + ci * ATT_CH;
+                const int ntile = min(ATT_CH, kt1 - c0);
+                const bool more = ci + 1 < nchunks;
+                if (more) stage(as.buf[(ci + 1) & 1], c0 + ATT_CH);   // that buffer was last read two barriers ago
+                if (active) {
+                    for (int tl = par; tl < ntile; tl += 2) {
+                        const int kt = c0 + tl;
+                        const uint4 *fr = as.buf[ci & 1] + (size_t)(tl * FPT) * 64 + lane;
+                        f32x16 sacc;
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (key0 + r >= lim) sacc[r] = -INFINITY;
-            }
-            float mx = sacc[0];
+                        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-            mx = fmaxf(mx, shx(mx, 32));
-            const float m_new = fmaxf(m_run, mx);
-            float p[16];
-            if (m_new == -INFINITY) {
+                        for (int s = 0; s < KSQ; ++s) {
+                            const uint4 kf = fr[s * 64];
+                            sacc = mfma32(kf, qh[s], sacc);
+                            sacc = mfma32(kf, ql[s], sacc);
+                        }
+                        // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
+                        const int key0 = kt * 32 + 16 * half;
+                        if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
 #pragma unroll
-                for (int r = 0; r < 16; ++r) p[r] = 0.f;
-            } else {
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
-                const float mb = m_new * scale_log2e;
-                float ls = 0.f;
+                            for (int r = 0; r < 16; ++r)
+                                if (key0 + r >= lim) sacc[r] = -INFINITY;
+                        }
+                        float mx = sacc[0];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) { p[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += p[r]; }
-                l_run = l_run * alpha + ls;
-                m_run = m_new;
-                if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+                        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+                        mx = fmaxf(mx, shx(mx, 32));
+                        const float m_new = fmaxf(m_run, mx);
+                        float pr[16];
+                        if (m_new == -INFINITY) {
 #pragma unroll
-                    for (int tt = 0; tt < HT; ++tt)
+                            for (int r = 0; r < 16; ++r) pr[r] = 0.f;
+                        } else {
+                            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                            const float mb = m_new * scale_log2e;
+                            float ls = 0.f;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+                            for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
+                            l_run = l_run * alpha + ls;
+                            m_run = m_new;
+                            if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+#pragma unroll
+                                for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                                    for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+                            }
+                        }
+                        uint4 ph[2], pl[2];
+                        pack8_split(pr, ph[0], pl[0]);
+                        pack8_split(pr + 8, ph[1], pl[1]);
+#pragma unroll
+                        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                            for (int s2 = 0; s2 < 2; ++s2) {
+                                const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
+                                oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
+                                oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+                            }
+                    }
                 }
+                stage_wait();
+                __syncthreads();
             }
-            // P enters the second contraction as a (hi, lo) bf16 pair like every other activation
-            uint4 ph[2], pl[2];
-            pack8_split(p, ph[0], pl[0]);
-            pack8_split(p + 8, ph[1], pl[1]);
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    oacc[tt] = mfma32(vf[tt][s2], ph[s2], oacc[tt]);
-                    oacc[tt] = mfma32(vf[tt][s2], pl[s2], oacc[tt]);
-                }
-        };
-        // tile buffers: loads of later tiles stay in flight behind the one being multiplied (two tiles
-        // ahead for head_dim <= 64, one tile ahead for head_dim 128, bounded by the register file)
-        constexpr int LPT = KSQ + 2 * HT;   // loads per tile
-        if (kt0 < kt1) {
-            const int last = kt1 - 1;       // a repeated last tile is a cache hit and is not used
-            u32x4 kfa[KSQ], vfa[HT][2], kfb[KSQ], vfb[HT][2];
-            if constexpr (HD <= 64) {
-                u32x4 kfc[KSQ], vfc[HT][2];
-                load_tile(kfa, vfa, kt0);
-                load_tile(kfb, vfb, min(kt0 + 1, last));
-                for (int kt = kt0; kt < kt1; kt += 3) {
-                    load_tile(kfc, vfc, min(kt + 2, last));
-                    wait_loads<2 * LPT>();
-                    compute_tile(kfa, vfa, kt);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_tile(kfa, vfa, min(kt + 3, last));
-                    wait_loads<2 * LPT>();
-                    if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_tile(kfb, vfb, min(kt + 4, last));
-                    wait_loads<2 * LPT>();
-                    if (kt + 2 < kt1) compute_tile(kfc, vfc, kt + 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            } else {
-                load_tile(kfa, vfa, kt0);
-                for (int kt = kt0; kt < kt1; kt += 2) {
-                    load_tile(kfb, vfb, min(kt + 1, last));
-                    wait_loads<LPT>();
-                    compute_tile(kfa, vfa, kt);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_tile(kfa, vfa, min(kt + 2, last));
-                    wait_loads<LPT>();
-                    if (kt + 1 < kt1) compute_tile(kfb, vfb, kt + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            wait_loads<0>();
-        }
-        const float l_tot = l_run + shx(l_run, 32);
-        if (NS == 1) {
-            attn_write_frag<HD, COH>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
         } else {
-            float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+            __syncthreads();   // the previous head round or item has been read
+        }
+        // combine the two key parities of each head: odd-parity waves park (m, l, O), even-parity waves merge
+        float4 *ox = (float4 *)as.buf[0];
+        if (par == 1) {
+            as.ml[g * 64 + lane] = make_float2(m_run, l_run);
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
-                for (int r2 = 0; r2 < 8; ++r2)
-                    if (COH) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-                    else *(float2 *)(pp + ((tt * 8 + r2) * 64 + lane) * 2) = make_float2(oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-            if (half == 0) {
-                if (COH) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
-                else *(float2 *)(pp + 32 * HD + 2 * qrow) = make_float2(m_run, l_tot);
+                for (int q = 0; q < 4; ++q)
+                    ox[((g * HT + tt) * 4 + q) * 64 + lane] = make_float4(oacc[tt][4 * q], oacc[tt][4 * q + 1], oacc[tt][4 * q + 2], oacc[tt][4 * q + 3]);
+        }
+        __syncthreads();
+        if (par == 0 && active) {
+            const float2 o_ml = as.ml[g * 64 + lane];
+            const float M = fmaxf(m_run, o_ml.x);
+            const float f0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * scale_log2e);
+            const float f1 = (o_ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((o_ml.x - M) * scale_log2e);
+            l_run = f0 * l_run + f1 * o_ml.y;
+            m_run = M;
+#pragma unroll
+            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 v = ox[((g * HT + tt) * 4 + q) * 64 + lane];
+                    oacc[tt][4 * q] = f0 * oacc[tt][4 * q] + f1 * v.x;
+                    oacc[tt][4 * q + 1] = f0 * oacc[tt][4 * q + 1] + f1 * v.y;
+                    oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
+                    oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
+                }
+            const float l_tot = l_run + shx(l_run, 32);
+            if (NS == 1) {
+                attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
+            } else {
+                float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+#pragma unroll
+                for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                    for (int r2 = 0; r2 < 8; ++r2) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
+                if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
             }
         }
     }
 }
 
+// grid: x = kv_head + Hkv * split, y = pass tile (32 query rows of one sequence); 512 threads
 template <int HD>
-__global__ __launch_bounds__(256) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
+__global__ __launch_bounds__(512) void k_attn(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
                                               const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
                                               size_t seq_stride, size_t head_stride, int max_seq,
                                               const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
                                               float *__restrict__ part, int Hq, int Hkv, int NS, float scale_log2e,
                                               uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
-    attn_group<HD, false>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, max_seq, tile_seq, row_limit, part, Hq, Hkv, NS,
-                          scale_log2e, xhi, xlo, blockIdx.x % Hkv, blockIdx.x / Hkv, blockIdx.y, threadIdx.x >> 6,
-                          threadIdx.x & 63);
+    __shared__ __attribute__((aligned(16))) AttnSmem as;
+    const int t = blockIdx.y;
+    attn_item<HD>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, max_seq, tile_seq[t], row_limit[t * 32 + (threadIdx.x & 31)],
+                  part, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, blockIdx.x % Hkv, blockIdx.x / Hkv, t);
 }
 
-// Merges the NS key-range partials of block attention in order s = 0..NS-1, normalises, and writes the
-// O-projection's input fragments.  grid: x = query head, y = pass tile; wave w merges O^T tile tt = w.
-// One wave merges O^T tile tt of one (tile, head).
-template <int HD, bool COH>
-__device__ __forceinline__ void attn_merge_wave(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi,
-                                                uint4 *xlo, int head, int t, int tt, int lane) {
-    constexpr int PF = AttnPartial<HD>::FLOATS;
-    const int qrow = lane & 31;
-    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
-    auto ld2 = [](const float *p) { return COH ? ld_agent2(p) : *(const float2 *)p; };
-    float M = -INFINITY;
-    for (int s0 = 0; s0 < NS; s0 += 8) {
-        float mv[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) mv[u] = ld2(p0 + (size_t)min(s0 + u, NS - 1) * PF + 32 * HD + 2 * qrow).x;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) M = fmaxf(M, mv[u]);
-    }
-    f32x16 o[1];
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[0][r] = 0.f;
-    float L = 0.f;
-    for (int s0 = 0; s0 < NS; s0 += 8) {   // eight splits per round: their loads are independent
-        float2 v[8][8], ml[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float *pp = p0 + (size_t)min(s0 + u, NS - 1) * PF;
-            ml[u] = ld2(pp + 32 * HD + 2 * qrow);
-#pragma unroll
-            for (int r2 = 0; r2 < 8; ++r2) v[u][r2] = ld2(pp + ((tt * 8 + r2) * 64 + lane) * 2);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float f = (s0 + u >= NS || ml[u].x == -INFINITY) ? 0.f : exp2f((ml[u].x - M) * scale_log2e);
-            L += f * ml[u].y;
-#pragma unroll
-            for (int r2 = 0; r2 < 8; ++r2) { o[0][2 * r2] += f * v[u][r2].x; o[0][2 * r2 + 1] += f * v[u][r2].y; }
-        }
-    }
-    attn_write_frag<HD, COH>(o, L > 0.f ? 1.f / L : 0.f, t, head, Hq, lane, xhi, xlo, tt, 1);
-}
-
-// Merges the NS key-range partials of block attention in order s = 0..NS-1, normalises, and writes the
-// O-projection's input fragments.  grid: x = query head, y = pass tile; wave w merges O^T tile tt = w.
+// Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
+// of O^T tile tt.  All (M, L) pairs are requested at once, then the partial outputs 16 splits at a time, so a
+// merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
 template <int HD>
-__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part, int NS, int Hq, float scale_log2e,
-                                                    uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
-    const int tt = threadIdx.x >> 6;
-    if (tt >= HD / 32) return;
-    attn_merge_wave<HD, false>(part, NS, Hq, scale_log2e, xhi, xlo, blockIdx.x, blockIdx.y, tt, threadIdx.x & 63);
+__device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
+                                                int head, int t, int tt, int hh, int lane, bool near = false) {
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    const int half = lane >> 5, qrow = lane & 31;
+    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
+    float f[32];
+    float M = -INFINITY, L = 0.f;
+    {
+        float2 ml[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) ml[s] = ld_x2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow, near);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            f[s] = (s >= NS || ml[s].x == -INFINITY) ? 0.f : exp2f((ml[s].x - M) * scale_log2e);
+            L += f[s] * ml[s].y;
+        }
+    }
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int s0 = 0; s0 < 32; s0 += 16) {
+        if (s0 < NS) {
+            float2 v[16][4];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+#pragma unroll
+                for (int r2 = 0; r2 < 4; ++r2)
+                    v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+#pragma unroll
+                for (int r2 = 0; r2 < 4; ++r2) { o[2 * r2] += f[s0 + u] * v[u][r2].x; o[2 * r2 + 1] += f[s0 + u] * v[u][r2].y; }
+        }
+    }
+    // registers 8*hh .. 8*hh+7 of tile tt: octets q = 2*hh and 2*hh + 1 (see attn_write_frag)
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const int KS = Hq * HD / 16;
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+        const int q = 2 * hh + qq;
+        float mine[4], other[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = shx(mine[e], 32); }
+        if ((q & 1) == half) {
+            float v8[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v8[e] = half ? other[e] : mine[e]; v8[4 + e] = half ? mine[e] : other[e]; }
+            uint4 hi, lo;
+            pack8_split(v8, hi, lo);
+            const size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
+            st16<true>(xhi + vec, hi);
+            st16<true>(xlo + vec, lo);
+        }
+    }
+}
+
+// grid: one wave per (tile, head, O^T tile, half): 256 threads = 4 wave items per block
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ part, int NS, int Hq, int n_items,
+                                                    float scale_log2e, uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
+    constexpr int HT = HD / 32;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= n_items) return;
+    const int hh = j & 1, tt = (j >> 1) % HT, head = (j / (2 * HT)) % Hq, t = j / (2 * HT * Hq);
+    attn_merge_item<HD>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, tt, hh, threadIdx.x & 63);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -88,16 +88,6 @@ __device__ __forceinline__ LayerX layer_x(const PassArgs &p, int l) {
     return x;
 }
 
-// A uniform value the optimiser cannot trace: divisions by it are expanded where they stand.  (The reciprocal
-// of a loop-invariant divisor is otherwise computed once at the top of the kernel, in a vector register that
-// lives through the whole kernel, is spilled, and is reloaded from scratch memory at every use.)
-__device__ __forceinline__ int opaque_s(int v) {
-    asm volatile("" : "+s"(v));
-    return v;
-}
-
-__device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // Every thread has drained its stores of the phase (drain_vmem) before the workgroup is counted in.  The
 // workgroup that completes the count releases the others by writing the epoch into the flag copies.
 __device__ __forceinline__ void bar_arrive(const PassArgs &p, unsigned &epoch, int nb) {
@@ -292,7 +282,7 @@ template <int MT, int D>
 __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, int epi, GemmSmem &sm, const Piece &pc,
                                           uint4 (&wb)[D][4]) {
     const int tidx = opaque_tid();
-    const int w = tidx >> 6, lane = tidx & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;
     const int N = a.N, KS = a.KS, S = pc.np, cg = pc.cg, s = pc.slot;
     int ks0, ks1;
     wave_slice(pc, w, ks0, ks1);
@@ -404,261 +394,6 @@ __device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, 
     }
 }
 
-// ---- block attention item for a whole workgroup ---------------------------------------------------------
-// Same mathematics and MFMA layouts as attn_group (S^T = K Q^T, O^T = V^T P^T, permuted key order, online
-// softmax in fp32, Q and P as (hi, lo) bf16 pairs), arranged for the persistent kernel:
-//  - one (tile, kv head, key-range split) item per workgroup; wave w serves query head (w & 3) of the GQA
-//    group on the tiles of parity (w >> 2) of each staged chunk, so two waves per SIMD overlap each other;
-//  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested all at once by the eight waves
-//    (one memory round trip per chunk, every fragment fetched once per workgroup instead of once per query
-//    head) and staged in LDS in fragment order; Q fragments stay in registers;
-//  - the two key parities of a head are combined through LDS, then the result goes to the output
-//    projection's input (NS == 1) or to an un-normalised partial (M, L, O) for the merge phase.
-constexpr int ATT_CH = 4;   // tiles per staged chunk
-struct AttnSmem {
-    uint4 kv[ATT_CH * 16 * 64];   // [tile][fragment: K k-steps, then V (tile, half) pairs][lane]; 64 KB at head_dim 128
-    uint4 q[4 * 16 * 64];         // Q fragments of the 4 heads of a round: [head][hi k-steps | lo k-steps][lane]
-    float2 ml[4 * 64];            // parked (m, l) of the odd-parity waves
-};
-
-template <int HD>
-__device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
-                                          const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
-                                          int max_seq, int b, int lim, float *part, int Hq, int Hkv, int NS,
-                                          float scale_log2e, uint4 *xhi, uint4 *xlo, AttnSmem &as, int kvh, int split, int t, bool near) {
-    constexpr int KSQ = HD / 16, HT = HD / 32, FPT = KSQ + 2 * HT;   // fragments per tile
-    constexpr int LPW = ATT_CH * FPT / 8;                            // staging loads per wave and chunk
-    constexpr int PF = AttnPartial<HD>::FLOATS;
-    const int tidx = opaque_tid();
-    const int w = tidx >> 6, lane = tidx & 63;
-    const int g = w & 3, par = w >> 2;
-    const int G = Hq / opaque_s(Hkv);
-    const int half = lane >> 5, qrow = lane & 31;
-    // b: the tile's sequence; lim: the key limit of this lane's query row (both read once at kernel start)
-    int maxlim = lim, minlim = lim;
-#pragma unroll
-    for (int off = 1; off < 32; off <<= 1) {
-        maxlim = max(maxlim, shx(maxlim, off));
-        minlim = min(minlim, shx(minlim, off));
-    }
-    const int nkt = (maxlim + 31) >> 5;
-    const int per = (nkt + NS - 1) / opaque_s(NS);
-    const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
-    const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
-    const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
-    const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);   // operand row -> key
-
-    for (int g0 = 0; g0 < G; g0 += 4) {
-        const bool active = g0 + g < G;
-        const int head = kvh * G + min(g0 + g, G - 1);
-        // Q fragments of the wave's head: the even-parity wave requests them and passes a copy to the odd-parity
-        // wave through LDS (a workgroup's load rate is the scarce resource of this phase).
-        uint4 qh[KSQ], ql[KSQ];
-        if (par == 0) {
-            const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
-#pragma unroll
-            for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
-        }
-        bool q_shared = false;
-        f32x16 oacc[HT];
-#pragma unroll
-        for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
-
-        for (int c0 = kt0; c0 < kt1; c0 += ATT_CH) {
-            const int ntile = min(ATT_CH, kt1 - c0);
-            __syncthreads();   // the previous chunk (or head round, or item) has been read
-            {   // stage: fragment f = w + 8 * i of the chunk; tiles past the range repeat the last one (unused)
-                uint4 st[LPW];
-#pragma unroll
-                for (int i = 0; i < LPW; ++i) {
-                    const int f = w + 8 * i, tl = f / FPT, fi = f % FPT;
-                    const int kt = c0 + min(tl, ntile - 1);
-                    const uint16_t *src;
-                    if (fi < KSQ) src = Kp + (size_t)(kt * 32 + keyperm) * HD + half * 8 + fi * 16;
-                    else src = Vp + (size_t)(((fi - KSQ) >> 1) * 32 + qrow) * max_seq + kt * 32 + 16 * half + 8 * ((fi - KSQ) & 1);
-                    st[i] = ld16_stream((const uint4 *)src);
-                }
-#pragma unroll
-                for (int i = 0; i < LPW; ++i) as.kv[(w + 8 * i) * 64 + lane] = st[i];
-                if (!q_shared && par == 0) {
-#pragma unroll
-                    for (int s = 0; s < KSQ; ++s) { as.q[(g * 2 * KSQ + s) * 64 + lane] = qh[s]; as.q[(g * 2 * KSQ + KSQ + s) * 64 + lane] = ql[s]; }
-                }
-            }
-            __syncthreads();
-            if (!q_shared && par == 1) {
-#pragma unroll
-                for (int s = 0; s < KSQ; ++s) { qh[s] = as.q[(g * 2 * KSQ + s) * 64 + lane]; ql[s] = as.q[(g * 2 * KSQ + KSQ + s) * 64 + lane]; }
-            }
-            q_shared = true;
-            if (active) {
-                for (int tl = par; tl < ntile; tl += 2) {
-                    const int kt = c0 + tl;
-                    const uint4 *fr = as.kv + (size_t)(tl * FPT) * 64 + lane;
-                    f32x16 sacc;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
-#pragma unroll
-                    for (int s = 0; s < KSQ; ++s) {
-                        const uint4 kf = fr[s * 64];
-                        sacc = mfma32(kf, qh[s], sacc);
-                        sacc = mfma32(kf, ql[s], sacc);
-                    }
-                    // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
-                    const int key0 = kt * 32 + 16 * half;
-                    if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            if (key0 + r >= lim) sacc[r] = -INFINITY;
-                    }
-                    float mx = sacc[0];
-#pragma unroll
-                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-                    mx = fmaxf(mx, shx(mx, 32));
-                    const float m_new = fmaxf(m_run, mx);
-                    float pr[16];
-                    if (m_new == -INFINITY) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) pr[r] = 0.f;
-                    } else {
-                        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
-                        const float mb = m_new * scale_log2e;
-                        float ls = 0.f;
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
-                        l_run = l_run * alpha + ls;
-                        m_run = m_new;
-                        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
-#pragma unroll
-                            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                                for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
-                        }
-                    }
-                    uint4 ph[2], pl[2];
-                    pack8_split(pr, ph[0], pl[0]);
-                    pack8_split(pr + 8, ph[1], pl[1]);
-#pragma unroll
-                    for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                        for (int s2 = 0; s2 < 2; ++s2) {
-                            const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
-                            oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
-                            oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
-                        }
-                }
-            }
-        }
-        // combine the two key parities of each head: odd-parity waves park (m, l, O), even-parity waves merge
-        __syncthreads();
-        float4 *ox = (float4 *)as.kv;
-        if (par == 1) {
-            as.ml[g * 64 + lane] = make_float2(m_run, l_run);
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    ox[((g * HT + tt) * 4 + q) * 64 + lane] = make_float4(oacc[tt][4 * q], oacc[tt][4 * q + 1], oacc[tt][4 * q + 2], oacc[tt][4 * q + 3]);
-        }
-        __syncthreads();
-        if (par == 0 && active) {
-            const float2 o_ml = as.ml[g * 64 + lane];
-            const float M = fmaxf(m_run, o_ml.x);
-            const float f0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * scale_log2e);
-            const float f1 = (o_ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((o_ml.x - M) * scale_log2e);
-            l_run = f0 * l_run + f1 * o_ml.y;
-            m_run = M;
-#pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = ox[((g * HT + tt) * 4 + q) * 64 + lane];
-                    oacc[tt][4 * q] = f0 * oacc[tt][4 * q] + f1 * v.x;
-                    oacc[tt][4 * q + 1] = f0 * oacc[tt][4 * q + 1] + f1 * v.y;
-                    oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
-                    oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
-                }
-            const float l_tot = l_run + shx(l_run, 32);
-            if (NS == 1) {
-                attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
-            } else {
-                float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
-#pragma unroll
-                for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                    for (int r2 = 0; r2 < 8; ++r2) st_agent2(pp + ((tt * 8 + r2) * 64 + lane) * 2, oacc[tt][2 * r2], oacc[tt][2 * r2 + 1]);
-                if (half == 0) st_agent2(pp + 32 * HD + 2 * qrow, m_run, l_tot);
-            }
-        }
-    }
-}
-
-// Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
-// of O^T tile tt.  All (M, L) pairs are requested at once, then the partial outputs 16 splits at a time, so a
-// merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
-template <int HD>
-__device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
-                                                int head, int t, int tt, int hh, int lane, bool near) {
-    constexpr int PF = AttnPartial<HD>::FLOATS;
-    const int half = lane >> 5, qrow = lane & 31;
-    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
-    float f[32];
-    float M = -INFINITY, L = 0.f;
-    {
-        float2 ml[32];
-#pragma unroll
-        for (int s = 0; s < 32; ++s) ml[s] = ld_x2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow, near);
-#pragma unroll
-        for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
-#pragma unroll
-        for (int s = 0; s < 32; ++s) {
-            f[s] = (s >= NS || ml[s].x == -INFINITY) ? 0.f : exp2f((ml[s].x - M) * scale_log2e);
-            L += f[s] * ml[s].y;
-        }
-    }
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = 0.f;
-#pragma unroll
-    for (int s0 = 0; s0 < 32; s0 += 16) {
-        if (s0 < NS) {
-            float2 v[16][4];
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-#pragma unroll
-                for (int r2 = 0; r2 < 4; ++r2)
-                    v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-#pragma unroll
-                for (int r2 = 0; r2 < 4; ++r2) { o[2 * r2] += f[s0 + u] * v[u][r2].x; o[2 * r2 + 1] += f[s0 + u] * v[u][r2].y; }
-        }
-    }
-    // registers 8*hh .. 8*hh+7 of tile tt: octets q = 2*hh and 2*hh + 1 (see attn_write_frag)
-    const float inv = L > 0.f ? 1.f / L : 0.f;
-    const int KS = Hq * HD / 16;
-#pragma unroll
-    for (int qq = 0; qq < 2; ++qq) {
-        const int q = 2 * hh + qq;
-        float mine[4], other[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = shx(mine[e], 32); }
-        if ((q & 1) == half) {
-            float v8[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { v8[e] = half ? other[e] : mine[e]; v8[4 + e] = half ? mine[e] : other[e]; }
-            uint4 hi, lo;
-            pack8_split(v8, hi, lo);
-            const size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
-            st16<true>(xhi + vec, hi);
-            st16<true>(xlo + vec, lo);
-        }
-    }
-}
-
 // per LM row: merge the per-group statistics (512 threads; same result as k_rowstat_final)
 __device__ __forceinline__ void rowstat_row(const RowStat *stat, int ncg_v, float T, RowResult *res, int row, float *scr) {
     const int tidx = opaque_tid();
@@ -712,7 +447,7 @@ __device__ __forceinline__ void gemm_phase(const PassArgs &p, GemmArgs &a, int e
                                            const Grouping &gr, unsigned &epoch, int &ns) {
     a.W = g.W; a.KS = g.KS; a.S = g.S; a.N = g.ncg * CG; a.near = (gr.near && (p.allow_near & 1)) ? 1 : 0; a.h_near = (gr.near && (p.allow_near & 2)) ? 1 : 0;
     const int tidx = opaque_tid();
-    const int w = tidx >> 6, lane = tidx & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;
     // The first piece's first weights travel while the previous phase's dependency chain resolves; a workgroup
     // without a piece makes a harmless in-range request so that wb is defined on every path.
     uint4 wb[D][4];
@@ -810,7 +545,7 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
             const int NSo = opaque_s(p.NS), nkvo = opaque_s(nkvl);
             const int split = j % NSo, kvh = ((j / NSo) % nkvo) * gr.G + gr.gi, t = j / (NSo * nkvo);
             attn_item<HD>(x.qh, x.ql, Kl, Vl, p.kv_seq_stride, p.kv_head_stride, p.max_seq, s_seq[t],
-                          s_lim[t * 32 + (opaque_tid() & 31)], p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t, gr.near && (p.allow_near & 4));
+                          s_lim[t * 32 + (opaque_tid() & 31)], p.opart, p.Hq, p.Hkv, p.NS, p.scale_log2e, x.x1h, x.x1l, smem.at, kvh, split, t);
         }
         drain_vmem();
         stamp(p, ns);
@@ -821,7 +556,7 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
             const int n = ntiles * nkvl * Gq * HT * 2;
             bar_wait(p, epoch);
             stamp(p, ns);
-            const int mt_ = opaque_tid(), w = mt_ >> 6, lane = mt_ & 63;
+            const int mt_ = opaque_tid(), w = __builtin_amdgcn_readfirstlane(mt_ >> 6), lane = mt_ & 63;
             for (int j = w * gr.R + gr.r; j < n; j += 8 * gr.R) {
                 const int Gqo = opaque_s(Gq), nkvo = opaque_s(nkvl);
                 const int hh = j & 1, tt = (j >> 1) % HT, gq = (j / (2 * HT)) % Gqo;
