@@ -30,9 +30,12 @@ HBM_PEAK_GBS = 8000.0
 
 
 # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain copy of known size gives): 18.51 GB read and
-# 1.61 GB written by one k_pass<128,1> launch of the qwen3_8b verify pass (15.77 GB algorithmic).
-MEASURED_TRAFFIC = {("qwen3_8b", "k_pass"): 18.51e9 + 1.61e9}
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain copy of known size gives), qwen3_8b verify pass:
+#  - k_gemm (one kernel per operation, 145 launches per pass): 113.7 MB read + 3.6 MB written per launch on
+#    average (104.4 MB algorithmic);
+#  - k_pass (the persistent kernel, DEER_PERSISTENT=1): 18.51 GB read + 1.61 GB written per launch
+#    (15.77 GB algorithmic).
+MEASURED_TRAFFIC = {("qwen3_8b", "k_gemm"): 113.7e6 + 3.6e6, ("qwen3_8b", "k_pass"): 18.51e9 + 1.61e9}
 
 
 def trunc_geom(k, mean):
@@ -276,6 +279,7 @@ def main():
         gemm_label = "k_pass (persistent verify pass: all layers' GEMMs, block attention, LM head)"
     else:
         gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
+        traffic = MEASURED_TRAFFIC.get((args.config, "k_gemm"))
     gemm_gbs = g_bytes / max(g_ms * 1e-3, 1e-12) / 1e9
     if t.n_experts:   # grouped expert GEMMs touch a data-dependent set of experts: use the pass-level figure
         gemm_gbs = (wbytes + kvbytes) / (tv * 1e-3) / 1e9
