@@ -87,6 +87,7 @@ struct deer_ctx {
     std::vector<int> h_len, h_ing_n, h_finished;
     std::string err;
     // persistent pass kernel
+    int n_cus = 0;                   // compute units of the device
     int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
     int pass_mode = 0;               // 0: one kernel per operation, 1: persistent kernel where possible
     bool pass_used = false;          // a pass kernel has run since the error flag was last read
@@ -273,7 +274,9 @@ const char *check_params(const deer_init_params *p) {
 // exist; long-K matrices prefer ~256 blocks.
 int choose_split(int N, int KS, int zgroups) {
     const int blocks = (N / CG) * zgroups;
-    const int target = KS > 256 ? 256 : 192;
+    static const int t_short = getenv("DEER_SPLIT_SHORT") ? atoi(getenv("DEER_SPLIT_SHORT")) : 192;
+    static const int t_long = getenv("DEER_SPLIT_LONG") ? atoi(getenv("DEER_SPLIT_LONG")) : 256;
+    const int target = KS > 256 ? t_long : t_short;
     int S = (target + blocks - 1) / blocks;
     S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
@@ -380,9 +383,11 @@ int run_pass_persistent(deer_ctx *c, int model, int ntiles, int max_limit, const
     pa.S_o = split(d, m.kattn / 16);
     pa.S_gu = split(2 * m.F, d / 16);
     pa.S_d = split(d, m.F / 16);
-    {   // a wide gate/up matrix (more than half as many column groups as workgroups) is cut into equal
+    {   // a wide gate/up matrix (more than half as many column groups as workgroups) can be cut into equal
         // consecutive shares instead; a column group then has at most KS / u + 2 pieces
-        static const bool stream_gu = !(getenv("DEER_PASS_GU_SHARES") && atoi(getenv("DEER_PASS_GU_SHARES")) == 0);
+        // Off by default: measured on the 8B shape, 192 whole column groups on 256 workgroups (a quarter idle in
+        // this phase, no partial tiles) give 4.74 ms per pass, equal shares with two pieces each 4.89 ms.
+        static const bool stream_gu = getenv("DEER_PASS_GU_SHARES") && atoi(getenv("DEER_PASS_GU_SHARES")) == 1;
         const int ncg = 2 * m.F / CG, KS = d / 16;
         const int u = (ncg * KS / nb) / 8 * 8;   // a lower bound of the share under either grouping
         pa.stream_gu = (stream_gu && ncg > nb / 2 && u >= 16 && ((size_t)KS / u + 2) * 2 * m.F <= PART_COLS) ? 1 : 0;
@@ -645,6 +650,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
         int occ = std::min({pass_occupancy<128, 1>(), pass_occupancy<128, 2>(), pass_occupancy<64, 1>(), pass_occupancy<64, 2>(),
                             pass_occupancy<32, 1>(), pass_occupancy<32, 2>()});
+        c->n_cus = cus;
         c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
         if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = atoi(e) == 1 ? 1 : 0;
         (void)hipGetLastError();

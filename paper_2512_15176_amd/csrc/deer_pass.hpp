@@ -279,7 +279,7 @@ __device__ __forceinline__ void pass_finish(int epi, const GemmArgs &a, GemmSmem
 
 // One piece of GEMM work.  wb holds the piece's first D weight k-steps, requested by gemm_phase.
 template <int MT, int D>
-__device__ __forceinline__ void gemm_item(const PassArgs &p, const GemmArgs &a, int epi, GemmSmem &sm, const Piece &pc,
+__device__ __forceinline__ void gemm_item(const GemmArgs &a, int epi, GemmSmem &sm, const Piece &pc,
                                           uint4 (&wb)[D][4]) {
     const int tidx = opaque_tid();
     const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;
@@ -457,7 +457,7 @@ __device__ __forceinline__ void gemm_phase(const PassArgs &p, GemmArgs &a, int e
     bar_wait(p, epoch);   // the phase's input is complete
     stamp(p, ns);
     while (piece_valid(it)) {
-        gemm_item<MT, D>(p, a, epi, sm, pc, wb);
+        gemm_item<MT, D>(a, epi, sm, pc, wb);
         piece_advance(g, gr, it, pc);
         if (piece_valid(it)) { pc = piece_at(g, gr, it); w_issue<D>(wb, g, pc, w, lane); }
     }
