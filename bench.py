@@ -173,6 +173,90 @@ def cpu_baseline(cfg, k, prefix, e_ncommit, batch=1):
     }
 
 
+def extras(eng, torch, k, T, vocab, x_pending):
+    """Block-size sweep, the k = 1 target step (an autoregressive step of the target alone) and the draft
+    pass timed after commits of m = 1, 9, 25, 32 tokens (rows the drafter has to ingest first).
+    Batch 1, T = 0.  x_pending: the last committed token (the first row of the next verify pass)."""
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def iters(kk, reps, warm=2):
+        rows = []
+        for i in range(warm + reps):
+            e = [ev() for _ in range(4)]
+            e[0].record()
+            dr = eng.draft_block(kk, T, di.SAMPLING_SEED)
+            e[1].record()
+            eng.verify_block(kk, T, dr)
+            e[2].record()
+            _, com, _ = eng.accept_and_commit(kk, T, di.SAMPLING_SEED)
+            e[3].record()
+            torch.cuda.synchronize()
+            if i >= warm:
+                rows.append([e[j].elapsed_time(e[j + 1]) for j in range(3)])
+        return [float(x) for x in np.median(np.array(rows), axis=0)], com[0][-1]
+
+    sweep = {}
+    for kk in (4, 8, 16, 32):
+        if kk > k:
+            continue
+        (td, tv, ta), x_pending = iters(kk, 10)
+        tot = td + tv + ta
+        sweep[str(kk)] = {"draft_ms": td, "verify_ms": tv, "accept_ms": ta,
+                          "tokens_per_s_mean_accept_k/4": trunc_geom(kk, kk / 4)[1] / (tot * 1e-3),
+                          "tokens_per_s_mean_accept_3k/4": trunc_geom(kk, 3 * kk / 4)[1] / (tot * 1e-3)}
+    (_, tv1, ta1), x_pending = iters(1, 10)
+    ar_ms = tv1 + ta1
+
+    # the target's greedy continuation from the current state, one committed token at a time (a random block
+    # is rejected at its first row, and whatever is accepted equals the target's argmax anyway)
+    L0 = int(eng.get_lengths()[0])
+    g = torch.Generator(device="cuda")
+    g.manual_seed(di.SAMPLING_SEED)
+    rnd = torch.randint(0, vocab, (1, k), generator=g, device="cuda", dtype=torch.int32)
+    greedy = []
+    while len(greedy) < k + 1:
+        eng.draft_block(k, T, di.SAMPLING_SEED)
+        eng.verify_block(k, T, rnd)
+        _, com, _ = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
+        greedy += com[0]
+    by_ingest = {}
+    for m in (1, 9, 25, 32):
+        if m > k:
+            continue
+        ts, got = [], []
+        for _ in range(5):
+            eng.set_prefilled([L0], [x_pending])      # back to the recorded state (the caches still hold it)
+            blk = greedy[: m - 1] + [(greedy[m - 1] + 1) % vocab] + [0] * (k - m)   # m-1 accepted, then a sure mismatch
+            inj = torch.tensor([blk], device="cuda", dtype=torch.int32)
+            eng.draft_block(k, T, di.SAMPLING_SEED)
+            eng.verify_block(k, T, inj)
+            _, _, ncom = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
+            got.append(int(ncom[0]))
+            e0, e1 = ev(), ev()
+            e0.record()
+            dr = eng.draft_block(k, T, di.SAMPLING_SEED)       # ingests the ncom committed tokens, then drafts
+            e1.record()
+            eng.verify_block(k, T, dr)
+            eng.accept_and_commit(k, T, di.SAMPLING_SEED)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        by_ingest[str(m)] = {"ingested_rows": got, "draft_ms": float(np.median(ts))}
+    return sweep, ar_ms, by_ingest
+
+
+def weighted_draft_ms(by_ingest, k, mean):
+    """Draft time averaged over the committed-token count of the previous iteration under the accepted-length law
+    (linear interpolation between the measured ingest sizes)."""
+    rho, _ = trunc_geom(k, mean)
+    ms = sorted(int(m) for m in by_ingest)
+    ts = [by_ingest[str(m)]["draft_ms"] for m in ms]
+    tot = 0.0
+    for a in range(k + 1):
+        p = (1 - rho) * rho ** a if a < k else rho ** k
+        tot += p * float(np.interp(min(a + 1, k), ms, ts))
+    return tot
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,6 +264,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="qwen3_8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the block-size sweep, the k=1 target step and the draft-by-ingest-size timings")
     ap.add_argument("--skip-prefill", action="store_true",
                     help="profiling aid: declare the prefix prefilled without running the models (zero caches)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -199,7 +285,7 @@ def main():
     long_prefix = prefix * B > 8192          # a real prefill of these would dominate the run
     if long_prefix:
         args.steps, args.warmup = min(args.steps, 10), min(args.warmup, 2)
-    max_seq = (prefix + (args.steps + args.warmup + 8) * k + k + 63) // 64 * 64
+    max_seq = (prefix + (args.steps + args.warmup + 8) * k + k + 512 + 63) // 64 * 64
     eng = DeerEngine(t, d, B, max_seq, k, di.mask_token_id(t.vocab), -1, False)
     load_random_model(eng, binding.DEER_TARGET, t, di.TARGET_SEED)
     load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
@@ -241,7 +327,7 @@ def main():
     acc_hist = np.zeros(k + 1, dtype=np.int64)
     t0 = time.perf_counter()
     for i in range(args.steps):
-        acc, _, _ = step(evs[i])
+        acc, com, _ = step(evs[i])
         for a in acc:
             acc_hist[a] += 1
     torch.cuda.synchronize()
@@ -265,7 +351,7 @@ def main():
         p_ms, p_n, p_bytes = p_ms + r2[0], p_n + r2[1], p_bytes + r2[2]
         g_ms, g_n, g_bytes = g_ms + r0[0], g_n + r0[1], g_bytes + r0[2]
         a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
-        eng.accept_and_commit(k, T, di.SAMPLING_SEED)
+        _, com, _ = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
     eng.debug_profile(False)
     wbytes, kvbytes = verify_bytes(t, prefix, k, B)
 
@@ -307,6 +393,16 @@ def main():
         "attention_kernel": {"launches": int(a_n), "avg_launch_us": a_ms / max(a_n, 1) * 1e3,
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }
+    if B == 1 and T == 0.0 and not args.no_extras:
+        sweep, ar_ms, by_ingest = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        out["block_size_sweep"] = sweep
+        out["target_step_k1_ms"] = ar_ms
+        out["draft_ms_by_ingested_rows"] = by_ingest
+        wd8, wd24 = weighted_draft_ms(by_ingest, k, k / 4), weighted_draft_ms(by_ingest, k, 3 * k / 4)
+        out["draft_ms_weighted"] = {"mean_accept_k/4": wd8, "mean_accept_3k/4": wd24}
+        # speed-up over the target decoding alone, the analogue of the paper's speed-up ratio under the stated law
+        out["speedup_over_target_alone"] = {"mean_accept_k/4": en8 * ar_ms / (wd8 + tv + ta),
+                                            "mean_accept_3k/4": en24 * ar_ms / (wd24 + tv + ta)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, k, prefix, B * en8, B)
     eng.close()
