@@ -311,12 +311,17 @@ def residual_distribution(logp, logq):
     return w / np.sum(w)
 
 
-def accept_block_sampling(logp, logq, yhat, rng, pos0):
+def accept_block_sampling(logp, logq, yhat, rng, pos0, bonus=False):
     """Lines "for i = 1..k" of Algorithm 1 under reading R1 (stop at the first rejection).
 
     logp[k][V] = log p_AR(. | x_{1:j+i-1}) with the draft prefix, logq[k][V] = log q_theta(. |
     x_{1:j}); yhat[k] the drafted tokens; pos0 = 0-indexed position of y^_1 (= j).
-    Returns (a, correction): a accepted drafts, then the residual sample, or None if a == k."""
+    Returns (a, correction): a accepted drafts, then the residual sample, or None if a == k.
+
+    bonus (an extension beside Algorithm 1, off by default): logp has a (k+1)-th row, log p_AR(. |
+    x_{1:j}, y^_1..y^_k), and when all k drafts are accepted one more token is drawn from it.  No draft
+    stands at that position, so the residual of Eq. "resample" with q = 0 is p itself; the Appendix
+    Theorem's induction step applies unchanged (a draw from p given an exactly distributed prefix)."""
     k = len(yhat)
     for i in range(k):
         y = int(yhat[i])
@@ -324,16 +329,21 @@ def accept_block_sampling(logp, logq, yhat, rng, pos0):
             continue
         c = rng.categorical(residual_logweights(logp[i], logq[i]), pos0 + i, TAG_RESID)
         return i, int(c)
+    if bonus:
+        return k, int(rng.categorical(logp[k], pos0 + k, TAG_RESID))
     return k, None
 
 
-def accept_block_greedy(target_argmax, yhat):
+def accept_block_greedy(target_argmax, yhat, bonus=False):
     """T = 0 limit (reading R5): q is one-hot at y^_i and p one-hot at the target's argmax, so
-    alpha_i = [y^_i == argmax] and the residual is one-hot at the argmax."""
+    alpha_i = [y^_i == argmax] and the residual is one-hot at the argmax.  With bonus, target_argmax
+    has k+1 entries and the last one is committed after k accepted drafts."""
     k = len(yhat)
     for i in range(k):
         if int(yhat[i]) != int(target_argmax[i]):
             return i, int(target_argmax[i])
+    if bonus:
+        return k, int(target_argmax[k])
     return k, None
 
 
@@ -373,14 +383,16 @@ class TransformerPair:
         pos = np.arange(self.dc.n, j + k)
         return self.d.forward(ids, pos, self.dc, drafter_block_mask(m, k), m, logits_rows=np.arange(m, m + k))
 
-    def verify_logits(self, yhat):
+    def verify_logits(self, yhat, bonus=False):
         """z^t_i, i=1..k: one target pass over rows [x_j, y^_1 .. y^_{k-1}], causal in the block.
-        All k rows' K,V are written; commit() rolls the cache length back."""
+        All k rows' K,V are written; commit() rolls the cache length back.
+        bonus: the last draft y^_k is a row too (k+1 rows), so the pass also yields z^t_{k+1}."""
         j = len(self.x)
         k = len(yhat)
         assert self.tc.n == j - 1
-        ids = [self.x[-1]] + [int(t) for t in yhat[:-1]]
-        return self.t.forward(ids, np.arange(j - 1, j - 1 + k), self.tc, causal_mask(k), k)
+        ids = [self.x[-1]] + [int(t) for t in (yhat if bonus else yhat[:-1])]
+        n = len(ids)
+        return self.t.forward(ids, np.arange(j - 1, j - 1 + n), self.tc, causal_mask(n), n)
 
     def commit(self, tokens):
         """Append the committed tokens; the target cache rolls back to (new length - 1)."""
@@ -391,12 +403,13 @@ class TransformerPair:
         return list(self.x)
 
 
-def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None):
+def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None, bonus=False):
     """One pass of Algorithm 1's while-body.  Returns a dict with the drafted block, accepted
     length a, committed tokens, and the two logit blocks (for parity checks).
 
     draft_override: tokens to use instead of the drafter's own pick (tests inject blocks that
-    force a given accepted length; random-init drafters are almost never accepted at T=0)."""
+    force a given accepted length; random-init drafters are almost never accepted at T=0).
+    bonus: verify k+1 rows and commit a (k+1)-th target token after k accepted drafts."""
     j = len(pair.prefix())
     zd = pair.draft_logits(k)
     if T == 0.0:
@@ -405,11 +418,11 @@ def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None):
         yhat = [rng.categorical(zd[i] / T, j + i, TAG_DRAFT) for i in range(k)]
     if draft_override is not None:
         yhat = [int(t) for t in draft_override]
-    zt = pair.verify_logits(yhat)
+    zt = pair.verify_logits(yhat, bonus)
     if T == 0.0:
-        a, c = accept_block_greedy([argmax_lowest(zt[i]) for i in range(k)], yhat)
+        a, c = accept_block_greedy([argmax_lowest(zt[i]) for i in range(len(zt))], yhat, bonus)
     else:
-        a, c = accept_block_sampling(log_softmax(zt / T), log_softmax(zd / T), yhat, rng, j)
+        a, c = accept_block_sampling(log_softmax(zt / T), log_softmax(zd / T), yhat, rng, j, bonus)
     committed = list(yhat[:a]) + ([] if c is None else [c])
     if eos_id >= 0 and eos_id in committed:
         committed = committed[: committed.index(eos_id) + 1]
@@ -417,12 +430,12 @@ def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None):
     return dict(draft=yhat, accept_len=a, committed=committed, draft_logits=zd, target_logits=zt)
 
 
-def deer_decode(pair, prompt, k, T, n_new, rng, eos_id=-1):
+def deer_decode(pair, prompt, k, T, n_new, rng, eos_id=-1, bonus=False):
     """Algorithm 1: repeat draft -> verify -> accept until n_new tokens (or EOS) are committed."""
     pair.prefill(prompt)
     out, accepts = [], []
     while len(out) < n_new:
-        it = deer_iteration(pair, k, T, rng, eos_id)
+        it = deer_iteration(pair, k, T, rng, eos_id, bonus=bonus)
         out.extend(it["committed"])
         accepts.append(it["accept_len"])
         if eos_id >= 0 and eos_id in it["committed"]:
@@ -459,13 +472,13 @@ def ar_decode(target: Decoder, prompt, n_new, T=0.0, rng=None, capacity=None):
 # =============================================================================================
 
 
-def deer_iteration_tabular(prefix, k, target_logp, drafter_logq, rng):
+def deer_iteration_tabular(prefix, k, target_logp, drafter_logq, rng, bonus=False):
     """Algorithm 1's while-body with the two models given as functions:
     target_logp(prefix_list) -> log p_AR(. | prefix); drafter_logq(prefix_list, i) -> log
     q_theta(x_{j+i} = . | x_{1:j}), i = 1..k.  rng supplies draft_token / accept / residual."""
     j = len(prefix)
     logq = np.stack([drafter_logq(prefix, i + 1) for i in range(k)])
     yhat = [rng.categorical(logq[i], j + i, TAG_DRAFT) for i in range(k)]
-    logp = np.stack([target_logp(list(prefix) + yhat[:i]) for i in range(k)])
-    a, c = accept_block_sampling(logp, logq, yhat, rng, j)
+    logp = np.stack([target_logp(list(prefix) + yhat[:i]) for i in range(k + (1 if bonus else 0))])
+    a, c = accept_block_sampling(logp, logq, yhat, rng, j, bonus)
     return list(yhat[:a]) + ([] if c is None else [c]), a
