@@ -206,6 +206,15 @@ def extras(eng, torch, k, T, vocab, x_pending):
                           "tokens_per_s_mean_accept_3k/4": trunc_geom(kk, 3 * kk / 4)[1] / (tot * 1e-3)}
     (_, tv1, ta1), x_pending = iters(1, 10)
     ar_ms = tv1 + ta1
+    bonus = None
+    if k >= 31:   # bonus-token variant: 31 drafts + the pending token = 32 target rows, up to 32 committed tokens
+        eng.set_bonus_token(True)
+        (td, tv, ta), x_pending = iters(31, 10)
+        eng.set_bonus_token(False)
+        tot = td + tv + ta
+        bonus = {"k": 31, "draft_ms": td, "verify_ms": tv, "accept_ms": ta}
+        for name, mean in (("k/4", 31 / 4), ("3k/4", 3 * 31 / 4)):   # E[committed] = E[accepted] + 1: a rejection is
+            bonus[f"tokens_per_s_mean_accept_{name}"] = (mean + 1.0) / (tot * 1e-3)   # replaced, k acceptances are extended
 
     # the target's greedy continuation from the current state, one committed token at a time (a random block
     # is rejected at its first row, and whatever is accepted equals the target's argmax anyway)
@@ -241,7 +250,7 @@ def extras(eng, torch, k, T, vocab, x_pending):
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
         by_ingest[str(m)] = {"ingested_rows": got, "draft_ms": float(np.median(ts))}
-    return sweep, ar_ms, by_ingest
+    return sweep, ar_ms, by_ingest, bonus
 
 
 def weighted_draft_ms(by_ingest, k, mean):
@@ -394,7 +403,9 @@ def main():
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }
     if B == 1 and T == 0.0 and not args.no_extras:
-        sweep, ar_ms, by_ingest = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        sweep, ar_ms, by_ingest, bonus = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        if bonus:
+            out["bonus_token_variant"] = bonus
         out["block_size_sweep"] = sweep
         out["target_step_k1_ms"] = ar_ms
         out["draft_ms_by_ingested_rows"] = by_ingest

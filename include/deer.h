@@ -147,6 +147,17 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_toke
 int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed,
                            int32_t *accept_len_host, int32_t *committed_host, int32_t *n_committed_host);
 
+/* Bonus token (an extension beside Alg. 1, off by default; Appendix, Theorem: its induction step is a
+ * draw from p_AR given an exactly distributed prefix, which holds for one more position).  When enabled,
+ * deer_verify_block feeds k + 1 rows [x_j, y^_1 .. y^_k] (draft_tokens_dev is read in full) and
+ * deer_accept_and_commit, after k accepted drafts, commits a (k+1)-th token: the argmax of p_{k+1} at
+ * T = 0, else a draw from p_{k+1} made with the residual stream of the counter generator at position
+ * j + k (a residual with no draft to subtract).  Then n_committed[b] <= k + 1 and committed_host holds
+ * batch * (k + 1) entries with stride k + 1.  The rows of a sequence stay within one 32-row tile, so
+ * calls need k <= 31 while the bonus token is on (DEER_EINVAL otherwise).  Not allowed between
+ * deer_draft_block and deer_accept_and_commit (DEER_ESTATE). */
+int deer_set_bonus_token(deer_ctx *c, int enable);
+
 int deer_destroy(deer_ctx *c);
 const char *deer_last_error(const deer_ctx *c); /* c may be NULL: last init-time error */
 

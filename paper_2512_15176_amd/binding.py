@@ -17,7 +17,7 @@ STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACIT
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
-           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode"]
+           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token"]
 
 
 class DeerError(RuntimeError):
@@ -75,6 +75,7 @@ def load_library(path: str = LIB_PATH):
     lib.deer_verify_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.deer_accept_and_commit.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.deer_destroy.argtypes = [C.c_void_p]
+    lib.deer_set_bonus_token.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
     lib.deer_get_lengths.argtypes = [C.c_void_p, C.c_void_p]
     lib.deer_get_kv_layout.argtypes = [C.c_void_p, C.c_int, C.POINTER(KvLayout)]
@@ -136,6 +137,7 @@ class DeerEngine:
         self.ctx = ctx
         self._timeline_on = False
         self.batch = 0
+        self.bonus = 0
         self._draft = torch.zeros(max_batch * 32, dtype=torch.int32, device=self.device)
 
     # -- helpers ---------------------------------------------------------------------------------
@@ -215,10 +217,14 @@ class DeerEngine:
         self._verify_arg = draft_dev   # keep alive until accept
         self._check(self.lib.deer_verify_block(self.ctx, k, T, draft_dev.data_ptr()))
 
+    def set_bonus_token(self, enable):
+        self._check(self.lib.deer_set_bonus_token(self.ctx, int(bool(enable))))
+        self.bonus = int(bool(enable))
+
     def accept_and_commit(self, k, T=0.0, seed=0):
         acc = np.zeros(self.batch, dtype=np.int32)
         ncom = np.zeros(self.batch, dtype=np.int32)
-        com = np.zeros((self.batch, k), dtype=np.int32)
+        com = np.zeros((self.batch, k + self.bonus), dtype=np.int32)
         self._check(self.lib.deer_accept_and_commit(self.ctx, k, T, seed, acc.ctypes.data, com.ctypes.data, ncom.ctypes.data))
         return acc, [com[b, : ncom[b]].tolist() for b in range(self.batch)], ncom
 

@@ -83,6 +83,7 @@ struct deer_ctx {
     int cur_k = 0;
     float cur_T = 0.f;
     int max_tiles = 0;
+    int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
     std::string err;
@@ -760,6 +761,7 @@ int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *dr
     if (!c) return DEER_EINVAL;
     if (!draft_dev || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
     if (c->state != ST_PREFILLED) return fail(c, DEER_ESTATE, "draft_block needs a prefilled or committed state");
+    if (k + c->bonus > 32) return fail(c, DEER_EINVAL, "with the bonus token on, k must be at most 31 (k + 1 rows per tile)");
     const int B = c->batch;
     int maxlim = 0, any_ing = 0;
     for (int b = 0; b < B; ++b) {
@@ -791,14 +793,15 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     if (c->state != ST_DRAFTED) return fail(c, DEER_ESTATE, "verify_block must follow draft_block");
     if (k != c->cur_k || T != c->cur_T) return fail(c, DEER_EINVAL, "k and T must match the draft_block call");
     const int B = c->batch;
+    const int nrows = k + c->bonus;   // [x_j, y^_1 .. y^_{k-1}] and, with the bonus token, y^_k
     int maxlim = 0;
-    for (int b = 0; b < B; ++b) maxlim = std::max(maxlim, c->h_len[b] - 1 + k);
+    for (int b = 0; b < B; ++b) maxlim = std::max(maxlim, c->h_len[b] - 1 + nrows);
     Work &w = c->wk;
-    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k, c->p.target.vocab);
+    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k, nrows, c->p.target.vocab);
     LAUNCHCHK(c, "k_rows_verify");
-    LmPlan lm{true, 0, 1, B, k, T, 0};
+    LmPlan lm{true, 0, 1, B, nrows, T, 0};
     double keys = 0;
-    for (int b = 0; b < B; ++b) keys += c->h_len[b] - 1 + k;
+    for (int b = 0; b < B; ++b) keys += c->h_len[b] - 1 + nrows;
     int rc = run_pass(c, DEER_TARGET, B, maxlim, lm, keys);
     if (rc) return rc;
     c->wk_draft = draft_dev;
@@ -815,23 +818,33 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
     Work &w = c->wk;
     const int V = c->p.target.vocab;
     if (T == 0.f)
-        hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET], k, c->p.eos_token_id);
+        hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET], k,
+                           c->p.eos_token_id, c->bonus);
     else
         hipLaunchKernelGGL(k_accept_sample, dim3(B), dim3(1024), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET],
-                           w.res[DEER_DRAFTER], w.logits[DEER_TARGET], w.logits[DEER_DRAFTER], k, V, T, seed, c->p.eos_token_id);
+                           w.res[DEER_DRAFTER], w.logits[DEER_TARGET], w.logits[DEER_DRAFTER], k, V, T, seed, c->p.eos_token_id,
+                           c->bonus);
     LAUNCHCHK(c, "k_accept");
+    const int cs = k + c->bonus;   // committed tokens per sequence: at most k, or k + 1 with the bonus token
     HIPCHK(c, hipMemcpyAsync(acc, w.ao.accept_len, B * 4, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(ncom, w.ao.n_committed, B * 4, hipMemcpyDeviceToHost, c->stream));
-    HIPCHK(c, hipMemcpyAsync(committed, w.ao.committed, (size_t)B * k * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipMemcpyAsync(committed, w.ao.committed, (size_t)B * cs * 4, hipMemcpyDeviceToHost, c->stream));
     if (int rc = pass_error_fetch(c)) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (int rc = pass_error_check(c)) return rc;
     for (int b = 0; b < B; ++b) {
         c->h_len[b] += ncom[b];
         c->h_ing_n[b] = ncom[b];
-        if (c->p.eos_token_id >= 0 && ncom[b] > 0 && committed[(size_t)b * k + ncom[b] - 1] == c->p.eos_token_id) c->h_finished[b] = 1;
+        if (c->p.eos_token_id >= 0 && ncom[b] > 0 && committed[(size_t)b * cs + ncom[b] - 1] == c->p.eos_token_id) c->h_finished[b] = 1;
     }
     c->state = ST_PREFILLED;
+    return DEER_OK;
+}
+
+int deer_set_bonus_token(deer_ctx *c, int enable) {
+    if (!c) return DEER_EINVAL;
+    if (c->state == ST_DRAFTED || c->state == ST_VERIFIED) return fail(c, DEER_ESTATE, "the bonus token cannot change inside an iteration");
+    c->bonus = enable ? 1 : 0;
     return DEER_OK;
 }
 
@@ -850,7 +863,7 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
     if (!out || model < 0 || model > 1) return fail(c, DEER_EINVAL, "bad model or null pointer");
     if (c->cur_k < 1) return fail(c, DEER_ESTATE, "no pass has run yet");
     if (!c->p.keep_logits && c->cur_T == 0.f) return fail(c, DEER_ESTATE, "logits were not kept (keep_logits = 0 and T = 0)");
-    const size_t n = (size_t)c->batch * c->cur_k * c->p.target.vocab;
+    const size_t n = (size_t)c->batch * (c->cur_k + (model == DEER_TARGET ? c->bonus : 0)) * c->p.target.vocab;
     if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
     HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
     if (int rc = pass_error_fetch(c)) return rc;

@@ -285,16 +285,17 @@ struct RowMeta {        // device arrays over the rows of a pass
     int *tile_seq;                   // [tiles]
 };
 
-// verify rows of sequence b: tile b; row i < k: [x_j, y^_1 .. y^_{k-1}] at positions j-1+i
+// verify rows of sequence b: tile b; row i < nrows: [x_j, y^_1 .. y^_{nrows-1}] at positions j-1+i, with
+// nrows = k, or k + 1 when the bonus token is on (the last draft is a row too)
 // token ids that reach the embedding gather are forced into [0, vocab): drafts come from caller memory
 __device__ __forceinline__ int safe_tok(int t, int vocab) { return (t < 0 || t >= vocab) ? 0 : t; }
 
-__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k, int vocab) {
+__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k, int nrows, int vocab) {
     int b = blockIdx.x, i = threadIdx.x;
     int row = b * 32 + i;
     int j = st.len[b];
     if (i == 0) rm.tile_seq[b] = b;
-    if (i < k) {
+    if (i < nrows) {
         int p = j - 1 + i;
         rm.tok[row] = safe_tok((i == 0) ? st.pending[b] : draft[b * k + i - 1], vocab);
         rm.pos[row] = p;
@@ -1453,16 +1454,18 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
 // ------------------------------------------------------------------------------------------
 // acceptance and commit, one block per sequence
 // ------------------------------------------------------------------------------------------
-struct AcceptOut { int *accept_len, *n_committed, *committed; };   // device [B], [B], [B][k]
+struct AcceptOut { int *accept_len, *n_committed, *committed; };   // device [B], [B], [B][k + bonus]
 
+// bonus = 1: the target pass had k + 1 rows and `corr` is also the extra token after k accepted drafts
 __device__ __forceinline__ void commit_tokens(SeqState st, AcceptOut out, int b, int k, int a, int corr, const int *d,
-                                              int eos) {
+                                              int eos, int bonus) {
     // thread 0 only
-    int n = (a < k) ? a + 1 : k;
+    const int cs = k + bonus;
+    int n = (a < k) ? a + 1 : cs;
     int fin = 0;
     for (int i = 0; i < n; ++i) {
         int tok = (i < a) ? d[i] : corr;
-        out.committed[b * k + i] = tok;
+        out.committed[b * cs + i] = tok;
         st.ing_tok[b * 32 + i] = tok;
         if (eos >= 0 && tok == eos) { n = i + 1; fin = 1; break; }
     }
@@ -1470,33 +1473,37 @@ __device__ __forceinline__ void commit_tokens(SeqState st, AcceptOut out, int b,
     out.n_committed[b] = n;
     st.ing_n[b] = n;
     st.len[b] += n;
-    st.pending[b] = out.committed[b * k + n - 1];
+    st.pending[b] = out.committed[b * cs + n - 1];
     if (fin) st.finished[b] = 1;
 }
 
-// T = 0: accept while the draft equals the target's argmax; the first mismatch is replaced by it
+// T = 0: accept while the draft equals the target's argmax; the first mismatch is replaced by it; with the
+// bonus token on, k matches are followed by the argmax of row k
 __global__ void k_accept_greedy(SeqState st, AcceptOut out, const int *__restrict__ draft,
-                                const RowResult *__restrict__ tres, int k, int eos) {
+                                const RowResult *__restrict__ tres, int k, int eos, int bonus) {
     const int b = blockIdx.x;
     if (threadIdx.x != 0) return;
     if (st.finished[b]) { out.accept_len[b] = 0; out.n_committed[b] = 0; return; }
     const int *d = draft + b * k;
-    int a = k, corr = -1;
+    const int kt = k + bonus;
+    int a = k, corr = bonus ? tres[b * kt + k].argmax : -1;
     for (int i = 0; i < k; ++i) {
-        int tgt = tres[b * k + i].argmax;
+        int tgt = tres[b * kt + i].argmax;
         if (d[i] != tgt) { a = i; corr = tgt; break; }
     }
-    commit_tokens(st, out, b, k, a, corr, d, eos);
+    commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
 }
 
 // T > 0: u_i <= min(1, p_i(y^_i) / q_i(y^_i)) in log space, stop at the first rejection and draw the
 // replacement from max(0, p_i - q_i) by Gumbel-max (falls back to p_i when the residual is empty).
+// With the bonus token on, k acceptances are followed by a draw from p_{k+1} (a residual without a draft:
+// the same generator stream at position j + k, weights p).
 __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut out, const int *__restrict__ draft,
                                                         const RowResult *__restrict__ tres,
                                                         const RowResult *__restrict__ dres,
                                                         const float *__restrict__ tlogits,
                                                         const float *__restrict__ dlogits, int k, int V, float T,
-                                                        uint64_t seed, int eos) {
+                                                        uint64_t seed, int eos, int bonus) {
     __shared__ int s_a;
     __shared__ float sv[1024]; __shared__ int sx[1024]; __shared__ int s_any[1024];
     const int b = blockIdx.x;
@@ -1505,15 +1512,16 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
         return;
     }
     const int *d = draft + b * k;
+    const int kt = k + bonus;           // target rows per sequence
     const int j = st.len[b];
     const float invT = 1.f / T;
     if (threadIdx.x == 0) {
         int a = k;
         for (int i = 0; i < k; ++i) {
-            const size_t r = (size_t)b * k + i;
+            const size_t rt = (size_t)b * kt + i, rd = (size_t)b * k + i;
             const int y = d[i];
-            const float logp = tlogits[r * V + y] * invT - tres[r].lse;
-            const float logq = dlogits[r * V + y] * invT - dres[r].lse;
+            const float logp = tlogits[rt * V + y] * invT - tres[rt].lse;
+            const float logq = dlogits[rd * V + y] * invT - dres[rd].lse;
             const float u = uniform01(row_key(seed, TAG_ACCEPT, (uint64_t)b, (uint64_t)(j + i)), 0);
             if (!(logf(u) <= fminf(0.f, logp - logq))) { a = i; break; }
         }
@@ -1522,17 +1530,20 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
     __syncthreads();
     const int a = s_a;
     int corr = -1;
-    if (a < k) {
-        const size_t r = (size_t)b * k + a;
-        const float lt = tres[r].lse, ld = dres[r].lse;
+    if (a < k || bonus) {
+        const bool has_q = a < k;       // a drafted token stands at this position
+        const size_t rt = (size_t)b * kt + a, rd = (size_t)b * k + (has_q ? a : 0);
+        const float lt = tres[rt].lse, ld = has_q ? dres[rd].lse : 0.f;
         const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
         float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
         for (int v = threadIdx.x; v < V; v += 1024) {
-            const float logp = tlogits[r * V + v] * invT - lt;
-            const float logq = dlogits[r * V + v] * invT - ld;
-            const float diff = expf(logp) - expf(logq);
+            const float logp = tlogits[rt * V + v] * invT - lt;
             const float gn = gumbel(key, (uint64_t)v);
-            if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+            if (has_q) {
+                const float logq = dlogits[rd * V + v] * invT - ld;
+                const float diff = expf(logp) - expf(logq);
+                if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+            }
             argmax_merge(bestp, bpi, logp + gn, v);
         }
         s_any[threadIdx.x] = any;
@@ -1551,7 +1562,7 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
         }
         corr = (sx[0] >= 0 && sx[0] < V) ? sx[0] : 0;   // all-NaN rows never update the index
     }
-    if (threadIdx.x == 0) commit_tokens(st, out, b, k, a, corr, d, eos);
+    if (threadIdx.x == 0) commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
 }
 
 }  // namespace deer

@@ -1,6 +1,7 @@
 """GPU parity at the real layer widths (8B-, 4B- and drafter-shaped layers, 2 layers each so the
 fp32 oracle finishes in seconds): prefixes that span several 32-row tiles with a ragged tail, block
-sizes 32 and 16, forced accepted lengths so the drafter ingests 1, k and a middling number of rows."""
+sizes 32 and 16, forced accepted lengths so the drafter ingests 1, k and a middling number of rows; the
+bonus-token variant at k = 31 (32 target rows, up to 32 committed tokens) in both launch modes."""
 import numpy as np
 import pytest
 
@@ -21,6 +22,8 @@ CASES = {
                                  drafter=di.scaled(di.DRAFTER_05B, n_layers=1), prefix=97, k=16,
                                  forced=[16, 3]),
 }
+CASES["8b_layers_bonus"] = dict(CASES["8b_layers"], k=31, forced=[31, 0, 9, 31], bonus=True)
+CASES["8b_layers_bonus_persistent"] = dict(CASES["8b_layers_bonus"], persistent=True)
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -29,7 +32,11 @@ def test_lockstep_at_real_widths(name):
     case = CASES[name]
     t, d, k, n = case["target"], case["drafter"], case["k"], case["prefix"]
     wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    bonus = bool(case.get("bonus"))
     eng = make_engine(t, d, wt, wd, 1, 512, k)
+    eng.set_bonus_token(bonus)
+    if case.get("persistent"):
+        eng.debug_pass_mode(1)
     pair = make_pair(t, d, wt, wd, 512, dtype=np.float32)
     prompt = di.prompt_ids(t.vocab, n)
     pair.prefill(prompt)
@@ -39,16 +46,17 @@ def test_lockstep_at_real_widths(name):
     for a_want in case["forced"]:
         truth = O.ar_decode(dec, pair.prefix(), k)
         block = list(truth)
+        n_want = a_want + 1 if (bonus or a_want < k) else k
         if a_want < k:
             block[a_want] = (block[a_want] + 1) % t.vocab
         gd = eng.draft_block(k, 0.0, 0).cpu().numpy()[0]
-        res = O.deer_iteration(pair, k, 0.0, None, draft_override=block)
+        res = O.deer_iteration(pair, k, 0.0, None, draft_override=block, bonus=bonus)
         zd = res["draft_logits"]
         ed = float(np.abs(eng.debug_get_logits(1, k)[0] - zd).max())
         ok = top2_margin(zd) > 1e-2
         assert np.array_equal(gd[ok], np.argmax(zd, -1)[ok])
         eng.verify_block(k, 0.0, torch.tensor([block], dtype=torch.int32, device="cuda"))
-        et = float(np.abs(eng.debug_get_logits(0, k)[0] - res["target_logits"]).max())
+        et = float(np.abs(eng.debug_get_logits(0, k + bonus)[0] - res["target_logits"]).max())
         worst_d, worst_t = max(worst_d, ed), max(worst_t, et)
         assert ed < TOL and et < TOL, (ed, et)
         acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
@@ -58,6 +66,6 @@ def test_lockstep_at_real_widths(name):
             assert top2_margin(res["target_logits"])[first] < 1e-2, (acc, com, res["accept_len"], res["committed"])
             eng.prefill([pair.prefix()])      # put both sides back on the oracle's text
         else:
-            assert acc[0] == a_want
+            assert acc[0] == a_want and ncom[0] == n_want
     print(f"\n[{name}] max |logit error|: drafter {worst_d:.2e}, target {worst_t:.2e}")
     eng.close()
