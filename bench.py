@@ -402,6 +402,16 @@ def main():
         "attention_kernel": {"launches": int(a_n), "avg_launch_us": a_ms / max(a_n, 1) * 1e3,
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }
+    if not long_prefix and not args.skip_prefill:
+        # prefill of the prefix through the same kernels, 512 rows per chunk: algorithmic flops 2 * rows * parameters
+        # of the layers (the LM head is not evaluated during prefill), both models
+        def layer_params(sh):
+            a = sh.d_model * (sh.n_q_heads + 2 * sh.n_kv_heads) * sh.head_dim + sh.n_q_heads * sh.head_dim * sh.d_model
+            f = sh.top_k * 3 * sh.d_model * sh.d_ff_expert if sh.n_experts else 3 * sh.d_model * sh.d_ff
+            return sh.n_layers * (a + f)
+        fl = 2.0 * B * ((prefix - 1) * layer_params(t) + prefix * layer_params(d))
+        out["prefill"] = {"tokens": B * prefix, "seconds": prefill_s, "tokens_per_s": B * prefix / prefill_s,
+                          "gemm_TFLOPs_algorithmic": fl / 1e12, "frac_of_bf16_mfma_peak": fl / prefill_s / 2.5e15}
     if B == 1 and T == 0.0 and not args.no_extras:
         sweep, ar_ms, by_ingest, bonus = extras(eng, torch, k, T, t.vocab, com[0][-1])
         if bonus:

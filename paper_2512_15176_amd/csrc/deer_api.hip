@@ -22,6 +22,7 @@ namespace {
 thread_local std::string g_init_error;
 
 constexpr int PASS_MAX_BLOCKS = 512;   // workgroups of the persistent pass kernel (one per compute unit)
+constexpr int PREFILL_TILES = 16;    // rows of a prefill chunk / 32: the weights are streamed once per chunk
 constexpr int MAX_NS = 32;          // key-range splits of block attention
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
@@ -197,7 +198,7 @@ void plan_model(ModelRT &m, const deer_model_cfg &c, int max_batch, int max_seq)
 // Carves the workspace; with base == nullptr only computes the size.
 void plan_work(Work &w, const deer_init_params &p, char *base) {
     const int B = p.max_batch;
-    const int MAXT = std::max(2 * B, 2), MAXR = MAXT * 32;
+    const int MAXT = std::max(2 * B, PREFILL_TILES), MAXR = MAXT * 32;
     const deer_model_cfg &t = p.target, &d = p.drafter;
     const size_t dmax = std::max(t.d_model, d.d_model);
     const size_t kattn = std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
@@ -295,7 +296,13 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     a.counters = c->wk.gemm_cnt;
     dim3 grid(a.N / CG, a.S, zg);
     ProfScope ps(c, 0, (double)a.N * K * 2.0);
-    if (MT == 2) hipLaunchKernelGGL((k_gemm<2, EPI>), grid, dim3(512), 0, c->stream, a);
+    static const int zmap = getenv("DEER_GEMM_ZMAP") ? atoi(getenv("DEER_GEMM_ZMAP")) : 1;
+    if (zg > 1 && zmap) {   // the row-tile groups of a (column group, K split) pair share an XCD's L2
+        const int ncg = a.N / CG, pairs8 = (ncg * a.S + 7) / 8;
+        dim3 g1((unsigned)(pairs8 * 8 * zg));
+        if (MT == 2) hipLaunchKernelGGL((k_gemm_rows<2, EPI>), g1, dim3(512), 0, c->stream, a, ncg, zg);
+        else hipLaunchKernelGGL((k_gemm_rows<1, EPI>), g1, dim3(512), 0, c->stream, a, ncg, zg);
+    } else if (MT == 2) hipLaunchKernelGGL((k_gemm<2, EPI>), grid, dim3(512), 0, c->stream, a);
     else hipLaunchKernelGGL((k_gemm<1, EPI>), grid, dim3(512), 0, c->stream, a);
     LAUNCHCHK(c, "k_gemm");
     return DEER_OK;
@@ -627,7 +634,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         c->m[i].kv = (uint16_t *)bufs->kv[i];
     }
     plan_work(c->wk, *p, (char *)bufs->workspace);
-    c->max_tiles = std::max(2 * p->max_batch, 2);
+    c->max_tiles = std::max(2 * p->max_batch, PREFILL_TILES);
     // caches must hold finite values everywhere: masked keys are multiplied by zero weights
     for (int i = 0; i < 2; ++i) {
         e = hipMemsetAsync(bufs->kv[i], 0, need.kv[i], c->stream);
@@ -727,8 +734,8 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(w.ids, ids + off, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
         for (int model = 0; model < 2; ++model) {
             const int nrows = (model == DEER_TARGET) ? n - 1 : n;   // the last token stays pending for the target
-            for (int c0 = 0; c0 < nrows; c0 += 64) {
-                const int nr = std::min(64, nrows - c0);
+            for (int c0 = 0; c0 < nrows; c0 += 32 * PREFILL_TILES) {
+                const int nr = std::min(32 * PREFILL_TILES, nrows - c0);
                 const int ntiles = (nr + 31) / 32;
                 hipLaunchKernelGGL(k_rows_prefill, dim3(ntiles), dim3(32), 0, c->stream, w.rm, w.ids, b, c0, nr);
                 LAUNCHCHK(c, "k_rows_prefill");

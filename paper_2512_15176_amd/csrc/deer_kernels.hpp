@@ -766,7 +766,9 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
 // One work item of the weight-streaming GEMM: column group cg, K split s, row-tile group z.
 // DEFER = false: with S > 1 the block that arrives last at the group's counter finishes the group;
 // DEFER = true: the partial tile is left for a later gemm_finish (after a grid-wide barrier).
-template <int MT, int EPI, bool COH, bool DEFER>
+// WSTREAM: weights are read once by the whole grid (non-temporal loads); false: several workgroups of an XCD read
+// the same weights at about the same time and should find them in its L2 (plain loads).
+template <int MT, int EPI, bool COH, bool DEFER, bool WSTREAM = true>
 __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int cg, int s, int z, int ncg) {
     const int tidx = opaque_tid();
     float *red = sm.red, *tile = sm.tile, *s_rstd = sm.rstd;
@@ -803,7 +805,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         int ks = ks0 + dd;
         if (ks < ks1) {
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
+            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)ks * 64) : wp[nb * wstride + (size_t)ks * 64];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)ks * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)ks * 64); }
         }
@@ -823,7 +825,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
                 int kn = ks + D;
                 if (kn < ks1) {
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
+                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)kn * 64) : wp[nb * wstride + (size_t)kn * 64];
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)kn * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)kn * 64); }
                 }
@@ -862,6 +864,19 @@ template <int MT, int EPI>
 __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
     __shared__ GemmSmem sm;
     gemm_block<MT, EPI, false, false>(a, sm, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.x);
+}
+
+// The same GEMM over Z > 1 row-tile groups (batched passes, prefill chunks): every group needs the same weights.
+// 1-D grid; workgroup ids 8 apart run on the same XCD at about the same time, so the Z workgroups of one
+// (column group, K split) pair p get the ids 8 * ((p / 8) * Z + z) + p % 8: the first of them to ask for a
+// weight line fetches it from memory, the others find it in that XCD's L2.
+template <int MT, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_rows(const GemmArgs a, int ncg, int Z) {
+    __shared__ GemmSmem sm;
+    const int lin = blockIdx.x, x = lin & 7, q = lin >> 3;
+    const int z = q % Z, p = 8 * (q / Z) + x;
+    if (p >= ncg * a.S) return;
+    gemm_block<MT, EPI, false, false, false>(a, sm, p % ncg, p / ncg, z, ncg);
 }
 
 // ------------------------------------------------------------------------------------------

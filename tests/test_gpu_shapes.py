@@ -19,7 +19,7 @@ CASES = {
                       drafter=di.scaled(di.DRAFTER_05B, n_layers=2, vocab=16384), prefix=203, k=32,
                       forced=[0, 32, 7]),
     "4b_layers_full_vocab": dict(target=di.scaled(di.CONFIGS["qwen3_4b"]["target"], n_layers=2),
-                                 drafter=di.scaled(di.DRAFTER_05B, n_layers=1), prefix=97, k=16,
+                                 drafter=di.scaled(di.DRAFTER_05B, n_layers=1), prefix=613, k=16,   # two prefill chunks: 512 + 101 rows
                                  forced=[16, 3]),
 }
 CASES["8b_layers_bonus"] = dict(CASES["8b_layers"], k=31, forced=[31, 0, 9, 31], bonus=True)
@@ -33,11 +33,11 @@ def test_lockstep_at_real_widths(name):
     t, d, k, n = case["target"], case["drafter"], case["k"], case["prefix"]
     wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
     bonus = bool(case.get("bonus"))
-    eng = make_engine(t, d, wt, wd, 1, 512, k)
+    eng = make_engine(t, d, wt, wd, 1, 1024, k)
     eng.set_bonus_token(bonus)
     if case.get("persistent"):
         eng.debug_pass_mode(1)
-    pair = make_pair(t, d, wt, wd, 512, dtype=np.float32)
+    pair = make_pair(t, d, wt, wd, 1024, dtype=np.float32)
     prompt = di.prompt_ids(t.vocab, n)
     pair.prefill(prompt)
     eng.prefill([prompt])
