@@ -266,6 +266,53 @@ def weighted_draft_ms(by_ingest, k, mean):
     return tot
 
 
+def run_no_kv_cache(args):
+    """The setting of the paper's batch-scalability experiment (Sec. "Batch Inference Scalability", Table 5): no KV
+    cache is kept between iterations, so every iteration recomputes the whole sequence with both models (here: a
+    prefill of all committed tokens, then draft, verify and accept), for batch sizes 2, 4, 8, 16; the autoregressive
+    baseline recomputes the sequence for every single token.  Synthetic stand-in: Qwen3-8B-shaped target, sequences
+    of 512 committed tokens, k = 32, T = 0, random-init weights; throughput under the accepted-length law."""
+    import torch
+    from paper_2512_15176_amd import DeerEngine, binding
+    cfg = di.CONFIGS["qwen3_8b"]
+    t, d, k, seq_len, T = cfg["target"], cfg["drafter"], 32, 512, 0.0
+    eng = DeerEngine(t, d, 16, 1024, k, di.mask_token_id(t.vocab), -1, False)
+    load_random_model(eng, binding.DEER_TARGET, t, di.TARGET_SEED)
+    load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
+    _, en8 = trunc_geom(k, k / 4)
+    _, en24 = trunc_geom(k, 3 * k / 4)
+    rows = {}
+    for B in (2, 4, 8, 16):
+        prompts = [di.prompt_ids(t.vocab, seq_len, seq=b) for b in range(B)]
+
+        def iteration(kk):
+            eng.prefill(prompts)                       # both models over every committed token: nothing is reused
+            dr = eng.draft_block(kk, T, di.SAMPLING_SEED)
+            eng.verify_block(kk, T, dr)
+            eng.accept_and_commit(kk, T, di.SAMPLING_SEED)
+
+        res = {}
+        for name, kk in (("deer", k), ("target_alone", 1)):
+            iteration(kk)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps_nokv):
+                iteration(kk)
+            torch.cuda.synchronize()
+            res[name] = (time.perf_counter() - t0) / args.steps_nokv
+        rows[str(B)] = {"iteration_ms": res["deer"] * 1e3, "target_alone_step_ms": res["target_alone"] * 1e3,
+                        "tokens_per_s_mean_accept_8": B * en8 / res["deer"], "tokens_per_s_mean_accept_24": B * en24 / res["deer"],
+                        "target_alone_tokens_per_s": B / res["target_alone"],
+                        "speedup_mean_accept_8": en8 * res["target_alone"] / res["deer"],
+                        "speedup_mean_accept_24": en24 * res["target_alone"] / res["deer"]}
+    eng.close()
+    print(json.dumps({"metric": "committed tokens/s without a KV cache (every iteration recomputes the sequence), 8B shape, k=32",
+                      "unit": "tokens/s", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"qwen3_8b widths, {seq_len} committed tokens per sequence, k={k}, T=0, batch 2/4/8/16",
+                                 "accepted_length_law": "truncated geometric, mean 8 / 24"},
+                      "by_batch": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -279,11 +326,18 @@ def main():
                     help="profiling aid: declare the prefix prefilled without running the models (zero caches)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="profiling aid: also run one plain 1 GiB device copy (scale factor for byte counters)")
+    ap.add_argument("--mode", default="step", choices=["step", "no_kv_cache"],
+                    help="step: the draft-verify step (default, the benchmark line); no_kv_cache: the paper's batch experiment "
+                         "setting, every iteration recomputes the sequence (its own JSON line)")
+    ap.add_argument("--steps-nokv", type=int, default=3)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding or collectives are built); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.mode == "no_kv_cache":
+        return run_no_kv_cache(args)
 
     import torch
     from paper_2512_15176_amd import DeerEngine, binding

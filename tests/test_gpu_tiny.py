@@ -166,3 +166,34 @@ def test_call_order_and_argument_errors(setup):
     with pytest.raises(DeerError) as e:
         eng.prefill([di.prompt_ids(CFG["target"].vocab, 250)])   # 250 + 8 > max_seq 256
     assert e.value.status == -3
+
+
+def test_recomputing_both_caches_every_iteration_gives_the_same_text(setup):
+    """The setting of the paper's batch experiment (no KV cache kept between iterations): a prefill of every
+    committed token before each iteration must lead to the same logits and commits as the kept caches."""
+    eng, wt, wd, torch = setup
+    t, k = CFG["target"], CFG["k"]
+    prompt = [int(v) for v in di.prompt_ids(t.vocab, 45, seq=4)]
+
+    def run(recompute):
+        text, logs = list(prompt), []
+        eng.prefill([text])
+        for _ in range(6):
+            if recompute:
+                eng.prefill([text])
+            dr = eng.draft_block(k, 0.0, 0)
+            zd = eng.debug_get_logits(1, k)[0]
+            eng.verify_block(k, 0.0, dr)
+            zt = eng.debug_get_logits(0, k)[0]
+            acc, com, _ = eng.accept_and_commit(k, 0.0, 0)
+            logs.append((zd, zt, int(acc[0]), com[0]))
+            text += com[0]
+        return logs
+
+    kept, redone = run(False), run(True)
+    for it, ((zd0, zt0, a0, c0), (zd1, zt1, a1, c1)) in enumerate(zip(kept, redone)):
+        assert np.abs(zd0 - zd1).max() < TOL_STORED and np.abs(zt0 - zt1).max() < TOL_STORED, it
+        if (a0, c0) != (a1, c1):     # only a near-tie may decide differently; the texts part ways there
+            assert min(top2_margin(zt0).min(), top2_margin(zd0).min()) < 1e-2, (it, a0, c0, a1, c1)
+            break
+    assert it >= 2
