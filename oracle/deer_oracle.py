@@ -375,11 +375,13 @@ class TransformerPair:
             self.t.forward(self.x[:-1], np.arange(n - 1), self.tc, causal_mask(n - 1), n - 1, logits_rows=[])
         self.d.forward(self.x, np.arange(n), self.dc, causal_mask(n), n, logits_rows=[])
 
-    def draft_logits(self, k):
-        """z^d_i, i=1..k: one drafter pass over the not-yet-cached committed rows plus k MASK rows."""
+    def draft_logits(self, k, fixed=()):
+        """z^d_i, i=1..k: one drafter pass over the not-yet-cached committed rows plus k block rows.
+        The block rows hold the MASK id, except the first len(fixed) ones, which hold the tokens `fixed`
+        (a partially filled block, see draft_block_multipass); every block row sees the whole block."""
         j = len(self.x)
         m = j - self.dc.n
-        ids = self.x[self.dc.n:] + [self.mask_id] * k
+        ids = self.x[self.dc.n:] + [int(t) for t in fixed] + [self.mask_id] * (k - len(fixed))
         pos = np.arange(self.dc.n, j + k)
         return self.d.forward(ids, pos, self.dc, drafter_block_mask(m, k), m, logits_rows=np.arange(m, m + k))
 
@@ -403,7 +405,33 @@ class TransformerPair:
         return list(self.x)
 
 
-def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None, bonus=False):
+def multipass_bounds(k, n_passes):
+    """Positions fixed after pass s = 1..n_passes of a multi-pass draft: the first ceil(k * s / n_passes)."""
+    return [-((-k * s) // n_passes) for s in range(n_passes + 1)]
+
+
+def draft_block_multipass(pair, k, T, rng, n_passes):
+    """Block regeneration (Sec. "Generative Capabilities": the drafter takes a partially masked block and fills
+    in the rest) used as a multi-pass draft: pass s sees the tokens fixed so far at the first hi_{s-1} block
+    positions and MASK at the others, and fixes positions hi_{s-1} .. hi_s - 1 (left to right, equal shares).
+    Position i's token and the logits that define its law q_i are those of the pass that fixed it, so q_i
+    depends on x_{1:j} and on drafts at EARLIER positions only - the condition under which the acceptance rule
+    of Eq. "accept"/"resample" stays exact.  n_passes = 1 is the one-pass draft of Sec. 3.2.
+    Returns (tokens[k], logits[k][V])."""
+    j = len(pair.prefix())
+    hi = multipass_bounds(k, n_passes)
+    yhat, rows = [], []
+    for s in range(1, n_passes + 1):
+        if hi[s] == hi[s - 1]:
+            continue
+        z = pair.draft_logits(k, yhat)
+        for i in range(hi[s - 1], hi[s]):
+            rows.append(z[i])
+            yhat.append(argmax_lowest(z[i]) if T == 0.0 else rng.categorical(z[i] / T, j + i, TAG_DRAFT))
+    return yhat, np.stack(rows)
+
+
+def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None, bonus=False, n_draft_passes=1):
     """One pass of Algorithm 1's while-body.  Returns a dict with the drafted block, accepted
     length a, committed tokens, and the two logit blocks (for parity checks).
 
@@ -411,11 +439,14 @@ def deer_iteration(pair, k, T, rng, eos_id=-1, draft_override=None, bonus=False)
     force a given accepted length; random-init drafters are almost never accepted at T=0).
     bonus: verify k+1 rows and commit a (k+1)-th target token after k accepted drafts."""
     j = len(pair.prefix())
-    zd = pair.draft_logits(k)
-    if T == 0.0:
-        yhat = [argmax_lowest(zd[i]) for i in range(k)]
+    if n_draft_passes > 1:
+        yhat, zd = draft_block_multipass(pair, k, T, rng, n_draft_passes)
     else:
-        yhat = [rng.categorical(zd[i] / T, j + i, TAG_DRAFT) for i in range(k)]
+        zd = pair.draft_logits(k)
+        if T == 0.0:
+            yhat = [argmax_lowest(zd[i]) for i in range(k)]
+        else:
+            yhat = [rng.categorical(zd[i] / T, j + i, TAG_DRAFT) for i in range(k)]
     if draft_override is not None:
         yhat = [int(t) for t in draft_override]
     zt = pair.verify_logits(yhat, bonus)
@@ -472,13 +503,21 @@ def ar_decode(target: Decoder, prompt, n_new, T=0.0, rng=None, capacity=None):
 # =============================================================================================
 
 
-def deer_iteration_tabular(prefix, k, target_logp, drafter_logq, rng, bonus=False):
+def deer_iteration_tabular(prefix, k, target_logp, drafter_logq, rng, bonus=False, n_draft_passes=1):
     """Algorithm 1's while-body with the two models given as functions:
     target_logp(prefix_list) -> log p_AR(. | prefix); drafter_logq(prefix_list, i) -> log
-    q_theta(x_{j+i} = . | x_{1:j}), i = 1..k.  rng supplies draft_token / accept / residual."""
+    q_theta(x_{j+i} = . | x_{1:j}), i = 1..k.  rng supplies draft_token / accept / residual.
+    n_draft_passes > 1: pass s conditions the drafter on the drafts fixed so far, given to it as an extended
+    prefix: position i (past hi_{s-1} fixed ones) has the law drafter_logq(prefix + fixed, i - hi_{s-1})."""
     j = len(prefix)
-    logq = np.stack([drafter_logq(prefix, i + 1) for i in range(k)])
-    yhat = [rng.categorical(logq[i], j + i, TAG_DRAFT) for i in range(k)]
+    hi = multipass_bounds(k, n_draft_passes)
+    yhat, logq = [], []
+    for s in range(1, n_draft_passes + 1):
+        fixed = list(yhat)
+        for i in range(hi[s - 1], hi[s]):
+            logq.append(drafter_logq(list(prefix) + fixed, i + 1 - len(fixed)))
+            yhat.append(rng.categorical(logq[i], j + i, TAG_DRAFT))
+    logq = np.stack(logq)
     logp = np.stack([target_logp(list(prefix) + yhat[:i]) for i in range(k + (1 if bonus else 0))])
     a, c = accept_block_sampling(logp, logq, yhat, rng, j, bonus)
     return list(yhat[:a]) + ([] if c is None else [c]), a
