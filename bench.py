@@ -216,6 +216,21 @@ def extras(eng, torch, k, T, vocab, x_pending):
         for name, mean in (("k/4", 31 / 4), ("3k/4", 3 * 31 / 4)):   # E[committed] = E[accepted] + 1: a rejection is
             bonus[f"tokens_per_s_mean_accept_{name}"] = (mean + 1.0) / (tot * 1e-3)   # replaced, k acceptances are extended
 
+    multipass = {}
+    for n_passes in (2, 4):   # a block filled in from the left over several drafter passes
+        ts = []
+        for _ in range(6):
+            e0, e1 = ev(), ev()
+            e0.record()
+            dr = eng.draft_block_multipass(k, T, di.SAMPLING_SEED, n_passes)
+            e1.record()
+            eng.verify_block(k, T, dr)
+            _, com, _ = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        x_pending = com[0][-1]
+        multipass[str(n_passes)] = {"draft_ms": float(np.median(ts[1:]))}
+
     # the target's greedy continuation from the current state, one committed token at a time (a random block
     # is rejected at its first row, and whatever is accepted equals the target's argmax anyway)
     L0 = int(eng.get_lengths()[0])
@@ -250,7 +265,7 @@ def extras(eng, torch, k, T, vocab, x_pending):
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
         by_ingest[str(m)] = {"ingested_rows": got, "draft_ms": float(np.median(ts))}
-    return sweep, ar_ms, by_ingest, bonus
+    return sweep, ar_ms, by_ingest, bonus, multipass
 
 
 def weighted_draft_ms(by_ingest, k, mean):
@@ -467,7 +482,8 @@ def main():
         out["prefill"] = {"tokens": B * prefix, "seconds": prefill_s, "tokens_per_s": B * prefix / prefill_s,
                           "gemm_TFLOPs_algorithmic": fl / 1e12, "frac_of_bf16_mfma_peak": fl / prefill_s / 2.5e15}
     if B == 1 and T == 0.0 and not args.no_extras:
-        sweep, ar_ms, by_ingest, bonus = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        sweep, ar_ms, by_ingest, bonus, multipass = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        out["multipass_draft"] = multipass
         if bonus:
             out["bonus_token_variant"] = bonus
         out["block_size_sweep"] = sweep

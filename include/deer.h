@@ -135,6 +135,16 @@ int deer_set_prefilled(deer_ctx *c, int32_t batch, const int32_t *lens_host, con
  * position).  Writes draft tokens to draft_tokens_dev[batch][k] (int32). */
 int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *draft_tokens_dev);
 
+/* Multi-pass draft (block regeneration, Sec. "Generative Capabilities": the drafter fills in a partially
+ * masked block), an extension beside Alg. 1: n_passes drafter passes, 1 <= n_passes <= k.  Pass s sees the
+ * tokens fixed so far at the first ceil(k (s-1) / n_passes) block positions and MASK at the others, and
+ * fixes the positions up to ceil(k s / n_passes) (left to right, so the law a token is drawn from depends
+ * on the prefix and on EARLIER drafts only, which keeps the acceptance rule exact).  The logits and
+ * log-normalisers kept for deer_accept_and_commit are, per position, those of the pass that fixed it.
+ * n_passes = 1 is deer_draft_block.  Same state rules, errors and output as deer_draft_block. */
+int deer_draft_block_multipass(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t n_passes,
+                               int32_t *draft_tokens_dev);
+
 /* Target pass over rows [x_j, y^_1 .. y^_{k-1}] (block-causal over the cache), reading the
  * drafts from draft_tokens_dev[batch][k] - normally the buffer deer_draft_block filled; tests
  * may inject blocks.  Leaves per-row argmax / log-normaliser (and logits at T > 0) on device. */

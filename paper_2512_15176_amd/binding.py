@@ -17,7 +17,8 @@ STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACIT
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
-           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token"]
+           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token",
+           "deer_draft_block_multipass"]
 
 
 class DeerError(RuntimeError):
@@ -72,6 +73,7 @@ def load_library(path: str = LIB_PATH):
     lib.deer_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.deer_set_prefilled.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.deer_draft_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p]
+    lib.deer_draft_block_multipass.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32, C.c_void_p]
     lib.deer_verify_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.deer_accept_and_commit.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.deer_destroy.argtypes = [C.c_void_p]
@@ -210,6 +212,11 @@ class DeerEngine:
     def draft_block(self, k, T=0.0, seed=0):
         """Returns the device tensor [batch][k] (int32) of drafted tokens."""
         self._check(self.lib.deer_draft_block(self.ctx, k, T, seed, self._draft.data_ptr()))
+        return self._draft[: self.batch * k].view(self.batch, k)
+
+    def draft_block_multipass(self, k, T=0.0, seed=0, n_passes=1):
+        """As draft_block, in n_passes drafter passes over a block that is filled in from the left."""
+        self._check(self.lib.deer_draft_block_multipass(self.ctx, k, T, seed, n_passes, self._draft.data_ptr()))
         return self._draft[: self.batch * k].view(self.batch, k)
 
     def verify_block(self, k, T, draft_dev):

@@ -308,7 +308,7 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     return DEER_OK;
 }
 
-struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; };
+struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; int k_lo = 0; };
 
 template <int HD>
 int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float scale_log2e, double kv_bytes) {
@@ -356,7 +356,7 @@ int pass_occupancy() {
 // against 3.90 ms, the 0.5B drafter 2.80 ms against 2.53 ms.
 bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
     if (c->pass_mode != 1 || c->pass_blocks < 1 || c->prof_split) return false;
-    if (m.c.n_experts || ntiles > 2 || (lm.on && lm.n_tiles != 1)) return false;
+    if (m.c.n_experts || ntiles > 2 || (lm.on && (lm.n_tiles != 1 || lm.k_lo > 0))) return false;
     return m.c.d_model / CG <= 64;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
 }
 
@@ -557,11 +557,11 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         GemmArgs a = base;
         a.W = (const uint4 *)(m.w + m.off_lm); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = V;
         a.mt0 = lm.mt0; a.mt_stride = lm.mt_stride;
-        a.k = lm.k; a.T = lm.T; a.seed = lm.seed; a.stat = w.stat; a.ncg_v = V / CG;
+        a.k = lm.k; a.k_lo = lm.k_lo; a.T = lm.T; a.seed = lm.seed; a.stat = w.stat; a.ncg_v = V / CG;
         a.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
         int rc = launch_gemm<EPI_LMHEAD>(c, a, d, lm.n_tiles, 1);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_rowstat_final, dim3(lm.n_tiles * lm.k), dim3(256), 0, s, w.stat, V / CG, lm.T, w.res[model]);
+        hipLaunchKernelGGL(k_rowstat_final, dim3(lm.n_tiles * lm.k), dim3(256), 0, s, w.stat, V / CG, lm.T, w.res[model], lm.k, lm.k_lo);
         LAUNCHCHK(c, "k_rowstat_final");
     }
     return DEER_OK;
@@ -764,9 +764,10 @@ int deer_set_prefilled(deer_ctx *c, int32_t batch, const int32_t *lens, const in
     return upload_state(c, batch, lens, lens, last);
 }
 
-int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *draft_dev) {
+int deer_draft_block_multipass(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t n_passes, int32_t *draft_dev) {
     if (!c) return DEER_EINVAL;
     if (!draft_dev || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
+    if (n_passes < 1 || n_passes > k) return fail(c, DEER_EINVAL, "n_passes must be in 1..k");
     if (c->state != ST_PREFILLED) return fail(c, DEER_ESTATE, "draft_block needs a prefilled or committed state");
     if (k + c->bonus > 32) return fail(c, DEER_EINVAL, "with the bonus token on, k must be at most 31 (k + 1 rows per tile)");
     const int B = c->batch;
@@ -777,21 +778,33 @@ int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *dr
         any_ing |= c->h_ing_n[b] > 0;
     }
     Work &w = c->wk;
-    const int tps = any_ing ? 2 : 1;
-    hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps, c->p.drafter.vocab);
-    LAUNCHCHK(c, "k_rows_draft");
-    LmPlan lm{true, 0, tps, B, k, T, seed};
     double keys = 0;
     for (int b = 0; b < B; ++b) keys += c->h_len[b] + k;
-    int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm, keys);
-    if (rc) return rc;
-    hipLaunchKernelGGL(k_draft_finish, dim3(B), dim3(32), 0, c->stream, w.st, w.res[DEER_DRAFTER], draft_dev, k);
-    LAUNCHCHK(c, "k_draft_finish");
+    // pass s fixes block positions [lo, hi), lo = ceil(k (s-1) / n), hi = ceil(k s / n); the first pass also
+    // ingests the committed tokens the drafter has not cached yet
+    for (int s = 1; s <= n_passes; ++s) {
+        const int lo = (k * (s - 1) + n_passes - 1) / n_passes, hi = (k * s + n_passes - 1) / n_passes;
+        if (hi == lo) continue;
+        const int tps = any_ing ? 2 : 1;
+        hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps, c->p.drafter.vocab,
+                           draft_dev, lo);
+        LAUNCHCHK(c, "k_rows_draft");
+        LmPlan lm{true, 0, tps, B, k, T, seed, lo};
+        int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm, keys);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_draft_finish, dim3(B), dim3(32), 0, c->stream, w.st, w.res[DEER_DRAFTER], draft_dev, k, lo);
+        LAUNCHCHK(c, "k_draft_finish");
+        any_ing = 0;   // the device-side counts were cleared by k_draft_finish
+    }
     std::fill(c->h_ing_n.begin(), c->h_ing_n.end(), 0);
     c->cur_k = k;
     c->cur_T = T;
     c->state = ST_DRAFTED;
     return DEER_OK;
+}
+
+int deer_draft_block(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *draft_dev) {
+    return deer_draft_block_multipass(c, k, T, seed, 1, draft_dev);
 }
 
 int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev) {

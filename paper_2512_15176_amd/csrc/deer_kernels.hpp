@@ -309,7 +309,10 @@ __global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ d
 // draft rows of sequence b: tile 2b = k MASK rows at positions j..j+k-1 (see cache + ingested rows +
 // every MASK row; their K,V land in slots past the cached length and are never kept); tile 2b+1 =
 // the m not-yet-cached committed tokens, causal.  With tiles_per_seq == 1 only the MASK tile exists.
-__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq, int vocab) {
+// The first n_fixed block rows hold the tokens fixed[b][0 .. n_fixed) instead of the MASK id (a partially filled
+// block: a later pass of a multi-pass draft).
+__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq, int vocab,
+                             const int *__restrict__ fixed, int n_fixed) {
     int b = blockIdx.x, i = threadIdx.x;   // 64 threads
     int t = i >> 5, r = i & 31;
     if (t >= tiles_per_seq) return;
@@ -318,7 +321,8 @@ __global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int ti
     int j = st.len[b], dl = st.dr_len[b], m = st.ing_n[b];
     if (r == 0) rm.tile_seq[tile] = b;
     if (t == 0 && r < k) {
-        rm.tok[row] = mask_id; rm.pos[row] = j + r; rm.slot[row] = j + r; rm.limit[row] = j + k;
+        rm.tok[row] = r < n_fixed ? safe_tok(fixed[b * k + r], vocab) : mask_id;
+        rm.pos[row] = j + r; rm.slot[row] = j + r; rm.limit[row] = j + k;
     } else if (t == 1 && r < m) {
         rm.tok[row] = safe_tok(st.ing_tok[b * 32 + r], vocab); rm.pos[row] = dl + r; rm.slot[row] = dl + r; rm.limit[row] = dl + r + 1;
     } else {
@@ -425,6 +429,7 @@ struct GemmArgs {
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
     int k; float *logits; float T; uint64_t seed; RowStat *stat; int ncg_v;
+    int k_lo;   // rows below k_lo keep the logits and statistics of an earlier pass (multi-pass draft)
     // ROUTER: top-k of softmax over n_experts (<= 128), renormalised
     int n_experts, top_k; int *route_e; float *route_w;
 };
@@ -574,7 +579,7 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
     const int V = a.N, k = a.k;
     const float T = a.T;
     const int row = tidx >> 3, sub = tidx & 7;   // 8 threads per row, 16 columns each
-    const bool live = row < k;
+    const bool live = row < k && row >= a.k_lo;
     float m = -INFINITY, gm = -INFINITY, se = 0.f;
     int idx = 0x7fffffff, gidx = 0x7fffffff;
     float z[16];
@@ -1065,10 +1070,11 @@ struct RowResult {   // per LM row
 
 // one block per LM row: merge the per-group partials
 __global__ __launch_bounds__(256) void k_rowstat_final(const RowStat *__restrict__ stat, int ncg_v, float T,
-                                                       RowResult *__restrict__ res) {
+                                                       RowResult *__restrict__ res, int k, int k_lo) {
     __shared__ float sm[256]; __shared__ int si[256]; __shared__ float sg[256]; __shared__ int sgi[256];
     __shared__ float ss[256];
     const int row = blockIdx.x;
+    if (row % k < k_lo) return;   // kept from an earlier pass
     const RowStat *p = stat + (size_t)row * ncg_v;
     float m = -INFINITY, gm = -INFINITY; int idx = 0x7fffffff, gidx = 0x7fffffff;
     for (int g = threadIdx.x; g < ncg_v; g += 256) {
@@ -1108,9 +1114,9 @@ __global__ __launch_bounds__(256) void k_rowstat_final(const RowStat *__restrict
 }
 
 // draft pass tail: draft tokens out, drafter cache length advances over the ingested rows
-__global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, int *__restrict__ draft, int k) {
+__global__ void k_draft_finish(SeqState st, const RowResult *__restrict__ res, int *__restrict__ draft, int k, int k_lo) {
     int b = blockIdx.x, i = threadIdx.x;
-    if (i < k) draft[b * k + i] = res[b * k + i].sample;
+    if (i < k && i >= k_lo) draft[b * k + i] = res[b * k + i].sample;   // positions below k_lo were fixed by earlier passes
     if (i == 0) { st.dr_len[b] += st.ing_n[b]; st.ing_n[b] = 0; }
 }
 
