@@ -95,15 +95,13 @@ def fill_random_caches(eng, shape_by_model, lens):
     g = torch.Generator(device="cuda")
     g.manual_seed(di.KV_SEED)
     for model, shape in shape_by_model.items():
-        lay = eng.get_kv_layout(model)
-        kv = eng.kv_tensor(model)
-        L, B, H, hd, S = shape.n_layers, eng.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
-        K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
-        Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, hd, S)
-        for l in range(L):
+        views = eng.kv_views(model, shape)
+        H, hd = shape.n_kv_heads, shape.head_dim
+        for l in range(shape.n_layers):
             for b, n in enumerate(lens):
-                K[l, b, :, :n, :] = torch.randn(H, n, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
-                Vt[l, b, :, :, :n] = torch.randn(H, hd, n, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+                kr = torch.randn(n, H, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+                vr = torch.randn(n, H, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+                eng.write_kv_rows(views, l, b, kr, vr)
 
 
 def cpu_baseline(cfg, k, prefix, e_ncommit, batch=1):

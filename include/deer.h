@@ -207,8 +207,9 @@ int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int
 int deer_get_lengths(const deer_ctx *c, int32_t *len_host);
 
 /* Where cache rows live, so that a caller can inspect or pre-fill them:
- *   K[layer][seq][kv_head][slot][head_dim]  and  V stored transposed  Vt[layer][seq][kv_head][head_dim][slot],
- * bf16, slot < max_seq.  Offsets are in elements from the start of the model's kv buffer. */
+ *   K[layer][seq][kv_head][slot][head_dim]  and  V stored transposed in blocks of 32 slots,
+ *   Vt[layer][seq][kv_head][slot / 32][head_dim][slot % 32]  (the 8 KB of a 32-key tile are contiguous),
+ * bf16, slot < max_seq (a multiple of 64).  Offsets are in elements from the start of the model's kv buffer. */
 typedef struct {
     size_t k_base, v_base;            /* element offsets of K and Vt blocks                        */
     size_t layer_stride, seq_stride, head_stride; /* same for both                                 */

@@ -285,5 +285,27 @@ class DeerEngine:
         """The model's whole KV buffer as a flat int16 (bf16 bit) device tensor."""
         return self._kv[model].view(self.torch.int16)
 
+    def kv_views(self, model, shape):
+        """(K, Vt) views of the model's cache: K[layer][seq][kv_head][slot][head_dim] and
+        Vt[layer][seq][kv_head][slot // 32][head_dim][slot % 32], int16 bit patterns of bf16."""
+        lay = self.get_kv_layout(model)
+        kv = self.kv_tensor(model)
+        L, B, H, hd, S = shape.n_layers, self.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
+        K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
+        Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, S // 32, hd, 32)
+        return K, Vt
+
+    def write_kv_rows(self, views, layer, b, k_rows, v_rows):
+        """Writes cache slots 0..n-1 of sequence slot b: k_rows, v_rows are int16 device tensors [n][kv_head][head_dim]."""
+        K, Vt = views
+        n = k_rows.shape[0]
+        K[layer, b, :, :n, :] = k_rows.permute(1, 0, 2)
+        full, rem = n // 32, n % 32
+        v = v_rows.permute(1, 2, 0)                       # [kv_head][head_dim][n]
+        if full:
+            Vt[layer, b, :, :full] = v[:, :, : full * 32].reshape(v.shape[0], v.shape[1], full, 32).permute(0, 2, 1, 3)
+        if rem:
+            Vt[layer, b, :, full, :, :rem] = v[:, :, full * 32:]
+
     def synchronize(self):
         self.torch.cuda.current_stream(self.device).synchronize()

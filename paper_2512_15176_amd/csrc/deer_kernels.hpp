@@ -491,7 +491,8 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
                     st16<COH>((uint4 *)(a.kv.k + base + (size_t)slot * hd + i0), pack8(v));
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) st_u16<COH>(a.kv.vt + base + (size_t)(i0 + e) * a.kv.max_seq + slot, (uint16_t)f2bf(v[e]));
+                    for (int e = 0; e < 8; ++e)   // V^T in blocks of 32 slots: [slot / 32][channel][slot % 32]
+                        st_u16<COH>(a.kv.vt + base + (size_t)(slot >> 5) * (hd * 32) + (i0 + e) * 32 + (slot & 31), (uint16_t)f2bf(v[e]));
                 }
             }
         }
@@ -724,7 +725,9 @@ struct GemmSmem {
 };
 
 // Sums the S partial tiles of column group cg (row-tile group z) in order s = 0..S-1 and runs the epilogue.
-template <int MT, int EPI, bool COH>
+// RSTD_EARLY: sm.rstd already holds the RMSNorm factors of the group's MT row tiles (gemm_block computed them
+// while its first weights were on their way).
+template <int MT, int EPI, bool COH, bool RSTD_EARLY = false>
 __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int cg, int z) {
     const int tidx = opaque_tid();
     float *tile = sm.tile;
@@ -764,7 +767,7 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
             tp[0] = v[i].x; tp[1] = v[i].y;
         }
         __syncthreads();
-        run_epilogue<EPI, COH>(a, tile, sm.rstd, sm.red, hreg, cg, ct);
+        run_epilogue<EPI, COH, RSTD_EARLY>(a, tile, sm.rstd + 32 * mt, sm.red, hreg, cg, ct);
     }
 }
 
@@ -815,6 +818,14 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
             for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)ks * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)ks * 64); }
         }
     }
+    // RMSNorm factors of the input rows: their sums of squares were finished by the previous kernel, so they are
+    // requested now, behind the first weights, instead of as a dependent round trip inside the epilogue
+    constexpr bool RSTD_EARLY = !COH && EPI != EPI_RESID;
+    if (RSTD_EARLY) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            tile_rstd<COH>(a.ssq_in, s_rstd + 32 * mt, (a.mt0 + (z * MT + mt) * a.mt_stride) * 32, a.ncg_in, a.d_in, a.eps);
+    }
     for (int kb = ks0; kb < ks1; kb += D) {
 #pragma unroll
         for (int dd = 0; dd < D; ++dd) {
@@ -847,7 +858,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         if (EPI == EPI_RESID && S == 1) resid_prefetch<COH>(a, hreg, cg, a.mt0 + ct * a.mt_stride);
         reduce_waves_to_tile(acc[mt], red, tile, w, lane);
         if (S == 1) {
-            run_epilogue<EPI, COH>(a, tile, s_rstd, red, hreg, cg, ct);
+            run_epilogue<EPI, COH, RSTD_EARLY>(a, tile, s_rstd + 32 * mt, red, hreg, cg, ct);
         } else {
             float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
 #pragma unroll
@@ -862,7 +873,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     if (S == 1 || DEFER) return;
     // the block that arrives last at this column group's counter sums all partials and finishes
     if (!arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last)) return;
-    gemm_finish<MT, EPI, COH>(a, sm, cg, z);
+    gemm_finish<MT, EPI, COH, RSTD_EARLY>(a, sm, cg, z);
 }
 
 template <int MT, int EPI>
@@ -1177,22 +1188,22 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
 // Block attention item for a whole workgroup of 8 waves (both launch modes use it).
 //  - one (row tile, kv head, key-range split) item per workgroup; wave w serves query head (w & 3) of the
 //    GQA group on the key tiles of parity (w >> 2) of each staged chunk, so two waves per SIMD overlap;
-//  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested at once by the eight waves (one
-//    memory round trip per chunk, every fragment fetched once per workgroup instead of once per query head)
-//    and land in LDS in fragment order (direct-to-LDS loads); the next chunk travels into the other of two
-//    LDS buffers while the current chunk is multiplied;
-//  - Q fragments stay in registers; the even-parity wave of a head requests them and passes a copy to the
-//    odd-parity wave through the second LDS buffer before that buffer's first use;
+//  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested by the eight waves together (every
+//    fragment fetched once per workgroup instead of once per query head) and land in LDS in fragment order
+//    (direct-to-LDS loads, no registers held while they travel); ATT_NBUF chunk buffers form a ring, so
+//    ATT_NBUF - 1 chunks are on their way while one is multiplied, with one barrier per chunk;
+//  - Q fragments stay in registers, loaded by every wave for its own head;
 //  - the two key parities of a head are combined through LDS, then the result goes to the output
 //    projection's input (NS == 1) or to an un-normalised partial (M, L, O) for the merge.
 // Partials and outputs are written with agent-scope stores, so the item serves the persistent kernel
 // (consumers in the same kernel) and the per-operation path alike.  b: the tile's sequence; lim: the key
 // limit of this lane's query row.
 // ------------------------------------------------------------------------------------------
-constexpr int ATT_CH = 4;   // tiles per staged chunk
+constexpr int ATT_CH = 2;     // key tiles per staged chunk: one per key parity
+constexpr int ATT_NBUF = 4;   // chunk buffers: ATT_NBUF - 1 chunks (96 KB) are on their way while one is multiplied
 struct AttnSmem {
-    uint4 buf[2][ATT_CH * 16 * 64];   // [tile][fragment: K k-steps, then V (tile, half) pairs][lane]; 2 x 64 KB
-    float2 ml[4 * 64];                // parked (m, l) of the odd-parity waves
+    uint4 buf[ATT_NBUF][ATT_CH * 16 * 64];   // [tile][fragment: K k-steps, then V (tile, half) pairs][lane]; 4 x 32 KB
+    float2 ml[4 * 64];                       // parked (m, l) of the odd-parity waves
 };
 
 template <int HD>
@@ -1229,7 +1240,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
         const int ntile = min(ATT_CH, kt1 - c0);
         // lane offsets (elements) are rebuilt here from two small values, so that eight 64-bit addresses per
         // lane do not live (spilled) across the whole item
-        int ko = keyperm * HD + half * 8, vo = qrow * max_seq + 16 * half;
+        int ko = keyperm * HD + half * 8, vo = qrow * 32 + 16 * half;   // V^T block of a key tile: [channel][32 keys]
         asm volatile("" : "+v"(ko), "+v"(vo));
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
@@ -1237,12 +1248,11 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
             const int kt = c0 + min(tl, ntile - 1);
             const uint16_t *src;
             if (fi < KSQ) src = Kp + (ko + kt * 32 * HD + fi * 16);
-            else src = Vp + (vo + ((fi - KSQ) >> 1) * 32 * max_seq + kt * 32 + 8 * ((fi - KSQ) & 1));
+            else src = Vp + (vo + kt * (32 * HD) + ((fi - KSQ) >> 1) * (32 * 32) + 8 * ((fi - KSQ) & 1));
             __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
                                              (void __attribute__((address_space(3))) *)(dst + f * 64), 16, 0, 0);
         }
     };
-    auto stage_wait = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     for (int g0 = 0; g0 < G; g0 += 4) {
         const bool active = g0 + g < G;
@@ -1257,87 +1267,81 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
         if (nchunks > 0) {
             uint4 qh[KSQ], ql[KSQ];
             __syncthreads();   // the previous head round or item has been read
-            stage(as.buf[0], kt0);
-            if (par == 0) {
+            {   // this wave's Q fragments (requested first: every later wait covers them)
                 const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
 #pragma unroll
                 for (int s = 0; s < KSQ; ++s) { qh[s] = Qhi[qb + (size_t)s * 64]; ql[s] = Qlo[qb + (size_t)s * 64]; }
-#pragma unroll
-                for (int s = 0; s < KSQ; ++s) { as.buf[1][(g * 2 * KSQ + s) * 64 + lane] = qh[s]; as.buf[1][(g * 2 * KSQ + KSQ + s) * 64 + lane] = ql[s]; }
             }
-            stage_wait();
-            __syncthreads();
-            if (par == 1) {
 #pragma unroll
-                for (int s = 0; s < KSQ; ++s) { qh[s] = as.buf[1][(g * 2 * KSQ + s) * 64 + lane]; ql[s] = as.buf[1][(g * 2 * KSQ + KSQ + s) * 64 + lane]; }
-            }
-            if (nchunks > 1) __syncthreads();   // Q has been taken out of the second buffer
+            for (int c = 0; c < ATT_NBUF - 1; ++c)
+                if (c < nchunks) stage(as.buf[c], kt0 + c * ATT_CH);
 
             for (int ci = 0; ci < nchunks; ++ci) {
                 const int c0 = kt0 + ci * ATT_CH;
                 const int ntile = min(ATT_CH, kt1 - c0);
-                const bool more = ci + 1 < nchunks;
-                if (more) stage(as.buf[(ci + 1) & 1], c0 + ATT_CH);   // that buffer was last read two barriers ago
-                if (active) {
-                    for (int tl = par; tl < ntile; tl += 2) {
-                        const int kt = c0 + tl;
-                        const uint4 *fr = as.buf[ci & 1] + (size_t)(tl * FPT) * 64 + lane;
-                        f32x16 sacc;
+                // chunk ci has landed once at most the loads of the chunks requested after it are outstanding
+                const int later = min(ATT_NBUF - 2, nchunks - 1 - ci);
+                if (later >= 2) wait_loads<2 * LPW>(); else if (later == 1) wait_loads<LPW>(); else wait_loads<0>();
+                __syncthreads();   // every wave's share of chunk ci is in LDS, and chunk ci - 1 has been read by all
+                if (ci + ATT_NBUF - 1 < nchunks) stage(as.buf[(ci + ATT_NBUF - 1) % ATT_NBUF], c0 + (ATT_NBUF - 1) * ATT_CH);
+                if (active && par < ntile) {
+                    const int tl = par;
+                    const int kt = c0 + tl;
+                    const uint4 *fr = as.buf[ci % ATT_NBUF] + (size_t)(tl * FPT) * 64 + lane;
+                    f32x16 sacc;
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+                    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
-                        for (int s = 0; s < KSQ; ++s) {
-                            const uint4 kf = fr[s * 64];
-                            sacc = mfma32(kf, qh[s], sacc);
-                            sacc = mfma32(kf, ql[s], sacc);
-                        }
-                        // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
-                        const int key0 = kt * 32 + 16 * half;
-                        if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
-#pragma unroll
-                            for (int r = 0; r < 16; ++r)
-                                if (key0 + r >= lim) sacc[r] = -INFINITY;
-                        }
-                        float mx = sacc[0];
-#pragma unroll
-                        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
-                        mx = fmaxf(mx, shx(mx, 32));
-                        const float m_new = fmaxf(m_run, mx);
-                        float pr[16];
-                        if (m_new == -INFINITY) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) pr[r] = 0.f;
-                        } else {
-                            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
-                            const float mb = m_new * scale_log2e;
-                            float ls = 0.f;
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
-                            l_run = l_run * alpha + ls;
-                            m_run = m_new;
-                            if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
-#pragma unroll
-                                for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                                    for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
-                            }
-                        }
-                        uint4 ph[2], pl[2];
-                        pack8_split(pr, ph[0], pl[0]);
-                        pack8_split(pr + 8, ph[1], pl[1]);
-#pragma unroll
-                        for (int tt = 0; tt < HT; ++tt)
-#pragma unroll
-                            for (int s2 = 0; s2 < 2; ++s2) {
-                                const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
-                                oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
-                                oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
-                            }
+                    for (int s = 0; s < KSQ; ++s) {
+                        const uint4 kf = fr[s * 64];
+                        sacc = mfma32(kf, qh[s], sacc);
+                        sacc = mfma32(kf, ql[s], sacc);
                     }
+                    // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
+                    const int key0 = kt * 32 + 16 * half;
+                    if (kt * 32 + 32 > minlim) {   // only tiles that reach some row's limit need the mask
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            if (key0 + r >= lim) sacc[r] = -INFINITY;
+                    }
+                    float mx = sacc[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+                    mx = fmaxf(mx, shx(mx, 32));
+                    const float m_new = fmaxf(m_run, mx);
+                    float pr[16];
+                    if (m_new == -INFINITY) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) pr[r] = 0.f;
+                    } else {
+                        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+                        const float mb = m_new * scale_log2e;
+                        float ls = 0.f;
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
+                        l_run = l_run * alpha + ls;
+                        m_run = m_new;
+                        if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+#pragma unroll
+                            for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                                for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+                        }
+                    }
+                    uint4 ph[2], pl[2];
+                    pack8_split(pr, ph[0], pl[0]);
+                    pack8_split(pr + 8, ph[1], pl[1]);
+#pragma unroll
+                    for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                        for (int s2 = 0; s2 < 2; ++s2) {
+                            const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
+                            oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
+                            oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+                        }
                 }
-                stage_wait();
-                __syncthreads();
             }
+            __syncthreads();   // the buffers have been read: the parity merge below reuses them
         } else {
             __syncthreads();   // the previous head round or item has been read
         }

@@ -106,17 +106,12 @@ def test_batch_sampling_uses_per_sequence_streams(setup):
 
 
 def _fill_engine_cache(eng, torch, model, shape, lens):
-    lay = eng.get_kv_layout(model)
-    kv = eng.kv_tensor(model)
-    L, B, H, hd, S = shape.n_layers, eng.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
-    K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
-    Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, hd, S)
-    for l in range(L):
+    views = eng.kv_views(model, shape)
+    for l in range(shape.n_layers):
         for b, n in enumerate(lens):
             kb = torch.from_numpy(di.kv_fill_bits(shape, "k", l, b, n).view(np.int16)).cuda()
             vb = torch.from_numpy(di.kv_fill_bits(shape, "v", l, b, n).view(np.int16)).cuda()
-            K[l, b, :, :n, :] = kb.permute(1, 0, 2)
-            Vt[l, b, :, :, :n] = vb.permute(1, 2, 0)
+            eng.write_kv_rows(views, l, b, kb, vb)
     torch.cuda.synchronize()
 
 

@@ -32,35 +32,26 @@ def big():
     eng.close()
 
 
-def _views(eng, torch, model, shape):
-    lay = eng.get_kv_layout(model)
-    kv = eng.kv_tensor(model)
-    L, B, H, hd, S = shape.n_layers, eng.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
-    K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
-    Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, hd, S)
-    return K, Vt
-
-
 def _fill_seeded(eng, torch, model, shape, b, n, cache):
     """Same bytes into the engine's cache (sequence slot b) and the oracle's KVCache."""
-    K, Vt = _views(eng, torch, model, shape)
+    views = eng.kv_views(model, shape)
     for l in range(shape.n_layers):
         kb = di.kv_fill_bits(shape, "k", l, b, n, threads=16)
         vb = di.kv_fill_bits(shape, "v", l, b, n, threads=16)
-        K[l, b, :, :n, :] = torch.from_numpy(kb.view(np.int16)).cuda().permute(1, 0, 2)
-        Vt[l, b, :, :, :n] = torch.from_numpy(vb.view(np.int16)).cuda().permute(1, 2, 0)
+        eng.write_kv_rows(views, l, b, torch.from_numpy(kb.view(np.int16)).cuda(), torch.from_numpy(vb.view(np.int16)).cuda())
         cache.K[l, :n] = di.bf16_bits_to_f32(kb)
         cache.V[l, :n] = di.bf16_bits_to_f32(vb)
     cache.n = n
 
 
 def _fill_device_random(eng, torch, model, shape, b, n, seed):
-    K, Vt = _views(eng, torch, model, shape)
+    views = eng.kv_views(model, shape)
     g = torch.Generator(device="cuda")
     g.manual_seed(seed)
     for l in range(shape.n_layers):
-        K[l, b, :, :n, :] = torch.randn(shape.n_kv_heads, n, shape.head_dim, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
-        Vt[l, b, :, :, :n] = torch.randn(shape.n_kv_heads, shape.head_dim, n, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+        kr = torch.randn(n, shape.n_kv_heads, shape.head_dim, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+        vr = torch.randn(n, shape.n_kv_heads, shape.head_dim, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
+        eng.write_kv_rows(views, l, b, kr, vr)
 
 
 def _oracle_pair(t, d, wt, wd, cap):
