@@ -203,6 +203,12 @@ int deer_debug_pass_mode(deer_ctx *c, int mode);
  * Pass stamps_host = NULL first to learn the two sizes. */
 int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block);
 
+/* GEMMs of passes with at least 256 rows run blocked for the matrix cores (256 x 256 tiles through LDS)
+ * where a launch has at least `min_tiles` such tiles (default 128: enough to fill the chip), else as the
+ * weight-streaming kernel.  0 switches the blocked kernel off; tests lower the threshold to cover it at
+ * small sizes.  Results agree within rounding (different summation order over K). */
+int deer_debug_gemm_tiled(deer_ctx *c, int min_tiles);
+
 /* Current committed length j per sequence (host mirror). */
 int deer_get_lengths(const deer_ctx *c, int32_t *len_host);
 

@@ -18,7 +18,7 @@ EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_pre
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
            "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token",
-           "deer_draft_block_multipass"]
+           "deer_draft_block_multipass", "deer_debug_gemm_tiled"]
 
 
 class DeerError(RuntimeError):
@@ -249,6 +249,9 @@ class DeerEngine:
         ms, n, by = C.c_double(), C.c_int64(), C.c_double()
         self._check(self.lib.deer_debug_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(by)))
         return ms.value, n.value, by.value
+
+    def debug_gemm_tiled(self, min_tiles):
+        self._check(self.lib.deer_debug_gemm_tiled(self.ctx, int(min_tiles)))
 
     def debug_pass_mode(self, mode):
         """0: one kernel per operation (default); 1: persistent pass kernel wherever it applies."""

@@ -2,6 +2,7 @@
 // The C ABI is declared in include/deer.h.  Nothing here allocates device memory.
 #include "deer_kernels.hpp"
 #include "deer_pass.hpp"
+#include "deer_tiled.hpp"
 
 #include <algorithm>
 #include <cmath>
@@ -22,7 +23,11 @@ namespace {
 thread_local std::string g_init_error;
 
 constexpr int PASS_MAX_BLOCKS = 512;   // workgroups of the persistent pass kernel (one per compute unit)
-constexpr int PREFILL_TILES = 16;    // rows of a prefill chunk / 32: the weights are streamed once per chunk
+// rows of a prefill chunk / 32: dense models take 4096 rows per pass through the LDS-tiled GEMM, mixtures 512
+// (their grouped expert buffers grow with the rows of a pass)
+constexpr int PREFILL_TILES_DENSE = 128, PREFILL_TILES_MOE = 16;
+int prefill_tiles(const deer_init_params &p) { return (p.target.n_experts || p.drafter.n_experts) ? PREFILL_TILES_MOE : PREFILL_TILES_DENSE; }
+constexpr int PART_TILES_MIN = 16;   // split-K partials exist for passes of up to max(2 * batch, 16) row tiles
 constexpr int MAX_NS = 32;          // key-range splits of block attention
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
@@ -64,6 +69,7 @@ struct Work {   // carved from the workspace
     size_t cnt_bytes = 0; char *cnt_base = nullptr;
     double *theta[2] = {nullptr, nullptr};
     // persistent pass kernel: per-layer activation fragments (dense models, two tiles) and its barrier words
+    size_t part_floats = 0;   // capacity of `part`
     uint4 *pass_x = nullptr; size_t pass_x_vecs = 0;
     unsigned *pass_sync = nullptr;
     unsigned long long *pass_stamps = nullptr;   // [PASS_MAX_BLOCKS][PASS_STAMPS], written on request
@@ -84,6 +90,7 @@ struct deer_ctx {
     int cur_k = 0;
     float cur_T = 0.f;
     int max_tiles = 0;
+    int tiled_min_tiles = 128;       // the LDS-tiled GEMM runs where a launch has at least this many 256 x 256 tiles; 0: never
     int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
@@ -198,7 +205,8 @@ void plan_model(ModelRT &m, const deer_model_cfg &c, int max_batch, int max_seq)
 // Carves the workspace; with base == nullptr only computes the size.
 void plan_work(Work &w, const deer_init_params &p, char *base) {
     const int B = p.max_batch;
-    const int MAXT = std::max(2 * B, PREFILL_TILES), MAXR = MAXT * 32;
+    const int MAXT = std::max(2 * B, prefill_tiles(p)), MAXR = MAXT * 32;
+    const int PARTR = std::max(2 * B, PART_TILES_MIN) * 32;
     const deer_model_cfg &t = p.target, &d = p.drafter;
     const size_t dmax = std::max(t.d_model, d.d_model);
     const size_t kattn = std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
@@ -221,7 +229,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.xa_hi = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024); w.xa_lo = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024);
     w.xb_hi = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024); w.xb_lo = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024);
     w.q_hi = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024); w.q_lo = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024);
-    w.part = (float *)take((size_t)MAXR * PART_COLS * 4);
+    w.part = (float *)take((size_t)PARTR * PART_COLS * 4); w.part_floats = (size_t)PARTR * PART_COLS;
     w.opart = (float *)take((size_t)std::max(64, MAXT) * hq * (32 * hdmax + 64) * 4);
     w.logits[0] = (float *)take(lmrows * V * 4); w.logits[1] = (float *)take(lmrows * V * 4);
     w.stat = (RowStat *)take(lmrows * (V / CG) * sizeof(RowStat));
@@ -290,8 +298,23 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     a.KS = K / 16;
     const int MT = (ntiles % 2 == 0) ? 2 : 1;
     const int zg = ntiles / MT;
-    a.S = force_S > 0 ? force_S : choose_split(a.N, a.KS, zg);
     a.rows_total = ntiles * 32;
+    {   // many rows and enough 256 x 256 tiles to fill the chip: blocked for the matrix cores
+        const int ncg = a.N / CG;
+        const int tiles = ((ntiles + TG_RT - 1) / TG_RT) * ((ncg + 1) / 2);
+        // measured: at 512 and 1024 rows (two and four row blocks) the streaming kernel with shared L2 lines is still
+        // ahead (config-5 verify 42.8 against 48.5 ms); from 2048 rows on the blocked kernel wins (prefill 133 against 167 ms)
+        const int min_rows_tiles = c->tiled_min_tiles >= 128 ? 64 : TG_RT;   // tests lower both thresholds
+        if (c->tiled_min_tiles > 0 && EPI != EPI_ROUTER && ntiles >= min_rows_tiles && a.KS % TG_KST == 0 && tiles >= c->tiled_min_tiles) {
+            a.S = 1; a.part = nullptr; a.counters = nullptr;
+            ProfScope ps(c, 0, (double)a.N * K * 2.0);
+            hipLaunchKernelGGL((k_gemm_tiled<EPI>), dim3((unsigned)tiled_blocks(ntiles, ncg)), dim3(512), 0, c->stream, a, ncg, ntiles);
+            LAUNCHCHK(c, "k_gemm_tiled");
+            return DEER_OK;
+        }
+    }
+    a.S = force_S > 0 ? force_S : choose_split(a.N, a.KS, zg);
+    while (a.S > 1 && (size_t)a.S * a.rows_total * a.N > c->wk.part_floats) --a.S;   // partials must fit their buffer
     a.part = (EPI == EPI_LMHEAD) ? nullptr : c->wk.part;
     a.counters = c->wk.gemm_cnt;
     dim3 grid(a.N / CG, a.S, zg);
@@ -634,7 +657,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         c->m[i].kv = (uint16_t *)bufs->kv[i];
     }
     plan_work(c->wk, *p, (char *)bufs->workspace);
-    c->max_tiles = std::max(2 * p->max_batch, PREFILL_TILES);
+    c->max_tiles = std::max(2 * p->max_batch, prefill_tiles(*p));
     // caches must hold finite values everywhere: masked keys are multiplied by zero weights
     for (int i = 0; i < 2; ++i) {
         e = hipMemsetAsync(bufs->kv[i], 0, need.kv[i], c->stream);
@@ -661,6 +684,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         c->n_cus = cus;
         c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
         if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = atoi(e) == 1 ? 1 : 0;
+        if (const char *e = getenv("DEER_GEMM_TILED_MIN")) c->tiled_min_tiles = std::max(0, atoi(e));
         (void)hipGetLastError();
     }
     *out = c;
@@ -734,8 +758,9 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(w.ids, ids + off, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
         for (int model = 0; model < 2; ++model) {
             const int nrows = (model == DEER_TARGET) ? n - 1 : n;   // the last token stays pending for the target
-            for (int c0 = 0; c0 < nrows; c0 += 32 * PREFILL_TILES) {
-                const int nr = std::min(32 * PREFILL_TILES, nrows - c0);
+            const int chunk = 32 * prefill_tiles(c->p);
+            for (int c0 = 0; c0 < nrows; c0 += chunk) {
+                const int nr = std::min(chunk, nrows - c0);
                 const int ntiles = (nr + 31) / 32;
                 hipLaunchKernelGGL(k_rows_prefill, dim3(ntiles), dim3(32), 0, c->stream, w.rm, w.ids, b, c0, nr);
                 LAUNCHCHK(c, "k_rows_prefill");
@@ -925,6 +950,13 @@ int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int
     if (enable && !c->pass_stamps_on)
         HIPCHK(c, hipMemsetAsync(c->wk.pass_stamps, 0, (size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8, c->stream));
     c->pass_stamps_on = enable != 0;
+    return DEER_OK;
+}
+
+int deer_debug_gemm_tiled(deer_ctx *c, int min_tiles) {
+    if (!c) return DEER_EINVAL;
+    if (min_tiles < 0) return fail(c, DEER_EINVAL, "min_tiles must not be negative");
+    c->tiled_min_tiles = min_tiles;
     return DEER_OK;
 }
 
