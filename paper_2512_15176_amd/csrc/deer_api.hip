@@ -288,6 +288,11 @@ int choose_split(int N, int KS, int zgroups) {
     static const int t_long = getenv("DEER_SPLIT_LONG") ? atoi(getenv("DEER_SPLIT_LONG")) : 256;
     const int target = KS > 256 ? t_long : t_short;
     int S = (target + blocks - 1) / blocks;
+    // the workgroup that finishes a column group sums S partial tiles (about 0.25 us each) before its epilogue:
+    // beyond 8 splits that costs more than the shorter streams save (drafter down projection, 7 column groups:
+    // 19 splits 22.8 us, 8 splits 18.5 us)
+    static const int s_max = getenv("DEER_SPLIT_MAX") ? atoi(getenv("DEER_SPLIT_MAX")) : 8;
+    S = std::min(S, s_max);
     S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);

@@ -732,20 +732,20 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
     const int tidx = opaque_tid();
     float *tile = sm.tile;
     const int N = a.N, S = a.S;
-    float hreg[8];
+    float hreg[MT][8];
+    float2 v[MT][4];
+    // the sums of all MT row tiles first (their loads do not depend on each other's epilogue), then the epilogues
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int ct = z * MT + mt;
-        if (mt > 0) __syncthreads();
-        if (EPI == EPI_RESID) resid_prefetch<COH>(a, hreg, cg, a.mt0 + ct * a.mt_stride);
+        if (EPI == EPI_RESID) resid_prefetch<COH>(a, hreg[mt], cg, a.mt0 + ct * a.mt_stride);
         const size_t sstride = (size_t)a.rows_total * N;
         const float *p[4];
-        float2 v[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int e = tidx + 512 * i;
             p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
-            v[i] = make_float2(0.f, 0.f);
+            v[mt][i] = make_float2(0.f, 0.f);
         }
         for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 4 elements of loads in flight, summed in order
             float2 pv[8][4];
@@ -757,17 +757,22 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < S) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { v[i].x += pv[u][i].x; v[i].y += pv[u][i].y; }
+                    for (int i = 0; i < 4; ++i) { v[mt][i].x += pv[u][i].x; v[mt][i].y += pv[u][i].y; }
                 }
         }
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int ct = z * MT + mt;
+        if (mt > 0) __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int e = tidx + 512 * i;
             float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
-            tp[0] = v[i].x; tp[1] = v[i].y;
+            tp[0] = v[mt][i].x; tp[1] = v[mt][i].y;
         }
         __syncthreads();
-        run_epilogue<EPI, COH, RSTD_EARLY>(a, tile, sm.rstd + 32 * mt, sm.red, hreg, cg, ct);
+        run_epilogue<EPI, COH, RSTD_EARLY>(a, tile, sm.rstd + 32 * mt, sm.red, hreg[mt], cg, ct);
     }
 }
 
