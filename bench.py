@@ -326,6 +326,36 @@ def run_no_kv_cache(args):
                       "by_batch": rows}))
 
 
+def run_gemm_stamps(args):
+    """Where the weight-streaming GEMM launches of one layer spend their time (device-clock stamps recorded by the
+    workgroups themselves, deer_debug_gemm_stamps): headline workload, layer 1 of the target and of the drafter."""
+    import torch
+    from paper_2512_15176_amd import DeerEngine, binding
+    cfg = di.CONFIGS["qwen3_8b"]
+    t, d, k, prefix = cfg["target"], cfg["drafter"], cfg["k"], cfg["prefix"]
+    eng = DeerEngine(t, d, 1, prefix + 64 * k, k, di.mask_token_id(t.vocab), -1, False)
+    load_random_model(eng, binding.DEER_TARGET, t, di.TARGET_SEED)
+    load_random_model(eng, binding.DEER_DRAFTER, d, di.DRAFTER_SEED)
+    eng.set_prefilled([prefix], [5])
+    names = ["QKV", "O", "gate/up", "down"]
+    print("times in microseconds from the first workgroup's start; median over workgroups (max for the last column)")
+    print(f"{'model':8s} {'launch':8s} {'workgroups':>10s} {'K slice of wave 0 multiplied':>30s} {'tile stored':>12s} {'arrived':>9s} {'group finished (max)':>21s}")
+    for model, mname in ((binding.DEER_TARGET, "target"), (binding.DEER_DRAFTER, "drafter")):
+        for i, name in enumerate(names):
+            eng.debug_gemm_stamps(model, 4 + i)      # layer 1: launches 4..7 of a pass
+            for _ in range(3):
+                dr = eng.draft_block(k, 0.0, 0)
+                eng.verify_block(k, 0.0, dr)
+                eng.accept_and_commit(k, 0.0, 0)
+            st = eng.debug_gemm_stamps(model, -1)
+            rel = (st - st[:, 0].min()) * 0.01
+            rel[st == 0] = np.nan
+            med = lambda c: float(np.nanmedian(rel[:, c])) if np.any(~np.isnan(rel[:, c])) else float("nan")
+            fin = float(np.nanmax(rel[:, 4])) if np.any(~np.isnan(rel[:, 4])) else float("nan")
+            print(f"{mname:8s} {name:8s} {st.shape[0]:10d} {med(1):30.2f} {med(2):12.2f} {med(3):9.2f} {fin:21.2f}")
+    eng.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -339,7 +369,7 @@ def main():
                     help="profiling aid: declare the prefix prefilled without running the models (zero caches)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="profiling aid: also run one plain 1 GiB device copy (scale factor for byte counters)")
-    ap.add_argument("--mode", default="step", choices=["step", "no_kv_cache"],
+    ap.add_argument("--mode", default="step", choices=["step", "no_kv_cache", "gemm_stamps"],
                     help="step: the draft-verify step (default, the benchmark line); no_kv_cache: the paper's batch experiment "
                          "setting, every iteration recomputes the sequence (its own JSON line)")
     ap.add_argument("--steps-nokv", type=int, default=3)
@@ -351,6 +381,8 @@ def main():
 
     if args.mode == "no_kv_cache":
         return run_no_kv_cache(args)
+    if args.mode == "gemm_stamps":
+        return run_gemm_stamps(args)
 
     import torch
     from paper_2512_15176_amd import DeerEngine, binding

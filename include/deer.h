@@ -203,6 +203,15 @@ int deer_debug_pass_mode(deer_ctx *c, int mode);
  * Pass stamps_host = NULL first to learn the two sizes. */
 int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block);
 
+/* Debugging aid: where a weight-streaming GEMM launch spends its time.  Copies the stamps recorded so far
+ * (*blocks workgroups x 8 ticks of the 100 MHz device clock: 0 workgroup started, 1 its first wave has
+ * multiplied its K slice, 2 its tile is stored (after the epilogue if the matrix is not split), 3 it has
+ * arrived at the column group's counter, 4 it was the last to arrive and has finished the group; 0 = not
+ * reached) into stamps_host (at most max_blocks workgroups), then selects the launch that records from now on:
+ * the `launch`-th streaming GEMM (counted from 0) of every following pass of `model`; launch < 0 switches
+ * recording off.  Waits for the stream.  Only the per-operation launch mode records. */
+int deer_debug_gemm_stamps(deer_ctx *c, int model, int launch, uint64_t *stamps_host, int32_t max_blocks, int32_t *blocks);
+
 /* GEMMs of passes with at least 256 rows run blocked for the matrix cores (256 x 256 tiles through LDS)
  * where a launch has at least `min_tiles` such tiles (default 128: enough to fill the chip), else as the
  * weight-streaming kernel.  0 switches the blocked kernel off; tests lower the threshold to cover it at

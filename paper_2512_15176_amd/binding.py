@@ -18,7 +18,8 @@ EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_pre
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
            "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token",
-           "deer_draft_block_multipass", "deer_debug_gemm_tiled"]
+           "deer_draft_block_multipass", "deer_debug_gemm_tiled",
+           "deer_debug_gemm_stamps"]
 
 
 class DeerError(RuntimeError):
@@ -77,6 +78,7 @@ def load_library(path: str = LIB_PATH):
     lib.deer_verify_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.deer_accept_and_commit.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.deer_destroy.argtypes = [C.c_void_p]
+    lib.deer_debug_gemm_stamps.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int32, C.c_void_p]
     lib.deer_set_bonus_token.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
     lib.deer_get_lengths.argtypes = [C.c_void_p, C.c_void_p]
@@ -249,6 +251,15 @@ class DeerEngine:
         ms, n, by = C.c_double(), C.c_int64(), C.c_double()
         self._check(self.lib.deer_debug_profile_read(self.ctx, kernel_class, C.byref(ms), C.byref(n), C.byref(by)))
         return ms.value, n.value, by.value
+
+    def debug_gemm_stamps(self, model, launch):
+        """Returns the stamps recorded so far as an int64 array [workgroups][8] (or None), then selects the
+        streaming-GEMM launch (index within a pass of `model`, < 0: off) that records from now on."""
+        nb = C.c_int32(0)
+        buf = np.zeros((32768, 8), dtype=np.uint64)
+        self._check(self.lib.deer_debug_gemm_stamps(self.ctx, model, -1 if launch is None else launch, buf.ctypes.data,
+                                                    buf.shape[0], C.byref(nb)))
+        return buf[: nb.value].astype(np.int64) if nb.value > 0 else None
 
     def debug_gemm_tiled(self, min_tiles):
         self._check(self.lib.deer_debug_gemm_tiled(self.ctx, int(min_tiles)))

@@ -91,6 +91,8 @@ struct deer_ctx {
     float cur_T = 0.f;
     int max_tiles = 0;
     int tiled_min_tiles = 128;       // the LDS-tiled GEMM runs where a launch has at least this many 256 x 256 tiles; 0: never
+    // deer_debug_gemm_stamps: which streaming-GEMM launch of which model's passes records its stamps
+    int stamp_model = 0, stamp_launch = -1, stamp_blocks = 0, gemm_launch_idx = 0, cur_pass_model = 0;
     int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
@@ -322,6 +324,14 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     while (a.S > 1 && (size_t)a.S * a.rows_total * a.N > c->wk.part_floats) --a.S;   // partials must fit their buffer
     a.part = (EPI == EPI_LMHEAD) ? nullptr : c->wk.part;
     a.counters = c->wk.gemm_cnt;
+    a.stamps = nullptr;
+    if (c->stamp_launch >= 0 && c->cur_pass_model == c->stamp_model && c->gemm_launch_idx == c->stamp_launch &&
+        (size_t)(a.N / CG) * a.S * zg * 8 <= (size_t)PASS_MAX_BLOCKS * PASS_STAMPS) {
+        a.stamps = c->wk.pass_stamps;
+        c->stamp_blocks = (a.N / CG) * a.S * zg;
+        (void)hipMemsetAsync(a.stamps, 0, (size_t)c->stamp_blocks * 64, c->stream);
+    }
+    c->gemm_launch_idx++;
     dim3 grid(a.N / CG, a.S, zg);
     ProfScope ps(c, 0, (double)a.N * K * 2.0);
     static const int zmap = getenv("DEER_GEMM_ZMAP") ? atoi(getenv("DEER_GEMM_ZMAP")) : 1;
@@ -496,6 +506,8 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
     const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG;
+    c->gemm_launch_idx = 0;
+    c->cur_pass_model = model;
     if (pass_eligible(c, m, ntiles, lm)) return run_pass_persistent(c, model, ntiles, max_limit, lm, kv_keys_total);
     hipStream_t s = c->stream;
     hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
@@ -955,6 +967,19 @@ int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int
     if (enable && !c->pass_stamps_on)
         HIPCHK(c, hipMemsetAsync(c->wk.pass_stamps, 0, (size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8, c->stream));
     c->pass_stamps_on = enable != 0;
+    return DEER_OK;
+}
+
+int deer_debug_gemm_stamps(deer_ctx *c, int model, int launch, uint64_t *stamps_host, int32_t max_blocks, int32_t *blocks) {
+    if (!c) return DEER_EINVAL;
+    if (model < 0 || model > 1) return fail(c, DEER_EINVAL, "bad model");
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (blocks) *blocks = c->stamp_blocks;
+    if (stamps_host && c->stamp_blocks > 0 && max_blocks > 0)
+        HIPCHK(c, hipMemcpy(stamps_host, c->wk.pass_stamps, (size_t)std::min(max_blocks, c->stamp_blocks) * 64, hipMemcpyDeviceToHost));
+    c->stamp_model = model;
+    c->stamp_launch = launch;
+    c->stamp_blocks = 0;
     return DEER_OK;
 }
 

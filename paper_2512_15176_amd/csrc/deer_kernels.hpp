@@ -429,6 +429,7 @@ struct GemmArgs {
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
     int k; float *logits; float T; uint64_t seed; RowStat *stat; int ncg_v;
+    unsigned long long *stamps;   // debugging: [workgroup][8] device-clock stamps of this launch, or null
     int k_lo;   // rows below k_lo keep the logits and statistics of an earlier pass (multi-pass draft)
     // ROUTER: top-k of softmax over n_experts (<= 128), renormalised
     int n_experts, top_k; int *route_e; float *route_w;
@@ -776,6 +777,11 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
     }
 }
 
+// Debugging aid: thread 0 of workgroup `lin` records the 100 MHz device clock at point i of the launch.
+__device__ __forceinline__ void gemm_stamp(const GemmArgs &a, int lin, int i) {
+    if (a.stamps && threadIdx.x == 0) a.stamps[lin * 8 + i] = wall_clock64();
+}
+
 // One work item of the weight-streaming GEMM: column group cg, K split s, row-tile group z.
 // DEFER = false: with S > 1 the block that arrives last at the group's counter finishes the group;
 // DEFER = true: the partial tile is left for a later gemm_finish (after a grid-wide barrier).
@@ -792,6 +798,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     const int ks0 = sl * per;
     const int ks1 = min(KS, ks0 + per);
 
+    const int lin = (z * S + s) * ncg + cg;   // stamps: 0 start, 1 this wave's K slice multiplied, 2 tile stored
+    gemm_stamp(a, lin, 0);                    // (epilogue done if S == 1), 3 arrived, 4 last workgroup's finish done
     f32x16 acc[MT][4];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
@@ -854,6 +862,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         }
     }
 
+    gemm_stamp(a, lin, 1);
     // sum the 8 waves, then either finish (S == 1) or hand the partial tile over
     float hreg[8];
 #pragma unroll
@@ -875,10 +884,14 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
             }
         }
     }
+    gemm_stamp(a, lin, 2);
     if (S == 1 || DEFER) return;
     // the block that arrives last at this column group's counter sums all partials and finishes
-    if (!arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last)) return;
+    const bool last = arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last);
+    gemm_stamp(a, lin, 3);
+    if (!last) return;
     gemm_finish<MT, EPI, COH, RSTD_EARLY>(a, sm, cg, z);
+    gemm_stamp(a, lin, 4);
 }
 
 template <int MT, int EPI>
