@@ -295,6 +295,10 @@ int choose_split(int N, int KS, int zgroups) {
     // 19 splits 22.8 us, 8 splits 18.5 us)
     static const int s_max = getenv("DEER_SPLIT_MAX") ? atoi(getenv("DEER_SPLIT_MAX")) : 8;
     S = std::min(S, s_max);
+    // a short contraction (the drafter's d = 896: 56 k-steps) is not split at all: the partial store, the arrival
+    // and the last workgroup's sum cost more than streaming a 128-column slab from one workgroup (2.44 -> 2.36 ms per draft pass)
+    static const int ks_nosplit = getenv("DEER_NOSPLIT_KS") ? atoi(getenv("DEER_NOSPLIT_KS")) : 64;
+    if (KS <= ks_nosplit) S = 1;
     S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);
