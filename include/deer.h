@@ -203,6 +203,18 @@ int deer_debug_pass_mode(deer_ctx *c, int mode);
  * Pass stamps_host = NULL first to learn the two sizes. */
 int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block);
 
+/* Benchmarking aid for random-init mixture models, whose router sends every row of a block to the same few
+ * experts: when enabled, each row is routed to top_k distinct pseudo-random experts (a function of layer and
+ * row) with equal weights instead of the router's own choice, so that a block touches as many experts as a
+ * trained router's would (n_experts must be a power of two, else ignored).  Changes the computed function:
+ * never on in parity tests. */
+int deer_debug_route_spread(deer_ctx *c, int enable);
+
+/* Mixture models: the number of (layer, expert) pairs whose expert weights the passes since the last call
+ * had to stream (an expert counts once per layer and pass if any row was routed to it), then resets the
+ * count - the data-dependent part of a pass's algorithmic bytes.  0 for dense models.  Waits for the stream. */
+int deer_debug_experts_streamed(deer_ctx *c, int64_t *pairs);
+
 /* Debugging aid: where a weight-streaming GEMM launch spends its time.  Copies the stamps recorded so far
  * (*blocks workgroups x 8 ticks of the 100 MHz device clock: 0 workgroup started, 1 its first wave has
  * multiplied its K slice, 2 its tile is stored (after the epilogue if the matrix is not split), 3 it has

@@ -19,7 +19,7 @@ EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_pre
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
            "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token",
            "deer_draft_block_multipass", "deer_debug_gemm_tiled",
-           "deer_debug_gemm_stamps"]
+           "deer_debug_gemm_stamps", "deer_debug_experts_streamed", "deer_debug_route_spread"]
 
 
 class DeerError(RuntimeError):
@@ -78,6 +78,8 @@ def load_library(path: str = LIB_PATH):
     lib.deer_verify_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.deer_accept_and_commit.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.deer_destroy.argtypes = [C.c_void_p]
+    lib.deer_debug_route_spread.argtypes = [C.c_void_p, C.c_int]
+    lib.deer_debug_experts_streamed.argtypes = [C.c_void_p, C.c_void_p]
     lib.deer_debug_gemm_stamps.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int32, C.c_void_p]
     lib.deer_set_bonus_token.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
@@ -260,6 +262,14 @@ class DeerEngine:
         self._check(self.lib.deer_debug_gemm_stamps(self.ctx, model, -1 if launch is None else launch, buf.ctypes.data,
                                                     buf.shape[0], C.byref(nb)))
         return buf[: nb.value].astype(np.int64) if nb.value > 0 else None
+
+    def debug_route_spread(self, enable):
+        self._check(self.lib.deer_debug_route_spread(self.ctx, int(bool(enable))))
+
+    def debug_experts_streamed(self):
+        n = C.c_int64(0)
+        self._check(self.lib.deer_debug_experts_streamed(self.ctx, C.byref(n)))
+        return n.value
 
     def debug_gemm_tiled(self, min_tiles):
         self._check(self.lib.deer_debug_gemm_tiled(self.ctx, int(min_tiles)))

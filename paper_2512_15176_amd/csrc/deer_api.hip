@@ -64,6 +64,7 @@ struct Work {   // carved from the workspace
     // mixture-of-experts routing and staging (target only)
     int *route_e = nullptr, *exp_cnt = nullptr, *pair_row = nullptr, *pair_slot = nullptr;
     float *route_w = nullptr, *moe_out = nullptr;
+    unsigned long long *moe_touched = nullptr;   // (layer, expert) pairs streamed since the last read
     uint4 *act_hi = nullptr, *act_lo = nullptr;
     int *gemm_cnt = nullptr, *attn_cnt = nullptr;   // arrival counters, zero between kernels
     size_t cnt_bytes = 0; char *cnt_base = nullptr;
@@ -93,6 +94,7 @@ struct deer_ctx {
     int tiled_min_tiles = 128;       // the LDS-tiled GEMM runs where a launch has at least this many 256 x 256 tiles; 0: never
     // deer_debug_gemm_stamps: which streaming-GEMM launch of which model's passes records its stamps
     int stamp_model = 0, stamp_launch = -1, stamp_blocks = 0, gemm_launch_idx = 0, cur_pass_model = 0;
+    int route_spread = 0;            // deer_debug_route_spread: synthetic uniform routing for mixture models
     int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
@@ -242,7 +244,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
         if (!mc->n_experts || w.route_e) continue;
         const size_t chunks = MAXT;   // 32-pair chunks per expert: at most every row of the pass
         w.route_e = (int *)take((size_t)MAXR * 8 * 4); w.route_w = (float *)take((size_t)MAXR * 8 * 4);
-        w.exp_cnt = (int *)take(128 * 4);
+        w.exp_cnt = (int *)take(128 * 4); w.moe_touched = (unsigned long long *)take(8);
         w.pair_row = (int *)take((size_t)128 * MAXR * 4); w.pair_slot = (int *)take((size_t)128 * MAXR * 4);
         w.moe_out = (float *)take((size_t)MAXR * 8 * dmax * 4);
         w.act_hi = (uint4 *)take((size_t)128 * chunks * (fmax / 16) * 1024); w.act_lo = (uint4 *)take((size_t)128 * chunks * (fmax / 16) * 1024);
@@ -567,11 +569,12 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             a = base;
             a.W = (const uint4 *)(lw + m.lo_router); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = CG;
             a.n_experts = mc.n_experts; a.top_k = mc.top_k; a.route_e = w.route_e; a.route_w = w.route_w;
+            a.route_spread = (c->route_spread && (mc.n_experts & (mc.n_experts - 1)) == 0) ? l + 1 : 0;
             rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, 0);
             if (rc) return rc;
             const int cap = rows, chunks = ntiles;
             hipLaunchKernelGGL(k_moe_group, dim3(1), dim3(256), 0, s, w.route_e, w.rm.slot, rows, mc.top_k, mc.n_experts, cap,
-                               w.exp_cnt, w.pair_row, w.pair_slot);
+                               w.exp_cnt, w.pair_row, w.pair_slot, w.moe_touched);
             LAUNCHCHK(c, "k_moe_group");
             MoeArgs ma{};
             ma.cap = cap; ma.chunks = chunks; ma.cnt = w.exp_cnt; ma.pair_row = w.pair_row; ma.pair_slot = w.pair_slot;
@@ -690,6 +693,7 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         e = hipMemcpy(c->m[i].theta, th, sizeof(double) * (mc.head_dim / 2), hipMemcpyHostToDevice);
         if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemcpy: %s", hipGetErrorString(e)); }
     }
+    if (c->wk.moe_touched) (void)hipMemsetAsync(c->wk.moe_touched, 0, 8, c->stream);
     e = hipMemsetAsync(c->wk.cnt_base, 0, c->wk.cnt_bytes, c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     e = hipMemsetAsync(c->wk.pass_sync, 0, PASS_SYNC_WORDS * 4, c->stream);
@@ -984,6 +988,24 @@ int deer_debug_gemm_stamps(deer_ctx *c, int model, int launch, uint64_t *stamps_
     c->stamp_model = model;
     c->stamp_launch = launch;
     c->stamp_blocks = 0;
+    return DEER_OK;
+}
+
+int deer_debug_route_spread(deer_ctx *c, int enable) {
+    if (!c) return DEER_EINVAL;
+    c->route_spread = enable ? 1 : 0;
+    return DEER_OK;
+}
+
+int deer_debug_experts_streamed(deer_ctx *c, int64_t *pairs) {
+    if (!c || !pairs) return DEER_EINVAL;
+    *pairs = 0;
+    if (!c->wk.moe_touched) return DEER_OK;
+    unsigned long long v = 0;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(&v, c->wk.moe_touched, 8, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemset(c->wk.moe_touched, 0, 8));
+    *pairs = (int64_t)v;
     return DEER_OK;
 }
 

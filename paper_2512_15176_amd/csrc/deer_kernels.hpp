@@ -433,6 +433,7 @@ struct GemmArgs {
     int k_lo;   // rows below k_lo keep the logits and statistics of an earlier pass (multi-pass draft)
     // ROUTER: top-k of softmax over n_experts (<= 128), renormalised
     int n_experts, top_k; int *route_e; float *route_w;
+    int route_spread;   // 0: the model's routing; layer + 1: synthetic uniform routing (benchmarks of random-init mixtures)
 };
 
 // rstd[row] = rsqrt(sum_g ssq[row][g] / d + eps) for the 32 rows of a tile, into LDS.  512 threads: 16 per
@@ -662,9 +663,20 @@ __device__ __forceinline__ void epi_router(const GemmArgs &a, const float *tile,
         wsum += wsel[j];
     }
     if (sub == 0) {
-        for (int j = 0; j < a.top_k; ++j) {
-            a.route_e[grow * 8 + j] = esel[j];
-            a.route_w[grow * 8 + j] = wsel[j] / wsum;
+        if (a.route_spread) {
+            // benchmarking stand-in for a trained router (a.route_spread - 1 = layer): every row gets top_k distinct
+            // pseudo-random experts with equal weights, so a block touches about n (1 - (1 - top_k / n)^rows) experts
+            const uint32_t base = (uint32_t)mix64(((uint64_t)a.route_spread << 32) | (uint32_t)grow);
+            const uint32_t stride = ((uint32_t)(mix64(base) >> 7) | 1u);   // odd: distinct picks when n is a power of two
+            for (int j = 0; j < a.top_k; ++j) {
+                a.route_e[grow * 8 + j] = (int)((base + (uint32_t)j * stride) % (uint32_t)a.n_experts);
+                a.route_w[grow * 8 + j] = 1.f / (float)a.top_k;
+            }
+        } else {
+            for (int j = 0; j < a.top_k; ++j) {
+                a.route_e[grow * 8 + j] = esel[j];
+                a.route_w[grow * 8 + j] = wsel[j] / wsum;
+            }
         }
     }
 }
@@ -920,7 +932,8 @@ __global__ __launch_bounds__(512) void k_gemm_rows(const GemmArgs a, int ncg, in
 // one block: cnt[e], and for pair i of expert e the pass row and its routing slot
 __global__ __launch_bounds__(256) void k_moe_group(const int *__restrict__ route_e, const int *__restrict__ row_slot,
                                                    int rows, int top_k, int n_experts, int cap, int *__restrict__ cnt,
-                                                   int *__restrict__ pair_row, int *__restrict__ pair_slot) {
+                                                   int *__restrict__ pair_row, int *__restrict__ pair_slot,
+                                                   unsigned long long *__restrict__ touched_total) {
     __shared__ int s_cnt[128];
     if (threadIdx.x < 128) s_cnt[threadIdx.x] = 0;
     __syncthreads();
@@ -933,7 +946,11 @@ __global__ __launch_bounds__(256) void k_moe_group(const int *__restrict__ route
         pair_slot[e * cap + i] = j;
     }
     __syncthreads();
-    if (threadIdx.x < n_experts) cnt[threadIdx.x] = s_cnt[threadIdx.x];
+    if (threadIdx.x < n_experts) {
+        cnt[threadIdx.x] = s_cnt[threadIdx.x];
+        // running count of (layer, expert) pairs whose weights a pass has to stream (for byte accounting)
+        if (s_cnt[threadIdx.x] > 0) atomicAdd(touched_total, 1ULL);
+    }
 }
 
 enum { MOE_GATEUP = 0, MOE_DOWN = 1 };
