@@ -33,6 +33,7 @@ def test_moe_lockstep(name):
     eng.prefill([prompt])
     dec = O.Decoder(t, wt.as_f32, dtype, "bf16")
     worst = 0.0
+    eng.debug_experts_streamed()      # reset: count the verify passes only
     for a_want in case["forced"]:
         truth = O.ar_decode(dec, pair.prefix(), k)
         block = list(truth)
@@ -51,5 +52,7 @@ def test_moe_lockstep(name):
             eng.prefill([pair.prefix()])
         else:
             assert acc[0] == a_want
-    print(f"\n[{name}] max |target logit error| {worst:.2e}")
+    per_pass = eng.debug_experts_streamed() / (len(case["forced"]) * t.n_layers)
+    print(f"\n[{name}] max |target logit error| {worst:.2e}; experts streamed per layer and verify pass: {per_pass:.1f} of {t.n_experts}")
+    assert per_pass > t.top_k      # the rows of a block do go to different experts (the grouped path is exercised)
     eng.close()
