@@ -570,7 +570,8 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             a.W = (const uint4 *)(lw + m.lo_router); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = CG;
             a.n_experts = mc.n_experts; a.top_k = mc.top_k; a.route_e = w.route_e; a.route_w = w.route_w;
             a.route_spread = (c->route_spread && (mc.n_experts & (mc.n_experts - 1)) == 0) ? l + 1 : 0;
-            rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, 0);
+            static const int router_S = getenv("DEER_ROUTER_SPLIT") ? atoi(getenv("DEER_ROUTER_SPLIT")) : 0;
+            rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, router_S);
             if (rc) return rc;
             const int cap = rows, chunks = ntiles;
             hipLaunchKernelGGL(k_moe_group, dim3(1), dim3(256), 0, s, w.route_e, w.rm.slot, rows, mc.top_k, mc.n_experts, cap,

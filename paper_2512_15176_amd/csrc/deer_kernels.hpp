@@ -1085,25 +1085,43 @@ __global__ __launch_bounds__(256) void k_moe_combine(const float *__restrict__ m
                                                      uint4 *__restrict__ xlo, float *__restrict__ ssq, int d) {
     __shared__ float tile[32 * RED_STRIDE];
     const int cg = blockIdx.x, t = blockIdx.y, ncg = gridDim.x;
-    for (int e = threadIdx.x; e < 32 * CG; e += 256) {
-        const int row = e >> 7, col = e & 127;
+    // 1024 float4 elements of the 32 x 128 tile, four per thread; all loads of a thread are requested before
+    // the first is used (the expert outputs of a row are summed in routing order, then added to h)
+    float4 hv[4], mv[4][8];
+    bool live[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e4 = threadIdx.x + 256 * i, row = e4 >> 5, c4 = (e4 & 31) * 4;
         const int grow = t * 32 + row;
-        const size_t gi = (size_t)grow * d + cg * CG + col;
-        float v = h[gi];
-        if (row_slot[grow] >= 0) {
-            float add = 0.f;
-            for (int j = 0; j < top_k; ++j) add += moe_out[((size_t)grow * 8 + j) * d + cg * CG + col];
-            v += add;
-        }
-        h[gi] = v;
-        tile[row * RED_STRIDE + col] = v;
+        live[i] = row_slot[grow] >= 0;
+        hv[i] = *(const float4 *)(h + (size_t)grow * d + cg * CG + c4);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            mv[i][j] = (live[i] && j < top_k) ? *(const float4 *)(moe_out + ((size_t)grow * 8 + j) * d + cg * CG + c4)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e4 = threadIdx.x + 256 * i, row = e4 >> 5, c4 = (e4 & 31) * 4;
+        float4 add = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { add.x += mv[i][j].x; add.y += mv[i][j].y; add.z += mv[i][j].z; add.w += mv[i][j].w; }
+        float4 v = hv[i];
+        if (live[i]) { v.x += add.x; v.y += add.y; v.z += add.z; v.w += add.w; }
+        *(float4 *)(h + (size_t)(t * 32 + row) * d + cg * CG + c4) = v;
+        float *tp = tile + row * RED_STRIDE + c4;
+        tp[0] = v.x; tp[1] = v.y; tp[2] = v.z; tp[3] = v.w;
     }
     __syncthreads();
     tile_to_frag(tile, xhi, xlo, (size_t)t * (d / 16) * 64, cg * CG);
-    if (threadIdx.x < 32) {
+    {   // sum of squares of a row's 128 columns: 8 threads per row, 16 columns each, then a fixed butterfly
+        const int row = threadIdx.x >> 3, sub = threadIdx.x & 7;
         float s = 0.f;
-        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
-        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) { const float v = tile[row * RED_STRIDE + sub * 16 + c]; s += v * v; }
+#pragma unroll
+        for (int off = 1; off < 8; off <<= 1) s += shx(s, off);
+        if (sub == 0) ssq[(size_t)(t * 32 + row) * ncg + cg] = s;
     }
 }
 
