@@ -1458,7 +1458,9 @@ __global__ __launch_bounds__(512) void k_attn(const uint4 *__restrict__ Qhi, con
 // Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
 // of O^T tile tt.  All (M, L) pairs are requested at once, then the partial outputs 16 splits at a time, so a
 // merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
-template <int HD>
+// EARLY (the merge kernel, which has the registers for it): the first 16 partial outputs are requested together
+// with the (M, L) pairs, which makes it two round trips.
+template <int HD, bool EARLY = false>
 __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
                                                 int head, int t, int tt, int hh, int lane, bool near = false) {
     constexpr int PF = AttnPartial<HD>::FLOATS;
@@ -1466,6 +1468,15 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
     const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
     float f[32];
     float M = -INFINITY, L = 0.f;
+    float2 v[16][4];
+    auto load_half = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+#pragma unroll
+            for (int r2 = 0; r2 < 4; ++r2)
+                v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
+    };
+    if (EARLY) load_half(0);
     {
         float2 ml[32];
 #pragma unroll
@@ -1484,12 +1495,7 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
 #pragma unroll
     for (int s0 = 0; s0 < 32; s0 += 16) {
         if (s0 < NS) {
-            float2 v[16][4];
-#pragma unroll
-            for (int u = 0; u < 16; ++u)
-#pragma unroll
-                for (int r2 = 0; r2 < 4; ++r2)
-                    v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
+            if (!(EARLY && s0 == 0)) load_half(s0);
 #pragma unroll
             for (int u = 0; u < 16; ++u)
 #pragma unroll
@@ -1526,7 +1532,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (j >= n_items) return;
     const int hh = j & 1, tt = (j >> 1) % HT, head = (j / (2 * HT)) % Hq, t = j / (2 * HT * Hq);
-    attn_merge_item<HD>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, tt, hh, threadIdx.x & 63);
+    attn_merge_item<HD, true>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, tt, hh, threadIdx.x & 63);
 }
 
 // ------------------------------------------------------------------------------------------
