@@ -1252,6 +1252,10 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
 // (consumers in the same kernel) and the per-operation path alike.  b: the tile's sequence; lim: the key
 // limit of this lane's query row.
 // ------------------------------------------------------------------------------------------
+#ifndef DEER_ATT_P_LO
+#define DEER_ATT_P_LO 1
+#endif
+constexpr bool ATT_P_LO = DEER_ATT_P_LO != 0;   // the low-order bf16 plane of the softmax weights enters P V
 constexpr int ATT_CH = 2;     // key tiles per staged chunk: one per key parity
 constexpr int ATT_NBUF = 4;   // chunk buffers: ATT_NBUF - 1 chunks (96 KB) are on their way while one is multiplied
 struct AttnSmem {
@@ -1390,7 +1394,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
                         for (int s2 = 0; s2 < 2; ++s2) {
                             const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
                             oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
-                            oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+                            if (ATT_P_LO) oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
                         }
                 }
             }
