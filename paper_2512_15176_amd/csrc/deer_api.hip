@@ -526,10 +526,10 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     }
     const int nkt = (max_limit + 31) / 32;
     // key-range splits: aim at one workgroup per compute unit; a split holds at least one staged chunk of 4 key
-    // tiles; ntiles * NS never exceeds the partial buffer (max(64, tiles))
+    // tiles; ntiles * NS never exceeds the partial buffer (max(64, most tiles of a pass) tile slots)
     static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
-    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 3) / 4}));
+    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, std::max(64, c->max_tiles) / ntiles), (nkt + 3) / 4}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     GemmArgs base{};

@@ -1273,8 +1273,12 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
     constexpr int PF = AttnPartial<HD>::FLOATS;
     const int tidx = opaque_tid();
     const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;   // the wave index as a scalar
-    const int g = w & 3, par = w >> 2;
     const int G = Hq / opaque_s(Hkv);
+    // up to four query heads per kv head: wave = (head, key-tile parity); more: wave = head, every key tile, so
+    // that eight heads share one pass over the keys instead of two
+    const bool wide = G > 4;
+    const int g = wide ? w : (w & 3), par = wide ? 0 : (w >> 2);
+    const int npar = wide ? 1 : 2, hpr = wide ? 8 : 4;   // key parities; heads per round
     const int half = lane >> 5, qrow = lane & 31;
     int maxlim = lim, minlim = lim;
 #pragma unroll
@@ -1311,7 +1315,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
         }
     };
 
-    for (int g0 = 0; g0 < G; g0 += 4) {
+    for (int g0 = 0; g0 < G; g0 += hpr) {
         const bool active = g0 + g < G;
         const int head = kvh * G + min(g0 + g, G - 1);
         f32x16 oacc[HT];
@@ -1341,8 +1345,8 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
                 if (later >= 2) wait_loads<2 * LPW>(); else if (later == 1) wait_loads<LPW>(); else wait_loads<0>();
                 __syncthreads();   // every wave's share of chunk ci is in LDS, and chunk ci - 1 has been read by all
                 if (ci + ATT_NBUF - 1 < nchunks) stage(as.buf[(ci + ATT_NBUF - 1) % ATT_NBUF], c0 + (ATT_NBUF - 1) * ATT_CH);
-                if (active && par < ntile) {
-                    const int tl = par;
+                if (active)
+                for (int tl = par; tl < ntile; tl += npar) {
                     const int kt = c0 + tl;
                     const uint4 *fr = as.buf[ci % ATT_NBUF] + (size_t)(tl * FPT) * 64 + lane;
                     f32x16 sacc;
@@ -1404,7 +1408,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
         }
         // combine the two key parities of each head: odd-parity waves park (m, l, O), even-parity waves merge
         float4 *ox = (float4 *)as.buf[0];
-        if (par == 1) {
+        if (par == 1) {   // never in the one-wave-per-head arrangement
             as.ml[g * 64 + lane] = make_float2(m_run, l_run);
 #pragma unroll
             for (int tt = 0; tt < HT; ++tt)
@@ -1414,22 +1418,24 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
         }
         __syncthreads();
         if (par == 0 && active) {
-            const float2 o_ml = as.ml[g * 64 + lane];
-            const float M = fmaxf(m_run, o_ml.x);
-            const float f0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * scale_log2e);
-            const float f1 = (o_ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((o_ml.x - M) * scale_log2e);
-            l_run = f0 * l_run + f1 * o_ml.y;
-            m_run = M;
+            if (!wide) {
+                const float2 o_ml = as.ml[g * 64 + lane];
+                const float M = fmaxf(m_run, o_ml.x);
+                const float f0 = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_run - M) * scale_log2e);
+                const float f1 = (o_ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((o_ml.x - M) * scale_log2e);
+                l_run = f0 * l_run + f1 * o_ml.y;
+                m_run = M;
 #pragma unroll
-            for (int tt = 0; tt < HT; ++tt)
+                for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 v = ox[((g * HT + tt) * 4 + q) * 64 + lane];
-                    oacc[tt][4 * q] = f0 * oacc[tt][4 * q] + f1 * v.x;
-                    oacc[tt][4 * q + 1] = f0 * oacc[tt][4 * q + 1] + f1 * v.y;
-                    oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
-                    oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
-                }
+                    for (int q = 0; q < 4; ++q) {
+                        const float4 v = ox[((g * HT + tt) * 4 + q) * 64 + lane];
+                        oacc[tt][4 * q] = f0 * oacc[tt][4 * q] + f1 * v.x;
+                        oacc[tt][4 * q + 1] = f0 * oacc[tt][4 * q + 1] + f1 * v.y;
+                        oacc[tt][4 * q + 2] = f0 * oacc[tt][4 * q + 2] + f1 * v.z;
+                        oacc[tt][4 * q + 3] = f0 * oacc[tt][4 * q + 3] + f1 * v.w;
+                    }
+            }
             const float l_tot = l_run + shx(l_run, 32);
             if (NS == 1) {
                 attn_write_frag<HD, true>(oacc, l_tot > 0.f ? 1.f / l_tot : 0.f, t, head, Hq, lane, xhi, xlo);
