@@ -62,3 +62,41 @@ def test_8b_layer_widths_prefill_through_tiled_gemm():
     print(f"\n[tiled prefill, 8B layer widths] max |logit error|: drafter {ed:.2e}, target {et:.2e}")
     assert ed < 2e-2 and et < 2e-2
     eng.close()
+
+
+def test_batch_of_64_sequences_through_tiled_gemm():
+    """64 sequences make 2048-row verify passes and 4096-row draft passes (ingest + MASK tiles, LM head on every
+    second tile): every GEMM of both passes, the LM heads included, runs through the tiled kernel."""
+    import torch
+    cfg = di.CONFIGS["tiny"]
+    t, d, k, B = cfg["target"], cfg["drafter"], cfg["k"], 64
+    wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    eng = make_engine(t, d, wt, wd, B, 128, k)
+    eng.debug_gemm_tiled(1)
+    prompts = [di.prompt_ids(t.vocab, 20 + (7 * b) % 41, seq=100 + b) for b in range(B)]
+    eng.prefill(prompts)
+    g = np.random.default_rng(4)
+    check = [0, 1, 17, 40, 63]
+    pairs = {}
+    for b in check:
+        pairs[b] = make_pair(t, d, wt, wd, 128)
+        pairs[b].prefill(prompts[b])
+    for it in range(2):                                  # the second iteration ingests the first one's commits
+        dr = eng.draft_block(k, 0.0, 0)
+        gzd = eng.debug_get_logits(1, k)
+        blocks = g.integers(0, t.vocab, (B, k)).astype(np.int32)
+        for b in check:                                  # forced accepted lengths 0..k on the checked sequences
+            truth = O.ar_decode(O.Decoder(t, wt.as_f32, np.float64, "bf16"), pairs[b].prefix(), k)
+            a_want = (b + 3 * it) % (k + 1)
+            blocks[b] = truth
+            if a_want < k:
+                blocks[b, a_want] = (truth[a_want] + 1) % t.vocab
+        eng.verify_block(k, 0.0, torch.tensor(blocks, device="cuda"))
+        gzt = eng.debug_get_logits(0, k)
+        acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
+        for b in check:
+            res = O.deer_iteration(pairs[b], k, 0.0, None, draft_override=[int(v) for v in blocks[b]])
+            assert np.abs(gzd[b] - res["draft_logits"]).max() < 2e-3, (it, b)
+            assert np.abs(gzt[b] - res["target_logits"]).max() < 2e-3, (it, b)
+            assert acc[b] == res["accept_len"] and com[b] == res["committed"], (it, b)
+    eng.close()
