@@ -71,6 +71,7 @@ struct Work {   // carved from the workspace
     double *theta[2] = {nullptr, nullptr};
     // persistent pass kernel: per-layer activation fragments (dense models, two tiles) and its barrier words
     size_t part_floats = 0;   // capacity of `part`
+    int4 *pf_desc = nullptr;  // prefill: per-tile (sequence, first position, rows, offset into ids)
     uint4 *pass_x = nullptr; size_t pass_x_vecs = 0;
     unsigned *pass_sync = nullptr;
     unsigned long long *pass_stamps = nullptr;   // [PASS_MAX_BLOCKS][PASS_STAMPS], written on request
@@ -239,7 +240,8 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.stat = (RowStat *)take(lmrows * (V / CG) * sizeof(RowStat));
     w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
     w.ao.accept_len = (int *)take(B * 4); w.ao.n_committed = (int *)take(B * 4); w.ao.committed = (int *)take((size_t)B * 32 * 4);
-    w.ids = (int *)take((size_t)p.max_seq * 4);
+    w.ids = (int *)take((size_t)B * p.max_seq * 4);
+    w.pf_desc = (int4 *)take((size_t)MAXT * sizeof(int4));
     for (const deer_model_cfg *mc : {&t, &d}) {
         if (!mc->n_experts || w.route_e) continue;
         const size_t chunks = MAXT;   // 32-pair chunks per expert: at most every row of the pass
@@ -776,31 +778,57 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     }
     Work &w = c->wk;
     std::vector<int> pend(batch), lenv(lens, lens + batch);
-    size_t off = 0;
+    std::vector<size_t> offs(batch);
+    size_t total = 0;
     for (int b = 0; b < batch; ++b) {
-        const int n = lens[b];
-        for (int i = 0; i < n; ++i)
-            if (ids[off + i] < 0 || ids[off + i] >= c->p.target.vocab) return fail(c, DEER_EINVAL, "token id outside the vocabulary");
-        HIPCHK(c, hipMemcpyAsync(w.ids, ids + off, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
-        for (int model = 0; model < 2; ++model) {
-            const int nrows = (model == DEER_TARGET) ? n - 1 : n;   // the last token stays pending for the target
-            const int chunk = 32 * prefill_tiles(c->p);
-            for (int c0 = 0; c0 < nrows; c0 += chunk) {
-                const int nr = std::min(chunk, nrows - c0);
-                const int ntiles = (nr + 31) / 32;
-                hipLaunchKernelGGL(k_rows_prefill, dim3(ntiles), dim3(32), 0, c->stream, w.rm, w.ids, b, c0, nr);
-                LAUNCHCHK(c, "k_rows_prefill");
-                LmPlan lm{false, 0, 1, 0, 0, 0.f, 0};
-                int rc = run_pass(c, model, ntiles, c0 + nr, lm);
-                if (rc) return rc;
+        offs[b] = total;
+        for (int i = 0; i < lens[b]; ++i)
+            if (ids[total + i] < 0 || ids[total + i] >= c->p.target.vocab) return fail(c, DEER_EINVAL, "token id outside the vocabulary");
+        total += lens[b];
+        pend[b] = ids[total - 1];
+    }
+    HIPCHK(c, hipMemcpyAsync(w.ids, ids, total * 4, hipMemcpyHostToDevice, c->stream));
+    // Passes of up to cap tiles; a pass takes the next rows of as many sequences as fit, each sequence's rows in
+    // whole tiles (rows of one sequence that are split over passes continue in the next pass, over the keys the
+    // earlier pass has written).  The descriptor lists stay alive until the stream has been waited for.
+    const int cap = prefill_tiles(c->p);
+    std::vector<std::vector<int4>> kept;
+    for (int model = 0; model < 2; ++model) {
+        std::vector<int4> desc;
+        int maxlim = 0;
+        auto flush = [&]() -> int {
+            if (desc.empty()) return DEER_OK;
+            kept.push_back(desc);
+            const std::vector<int4> &dsc = kept.back();
+            const int ntiles = (int)dsc.size();
+            HIPCHK(c, hipMemcpyAsync(w.pf_desc, dsc.data(), dsc.size() * sizeof(int4), hipMemcpyHostToDevice, c->stream));
+            hipLaunchKernelGGL(k_rows_prefill, dim3(ntiles), dim3(32), 0, c->stream, w.rm, w.ids, w.pf_desc);
+            LAUNCHCHK(c, "k_rows_prefill");
+            LmPlan lm{false, 0, 1, 0, 0, 0.f, 0};
+            int rc = run_pass(c, model, ntiles, maxlim, lm);
+            desc.clear();
+            maxlim = 0;
+            return rc;
+        };
+        for (int b = 0; b < batch; ++b) {
+            const int nrows = (model == DEER_TARGET) ? lens[b] - 1 : lens[b];   // the last token stays pending for the target
+            int c0 = 0;
+            while (c0 < nrows) {
+                if ((int)desc.size() == cap)
+                    if (int rc = flush()) return rc;
+                const int room = cap - (int)desc.size();
+                const int take = std::min(nrows - c0, room * 32);
+                for (int i = 0; i < take; i += 32)
+                    desc.push_back(make_int4(b, c0 + i, std::min(32, take - i), (int)(offs[b] + c0 + i)));
+                maxlim = std::max(maxlim, c0 + take);
+                c0 += take;
             }
         }
-        if (int rc = pass_error_fetch(c)) return rc;
-        HIPCHK(c, hipStreamSynchronize(c->stream));   // w.ids is reused by the next sequence
-        if (int rc = pass_error_check(c)) return rc;
-        pend[b] = ids[off + n - 1];
-        off += n;
+        if (int rc = flush()) return rc;
     }
+    if (int rc = pass_error_fetch(c)) return rc;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (int rc = pass_error_check(c)) return rc;
     return upload_state(c, batch, lenv.data(), lenv.data(), pend.data());
 }
 

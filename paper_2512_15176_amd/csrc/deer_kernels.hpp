@@ -330,12 +330,14 @@ __global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int ti
     }
 }
 
-// prefill chunk: rows c0..c0+n-1 of sequence b's prompt, causal; tiles 0..ntiles-1
-__global__ void k_rows_prefill(RowMeta rm, const int *__restrict__ ids, int b, int c0, int n) {
-    int row = blockIdx.x * 32 + threadIdx.x;
-    if (threadIdx.x == 0) rm.tile_seq[blockIdx.x] = b;
-    if (row < n) {
-        rm.tok[row] = ids[c0 + row]; rm.pos[row] = c0 + row; rm.slot[row] = c0 + row; rm.limit[row] = c0 + row + 1;
+// prefill pass: tile t holds desc[t].z rows of sequence desc[t].x, causal, at positions desc[t].y + r, whose token
+// ids start at ids[desc[t].w].  A pass may hold tiles of several sequences (each sequence's rows in whole tiles).
+__global__ void k_rows_prefill(RowMeta rm, const int *__restrict__ ids, const int4 *__restrict__ desc) {
+    const int4 dsc = desc[blockIdx.x];
+    const int r = threadIdx.x, row = blockIdx.x * 32 + r;
+    if (r == 0) rm.tile_seq[blockIdx.x] = dsc.x;
+    if (r < dsc.z) {
+        rm.tok[row] = ids[dsc.w + r]; rm.pos[row] = dsc.y + r; rm.slot[row] = dsc.y + r; rm.limit[row] = dsc.y + r + 1;
     } else {
         rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
     }
