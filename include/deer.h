@@ -117,8 +117,8 @@ int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int exper
 
 /* Prefix x_{1:j} for `batch` sequences (Alg. 1, Input).  prompt_ids_host: concatenated ids;
  * prompt_lens_host[b] >= 1.  Builds the target cache for x_{1:j-1} and the drafter cache for
- * x_{1:j} with causal attention, in chunks of 512 rows (each chunk streams the weights once).  Waits
- * for completion. */
+ * x_{1:j} with causal attention, in passes of up to 4096 rows (512 for mixture models) that hold the rows
+ * of as many sequences as fit (each pass streams the weights once).  Waits for completion. */
 int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *prompt_ids_host, const int32_t *prompt_lens_host);
 
 /* Sets the state as if `lens_host[b]` tokens had been prefilled, WITHOUT running the models:
