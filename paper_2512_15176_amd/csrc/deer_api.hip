@@ -587,14 +587,14 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             ma.N = 2 * m.F; ma.KS = d / 16;
             {
                 ProfScope ps(c, 0, 0.0);
-                hipLaunchKernelGGL(k_gemm_moe<MOE_GATEUP>, dim3(2 * m.F / CG, mc.n_experts, chunks), dim3(512), 0, s, ma);
+                hipLaunchKernelGGL(k_gemm_moe<MOE_GATEUP>, dim3((2 * m.F / CG + MOE_CGS - 1) / MOE_CGS, mc.n_experts, chunks), dim3(512), 0, s, ma);
             }
             LAUNCHCHK(c, "k_gemm_moe gate/up");
             ma.W = (const uint4 *)(lw + m.lo_d); ma.wexp_stride = m.exp_d_bytes / 16; ma.Xhi = w.act_hi; ma.Xlo = w.act_lo;
             ma.N = d; ma.KS = m.F / 16;
             {
                 ProfScope ps(c, 0, 0.0);
-                hipLaunchKernelGGL(k_gemm_moe<MOE_DOWN>, dim3(d / CG, mc.n_experts, chunks), dim3(512), 0, s, ma);
+                hipLaunchKernelGGL(k_gemm_moe<MOE_DOWN>, dim3((d / CG + MOE_CGS - 1) / MOE_CGS, mc.n_experts, chunks), dim3(512), 0, s, ma);
             }
             LAUNCHCHK(c, "k_gemm_moe down");
             hipLaunchKernelGGL(k_moe_combine, dim3(ncg_d, ntiles), dim3(256), 0, s, w.moe_out, w.rm.slot, mc.top_k, w.h, w.xa_hi,

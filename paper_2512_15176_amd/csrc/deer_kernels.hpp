@@ -967,16 +967,24 @@ struct MoeArgs {
     const float *route_w; float *moe_out; int d;        // DOWN out: moe_out[row][slot][d] = w * y
 };
 
-// grid: x = column group, y = expert, z = chunk of 32 pairs.  Same streaming loop and wave tree as k_gemm.
+#ifndef DEER_MOE_CGS
+#define DEER_MOE_CGS 2
+#endif
+constexpr int MOE_CGS = DEER_MOE_CGS;   // column groups per workgroup of the grouped expert GEMMs
+// grid: x = MOE_CGS column groups, y = expert, z = chunk of 32 pairs.  Same streaming loop and wave tree as k_gemm.
+// A workgroup does MOE_CGS column groups one after the other and requests the first k-steps of the next before it
+// sums and stores the current one: with one workgroup per CU at a time, a launch of many short work items otherwise
+// leaves the memory pipe idle during every item's wave sum, epilogue and first-load latency.
 template <int MODE>
 __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
     __shared__ float red[8 * 32 * 128];
     __shared__ float tile[32 * RED_STRIDE];
     __shared__ float s_rstd[32];
     __shared__ int s_row[32], s_slot[32];
-    const int cg = blockIdx.x, ex = blockIdx.y, chunk = blockIdx.z;
+    const int ex = blockIdx.y, chunk = blockIdx.z;
     const int n = a.cnt[ex] - chunk * 32;
     if (n <= 0) return;
+    const int ncg = a.N / CG;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, half = lane >> 5, cl = lane & 31;
     const int KS = a.KS;
     if (threadIdx.x < 32) {
@@ -985,15 +993,20 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
         s_slot[threadIdx.x] = v ? a.pair_slot[ex * a.cap + chunk * 32 + threadIdx.x] : 0;
     }
     __syncthreads();
+    if (MODE == MOE_GATEUP && threadIdx.x < 32) {   // RMSNorm factor of each pair's row
+        float sc = 0.f;
+        const int r = s_row[threadIdx.x];
+        if (r >= 0) {
+            const float *p = a.ssq_in + (size_t)r * a.ncg_in;
+            float ss = 0.f;
+            for (int g = 0; g < a.ncg_in; ++g) ss += p[g];
+            sc = rsqrtf(ss / (float)a.d_in + a.eps);
+        }
+        s_rstd[threadIdx.x] = sc;
+    }
     const int myrow = s_row[cl];
     const int per = (KS + 7) / 8;
     const int ks0 = w * per, ks1 = min(KS, ks0 + per);
-    f32x16 acc[4];
-#pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
-    const uint4 *wp = a.W + (size_t)ex * a.wexp_stride + ((size_t)(cg * 4) * KS) * 64 + lane;
     const size_t wstride = (size_t)KS * 64;
     // activation fragment of this lane: GATEUP gathers the pair's own row out of the pass's tiles
     const uint4 *xh, *xl;
@@ -1009,75 +1022,81 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
     const uint4 z4 = make_uint4(0u, 0u, 0u, 0u);
     constexpr int D = 4;
     uint4 wb[D][4], xhb[D], xlb[D];
-#pragma unroll
-    for (int dd = 0; dd < D; ++dd) {
-        int ks = ks0 + dd;
-        if (ks < ks1) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
-            xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
-        }
-    }
-    for (int kb = ks0; kb < ks1; kb += D) {
+    auto first_loads = [&](int cg) {
+        const uint4 *wp = a.W + (size_t)ex * a.wexp_stride + ((size_t)(cg * 4) * KS) * 64 + lane;
 #pragma unroll
         for (int dd = 0; dd < D; ++dd) {
-            int ks = kb + dd;
+            int ks = ks0 + dd;
             if (ks < ks1) {
-                const uint4 ah = live ? xhb[dd] : z4, al = live ? xlb[dd] : z4;
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    acc[nb] = mfma32(ah, wb[dd][nb], acc[nb]);
-                    acc[nb] = mfma32(al, wb[dd][nb], acc[nb]);
-                }
-                int kn = ks + D;
-                if (kn < ks1) {
+                for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
+                xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
+            }
+        }
+    };
+    const int cg_first = blockIdx.x * MOE_CGS;
+    first_loads(cg_first);
+#pragma unroll 1
+    for (int it = 0; it < MOE_CGS; ++it) {
+        const int cg = cg_first + it;
+        if (cg >= ncg) break;
+        const uint4 *wp = a.W + (size_t)ex * a.wexp_stride + ((size_t)(cg * 4) * KS) * 64 + lane;
+        f32x16 acc[4];
 #pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
-                    xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+        for (int kb = ks0; kb < ks1; kb += D) {
+#pragma unroll
+            for (int dd = 0; dd < D; ++dd) {
+                int ks = kb + dd;
+                if (ks < ks1) {
+                    const uint4 ah = live ? xhb[dd] : z4, al = live ? xlb[dd] : z4;
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) {
+                        acc[nb] = mfma32(ah, wb[dd][nb], acc[nb]);
+                        acc[nb] = mfma32(al, wb[dd][nb], acc[nb]);
+                    }
+                    int kn = ks + D;
+                    if (kn < ks1) {
+#pragma unroll
+                        for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
+                        xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
+                    }
                 }
             }
         }
-    }
-    reduce_waves_to_tile(acc, red, tile, w, lane);
-    if (MODE == MOE_GATEUP && threadIdx.x < 32) {
-        float sc = 0.f;
-        const int r = s_row[threadIdx.x];
-        if (r >= 0) {
-            const float *p = a.ssq_in + (size_t)r * a.ncg_in;
-            float ss = 0.f;
-            for (int g = 0; g < a.ncg_in; ++g) ss += p[g];
-            sc = rsqrtf(ss / (float)a.d_in + a.eps);
-        }
-        s_rstd[threadIdx.x] = sc;
-    }
-    __syncthreads();
-    if (MODE == MOE_GATEUP) {
-        for (int item = threadIdx.x; item < 256; item += blockDim.x) {
-            const int row = item & 31, oct = item >> 5;
-            float v[8];
+        if (it + 1 < MOE_CGS && cg + 1 < ncg) first_loads(cg + 1);   // on their way during the sum and the epilogue below
+        reduce_waves_to_tile(acc, red, tile, w, lane);
+        if (MODE == MOE_GATEUP) {
+            for (int item = threadIdx.x; item < 256; item += blockDim.x) {
+                const int row = item & 31, oct = item >> 5;
+                float v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float g = tile[row * RED_STRIDE + oct * 8 + e] * s_rstd[row];
-                float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * s_rstd[row];
-                v[e] = g / (1.f + expf(-g)) * u;
+                for (int e = 0; e < 8; ++e) {
+                    float g = tile[row * RED_STRIDE + oct * 8 + e] * s_rstd[row];
+                    float u = tile[row * RED_STRIDE + 64 + oct * 8 + e] * s_rstd[row];
+                    v[e] = g / (1.f + expf(-g)) * u;
+                }
+                uint4 hi, lo;
+                pack8_split(v, hi, lo);
+                size_t vec = (size_t)(ex * a.chunks + chunk) * (a.Fe / 16) * 64 + frag_vec(row, cg * 8 + oct);
+                a.ahi[vec] = hi;
+                a.alo[vec] = lo;
             }
-            uint4 hi, lo;
-            pack8_split(v, hi, lo);
-            size_t vec = (size_t)(ex * a.chunks + chunk) * (a.Fe / 16) * 64 + frag_vec(row, cg * 8 + oct);
-            a.ahi[vec] = hi;
-            a.alo[vec] = lo;
+        } else {
+            for (int e = threadIdx.x; e < 32 * 32; e += blockDim.x) {
+                const int row = e >> 5, c4 = (e & 31) * 4;
+                const int pr = s_row[row];
+                if (pr < 0) continue;
+                const int slot = s_slot[row];
+                const float wgt = a.route_w[pr * 8 + slot];
+                const float *tp = tile + row * RED_STRIDE + c4;
+                *(float4 *)(a.moe_out + ((size_t)pr * 8 + slot) * a.d + cg * CG + c4) =
+                    make_float4(tp[0] * wgt, tp[1] * wgt, tp[2] * wgt, tp[3] * wgt);
+            }
         }
-    } else {
-        for (int e = threadIdx.x; e < 32 * 32; e += blockDim.x) {
-            const int row = e >> 5, c4 = (e & 31) * 4;
-            const int pr = s_row[row];
-            if (pr < 0) continue;
-            const int slot = s_slot[row];
-            const float wgt = a.route_w[pr * 8 + slot];
-            const float *tp = tile + row * RED_STRIDE + c4;
-            *(float4 *)(a.moe_out + ((size_t)pr * 8 + slot) * a.d + cg * CG + c4) =
-                make_float4(tp[0] * wgt, tp[1] * wgt, tp[2] * wgt, tp[3] * wgt);
-        }
+        __syncthreads();   // the tile is read: the next column group's sum may overwrite it
     }
 }
 
