@@ -833,7 +833,10 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     }
 
     // Software pipeline: D k-steps of loads are in flight while older steps are multiplied.
-    constexpr int D = (MT == 1) ? 4 : 2;   // bounded by the register file: no spills
+#ifndef DEER_GEMM_D1
+#define DEER_GEMM_D1 4
+#endif
+    constexpr int D = (MT == 1) ? DEER_GEMM_D1 : 2;   // bounded by the register file: no spills
     uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) {
