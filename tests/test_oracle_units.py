@@ -114,9 +114,14 @@ def test_counter_rng_uniformity_and_range():
 
 
 def test_mix64_known_values():
-    # splitmix64 reference stream for seed 0: first output is mix64(golden) = 0xE220A8397B1DCDAF
-    assert int(O.mix64(np.uint64(0x9E3779B97F4A7C15))) == 0xE220A8397B1DCDAF
-    assert int(O.mix64(np.uint64((2 * 0x9E3779B97F4A7C15) & ((1 << 64) - 1)))) == 0x6E789E6AA1B965F4
+    # splitmix64 reference stream for seed 0 (tests/golden/splitmix64_seed0.txt): output i = mix64((i + 1) * golden)
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "splitmix64_seed0.txt")
+    want = [int(l, 16) for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(want) >= 3
+    for i, w in enumerate(want):
+        state = ((i + 1) * 0x9E3779B97F4A7C15) & ((1 << 64) - 1)
+        assert int(O.mix64(np.uint64(state))) == w
 
 
 def test_gumbel_max_samples_the_categorical():
