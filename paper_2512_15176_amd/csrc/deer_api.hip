@@ -293,7 +293,8 @@ int choose_split(int N, int KS, int zgroups) {
     static const int t_short = getenv("DEER_SPLIT_SHORT") ? atoi(getenv("DEER_SPLIT_SHORT")) : 192;
     static const int t_long = getenv("DEER_SPLIT_LONG") ? atoi(getenv("DEER_SPLIT_LONG")) : 256;
     const int target = KS > 256 ? t_long : t_short;
-    int S = (target + blocks - 1) / blocks;
+    static const int s_floor = getenv("DEER_SPLIT_FLOOR") ? atoi(getenv("DEER_SPLIT_FLOOR")) : 1;
+    int S = s_floor ? std::max(1, target / blocks) : (target + blocks - 1) / blocks;
     // the workgroup that finishes a column group sums S partial tiles (about 0.25 us each) before its epilogue:
     // beyond 8 splits that costs more than the shorter streams save (drafter down projection, 7 column groups:
     // 19 splits 22.8 us, 8 splits 18.5 us)
