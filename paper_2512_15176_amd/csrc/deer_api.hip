@@ -285,12 +285,13 @@ const char *check_params(const deer_init_params *p) {
 // ---------------------------------------------------------------------------------------------
 // launches
 // ---------------------------------------------------------------------------------------------
-// K splits per column group.  Measured on MI355X (per-launch time vs S for the four 8B-shaped matrices):
-// the split-K tail (partial store, arrival, partial loads) costs more than idle CUs once ~190 blocks
-// exist; long-K matrices prefer ~256 blocks.
+// K splits per column group: as many as keep the launch within one wave of workgroups (rounded down: a second
+// wave of workgroups costs more than idle CUs).  Measured on MI355X with the 8B- and 4B-shaped matrices: the split-K
+// tail (partial store, arrival, the last workgroup's sum) makes ~224 workgroups the best target for matrices with up
+// to 256 k-steps, 256 for longer contractions; at most 8 splits; none for contractions of up to 64 k-steps.
 int choose_split(int N, int KS, int zgroups) {
     const int blocks = (N / CG) * zgroups;
-    static const int t_short = getenv("DEER_SPLIT_SHORT") ? atoi(getenv("DEER_SPLIT_SHORT")) : 192;
+    static const int t_short = getenv("DEER_SPLIT_SHORT") ? atoi(getenv("DEER_SPLIT_SHORT")) : 224;
     static const int t_long = getenv("DEER_SPLIT_LONG") ? atoi(getenv("DEER_SPLIT_LONG")) : 256;
     const int target = KS > 256 ? t_long : t_short;
     static const int s_floor = getenv("DEER_SPLIT_FLOOR") ? atoi(getenv("DEER_SPLIT_FLOOR")) : 1;
