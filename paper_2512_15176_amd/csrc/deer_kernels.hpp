@@ -95,6 +95,12 @@ template <int N>
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void tie(u32x4 &r) { asm volatile("" : "+v"(r)); }
 
+// Workgroup barrier for loops that keep direct-to-LDS loads in flight across it: __syncthreads() waits for every
+// outstanding vector memory operation of the wave (its fence covers the LDS writes of those loads), which would
+// empty the ring of staged buffers at every barrier.  This one waits only for the wave's LDS reads; the caller
+// counts down the loads that must have landed with wait_loads<N>() first.
+__device__ __forceinline__ void barrier_keep_loads() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // The thread index as a value the optimiser cannot trace back to the hardware register.  Lane-dependent
 // indices and addresses derived from it are recomputed where they are used instead of being hoisted to the
 // top of a long kernel and kept in registers (or spilled) across all of its phases.
@@ -1367,7 +1373,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
                 // chunk ci has landed once at most the loads of the chunks requested after it are outstanding
                 const int later = min(ATT_NBUF - 2, nchunks - 1 - ci);
                 if (later >= 2) wait_loads<2 * LPW>(); else if (later == 1) wait_loads<LPW>(); else wait_loads<0>();
-                __syncthreads();   // every wave's share of chunk ci is in LDS, and chunk ci - 1 has been read by all
+                barrier_keep_loads();   // every wave's share of chunk ci is in LDS, and chunk ci - 1 has been read by all
                 if (ci + ATT_NBUF - 1 < nchunks) stage(as.buf[(ci + ATT_NBUF - 1) % ATT_NBUF], c0 + (ATT_NBUF - 1) * ATT_CH);
                 if (active)
                 for (int tl = par; tl < ntile; tl += npar) {

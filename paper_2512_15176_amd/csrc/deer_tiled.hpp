@@ -112,7 +112,7 @@ __global__ __launch_bounds__(512) void k_gemm_tiled(const GemmArgs a, int ncg, i
             case 3: wait_loads<3 * TG_LPW>(); break;
             default: wait_loads<4 * TG_LPW>(); break;
         }
-        __syncthreads();   // all waves' shares are in LDS, and stage it - 1 has been read by all
+        barrier_keep_loads();   // all waves' shares are in LDS, and stage it - 1 has been read by all
         if (it + TG_NST - 1 < nst) stage((it + TG_NST - 1) % TG_NST, it + TG_NST - 1);
         const uint4 *sb = sm.st[it % TG_NST] + lane;
 #pragma unroll
