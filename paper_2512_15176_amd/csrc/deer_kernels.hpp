@@ -719,7 +719,7 @@ __device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *re
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             red4[(w * 16 + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
-    __syncthreads();
+    barrier_keep_loads();   // LDS traffic only: loads requested earlier (next item, old h) stay in flight
     const int half = lane >> 5, cl = lane & 31;
     float4 v[2][8];
 #pragma unroll
@@ -735,7 +735,7 @@ __device__ __forceinline__ void reduce_waves_to_tile(f32x16 (&acc)[4], float *re
         float *tp = tile + (8 * q + 4 * half) * RED_STRIDE + nb * 32 + cl;   // rows 8q + 4*half + 0..3
         tp[0] = sum.x; tp[RED_STRIDE] = sum.y; tp[2 * RED_STRIDE] = sum.z; tp[3 * RED_STRIDE] = sum.w;
     }
-    __syncthreads();
+    barrier_keep_loads();   // LDS traffic only: loads requested earlier (next item, old h) stay in flight
 }
 
 struct GemmSmem {
