@@ -56,3 +56,26 @@ def test_moe_lockstep(name):
     print(f"\n[{name}] max |target logit error| {worst:.2e}; experts streamed per layer and verify pass: {per_pass:.1f} of {t.n_experts}")
     assert per_pass > t.top_k      # the rows of a block do go to different experts (the grouped path is exercised)
     eng.close()
+
+
+def test_uniform_routing_stand_in_spreads_the_rows():
+    """The benchmarking aid: with deer_debug_route_spread a block of 32 rows touches about
+    n (1 - (1 - top_k / n)^32) experts per layer, whatever the (random-init) router would choose."""
+    import torch
+    t = di.scaled(di.CONFIGS["qwen3_30b_a3b"]["target"], n_layers=3, vocab=4096)
+    d = di.scaled(di.DRAFTER_05B, n_layers=1, vocab=4096)
+    wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    eng = make_engine(t, d, wt, wd, 1, 256, 32)
+    eng.prefill([di.prompt_ids(t.vocab, 40)])
+    eng.debug_route_spread(True)
+    eng.debug_experts_streamed()
+    dr = eng.draft_block(32, 0.0, 0)
+    eng.verify_block(32, 0.0, dr)
+    per_layer = eng.debug_experts_streamed() / t.n_layers
+    expected = t.n_experts * (1.0 - (1.0 - t.top_k / t.n_experts) ** 32)
+    assert abs(per_layer - expected) < 8, (per_layer, expected)
+    acc, com, ncom = eng.accept_and_commit(32, 0.0, 0)
+    assert 0 <= acc[0] <= 32 and ncom[0] >= 1
+    logits_finite = np.isfinite(eng.debug_get_logits(0, 32)).all()
+    assert logits_finite
+    eng.close()

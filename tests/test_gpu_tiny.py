@@ -197,3 +197,24 @@ def test_recomputing_both_caches_every_iteration_gives_the_same_text(setup):
             assert min(top2_margin(zt0).min(), top2_margin(zd0).min()) < 1e-2, (it, a0, c0, a1, c1)
             break
     assert it >= 2
+
+
+def test_gemm_stamps_are_ordered(setup):
+    """deer_debug_gemm_stamps: every workgroup of the chosen launch records start <= multiplied <= stored, and in
+    a split launch exactly one workgroup per column group records the finish."""
+    eng, wt, wd, torch = setup
+    k = CFG["k"]
+    from paper_2512_15176_amd import binding
+    eng.prefill([di.prompt_ids(CFG["target"].vocab, 40, seq=3)])
+    for launch in (0, 1, 3):                      # QKV, O and down projection of the target's first layer
+        eng.debug_gemm_stamps(binding.DEER_TARGET, launch)
+        dr = eng.draft_block(k, 0.0, 0)
+        eng.verify_block(k, 0.0, dr)
+        eng.accept_and_commit(k, 0.0, 0)
+        st = eng.debug_gemm_stamps(binding.DEER_TARGET, -1)
+        assert st is not None and st.shape[1] == 8 and st.shape[0] >= 1
+        assert (st[:, 0] > 0).all() and (st[:, 1] >= st[:, 0]).all() and (st[:, 2] >= st[:, 1]).all()
+        split = (st[:, 3] > 0).any()
+        if split:
+            assert (st[:, 3] >= st[:, 2]).all() and 1 <= (st[:, 4] > 0).sum() <= st.shape[0]
+    assert eng.debug_gemm_stamps(binding.DEER_TARGET, -1) is None      # recording is off again
