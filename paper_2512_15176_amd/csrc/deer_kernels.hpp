@@ -842,7 +842,10 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
 #ifndef DEER_GEMM_D1
 #define DEER_GEMM_D1 4
 #endif
-    constexpr int D = (MT == 1) ? DEER_GEMM_D1 : 2;   // bounded by the register file: no spills
+#ifndef DEER_GEMM_D2
+#define DEER_GEMM_D2 3
+#endif
+    constexpr int D = (MT == 1) ? DEER_GEMM_D1 : DEER_GEMM_D2;   // bounded by the register file: no spills
     uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) {
