@@ -177,16 +177,16 @@ def extras(eng, torch, k, T, vocab, x_pending):
     Batch 1, T = 0.  x_pending: the last committed token (the first row of the next verify pass)."""
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def iters(kk, reps, warm=2):
+    def iters(kk, reps, warm=2, T=T):
         rows = []
         for i in range(warm + reps):
             e = [ev() for _ in range(4)]
             e[0].record()
-            dr = eng.draft_block(kk, T, di.SAMPLING_SEED)
+            dr = eng.draft_block(kk, T, di.SAMPLING_SEED + i)
             e[1].record()
             eng.verify_block(kk, T, dr)
             e[2].record()
-            _, com, _ = eng.accept_and_commit(kk, T, di.SAMPLING_SEED)
+            _, com, _ = eng.accept_and_commit(kk, T, di.SAMPLING_SEED + i)
             e[3].record()
             torch.cuda.synchronize()
             if i >= warm:
@@ -204,6 +204,9 @@ def extras(eng, torch, k, T, vocab, x_pending):
                           "tokens_per_s_mean_accept_3k/4": trunc_geom(kk, 3 * kk / 4)[1] / (tot * 1e-3)}
     (_, tv1, ta1), x_pending = iters(1, 10)
     ar_ms = tv1 + ta1
+    # the same step with sampling (T = 1): both LM heads also write their k x vocab logits, acceptance reads them
+    (tds, tvs, tas), x_pending = iters(k, 10, T=1.0)
+    sampling = {"T": 1.0, "draft_ms": tds, "verify_ms": tvs, "accept_ms": tas}
     bonus = None
     if k >= 31:   # bonus-token variant: 31 drafts + the pending token = 32 target rows, up to 32 committed tokens
         eng.set_bonus_token(True)
@@ -263,7 +266,7 @@ def extras(eng, torch, k, T, vocab, x_pending):
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
         by_ingest[str(m)] = {"ingested_rows": got, "draft_ms": float(np.median(ts))}
-    return sweep, ar_ms, by_ingest, bonus, multipass
+    return sweep, ar_ms, by_ingest, bonus, multipass, sampling
 
 
 def weighted_draft_ms(by_ingest, k, mean):
@@ -532,7 +535,8 @@ def main():
         out["prefill"] = {"tokens": B * prefix, "seconds": prefill_s, "tokens_per_s": B * prefix / prefill_s,
                           "gemm_TFLOPs_algorithmic": fl / 1e12, "frac_of_bf16_mfma_peak": fl / prefill_s / 2.5e15}
     if B == 1 and T == 0.0 and not args.no_extras:
-        sweep, ar_ms, by_ingest, bonus, multipass = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        sweep, ar_ms, by_ingest, bonus, multipass, sampling = extras(eng, torch, k, T, t.vocab, com[0][-1])
+        out["sampling_step"] = sampling
         out["multipass_draft"] = multipass
         if bonus:
             out["bonus_token_variant"] = bonus
