@@ -1642,17 +1642,20 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
     const int kt = k + bonus;           // target rows per sequence
     const int j = st.len[b];
     const float invT = 1.f / T;
-    if (threadIdx.x == 0) {
-        int a = k;
-        for (int i = 0; i < k; ++i) {
+    if (threadIdx.x < 64) {   // the k tests at once (each has its own uniform and rows), then the first rejection
+        const int i = threadIdx.x;
+        int rej = k;
+        if (i < k) {
             const size_t rt = (size_t)b * kt + i, rd = (size_t)b * k + i;
             const int y = d[i];
             const float logp = tlogits[rt * V + y] * invT - tres[rt].lse;
             const float logq = dlogits[rd * V + y] * invT - dres[rd].lse;
             const float u = uniform01(row_key(seed, TAG_ACCEPT, (uint64_t)b, (uint64_t)(j + i)), 0);
-            if (!(logf(u) <= fminf(0.f, logp - logq))) { a = i; break; }
+            if (!(logf(u) <= fminf(0.f, logp - logq))) rej = i;
         }
-        s_a = a;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) rej = min(rej, shx(rej, off));
+        if (i == 0) s_a = rej;
     }
     __syncthreads();
     const int a = s_a;
