@@ -71,6 +71,7 @@ struct Work {   // carved from the workspace
     double *theta[2] = {nullptr, nullptr};
     // persistent pass kernel: per-layer activation fragments (dense models, two tiles) and its barrier words
     size_t part_floats = 0;   // capacity of `part`
+    AccPart *acc_part = nullptr; int *acc_cnt = nullptr;   // sampling acceptance: per-share candidates, arrival counters
     int4 *pf_desc = nullptr;  // prefill: per-tile (sequence, first position, rows, offset into ids)
     uint4 *pass_x = nullptr; size_t pass_x_vecs = 0;
     unsigned *pass_sync = nullptr;
@@ -241,6 +242,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.stat = (RowStat *)take(lmrows * (V / CG) * sizeof(RowStat));
     w.res[0] = (RowResult *)take(lmrows * sizeof(RowResult)); w.res[1] = (RowResult *)take(lmrows * sizeof(RowResult));
     w.ao.accept_len = (int *)take(B * 4); w.ao.n_committed = (int *)take(B * 4); w.ao.committed = (int *)take((size_t)B * 32 * 4);
+    w.acc_part = (AccPart *)take((size_t)B * ACC_NB * sizeof(AccPart));
     w.ids = (int *)take((size_t)B * p.max_seq * 4);
     w.pf_desc = (int4 *)take((size_t)MAXT * sizeof(int4));
     for (const deer_model_cfg *mc : {&t, &d}) {
@@ -254,10 +256,11 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     }
     {
         const size_t ng = (size_t)(std::max(std::max(t.d_model, d.d_model), 4 * (int)fmax) / CG + 64) * MAXT, na = (size_t)MAXT * hq;
-        w.cnt_base = take((ng + na) * 4);
+        w.cnt_base = take((ng + na + (size_t)B) * 4);
         w.gemm_cnt = (int *)w.cnt_base;
         w.attn_cnt = w.gemm_cnt ? w.gemm_cnt + ng : nullptr;
-        w.cnt_bytes = (ng + na) * 4;
+        w.acc_cnt = w.gemm_cnt ? w.gemm_cnt + ng + na : nullptr;
+        w.cnt_bytes = (ng + na + (size_t)B) * 4;
     }
     for (const deer_model_cfg *mc : {&t, &d}) {
         if (mc->n_experts) continue;
@@ -923,9 +926,9 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
         hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET], k,
                            c->p.eos_token_id, c->bonus);
     else
-        hipLaunchKernelGGL(k_accept_sample, dim3(B), dim3(1024), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET],
+        hipLaunchKernelGGL(k_accept_sample, dim3(B, ACC_NB), dim3(1024), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET],
                            w.res[DEER_DRAFTER], w.logits[DEER_TARGET], w.logits[DEER_DRAFTER], k, V, T, seed, c->p.eos_token_id,
-                           c->bonus);
+                           c->bonus, w.acc_part, w.acc_cnt);
     LAUNCHCHK(c, "k_accept");
     const int cs = k + c->bonus;   // committed tokens per sequence: at most k, or k + 1 with the bonus token
     {   // the three result arrays lie one after the other in the workspace: one copy instead of three

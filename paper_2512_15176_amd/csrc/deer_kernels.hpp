@@ -1625,17 +1625,24 @@ __global__ void k_accept_greedy(SeqState st, AcceptOut out, const int *__restric
 // replacement from max(0, p_i - q_i) by Gumbel-max (falls back to p_i when the residual is empty).
 // With the bonus token on, k acceptances are followed by a draw from p_{k+1} (a residual without a draft:
 // the same generator stream at position j + k, weights p).
+// Grid (sequence, ACC_NB): every workgroup repeats the k tests (cheap), then scans its share of the vocabulary
+// row; the candidates of the ACC_NB shares meet through memory and the workgroup that arrives last picks the
+// winner (largest perturbed weight, lowest index on ties: the same token whatever the split) and commits.
+constexpr int ACC_NB = 32;
+struct AccPart { float best; int bi; float bestp; int bpi; int any; int pad[3]; };
+
 __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut out, const int *__restrict__ draft,
                                                         const RowResult *__restrict__ tres,
                                                         const RowResult *__restrict__ dres,
                                                         const float *__restrict__ tlogits,
                                                         const float *__restrict__ dlogits, int k, int V, float T,
-                                                        uint64_t seed, int eos, int bonus) {
-    __shared__ int s_a;
-    __shared__ float sv[1024]; __shared__ int sx[1024]; __shared__ int s_any[1024];
-    const int b = blockIdx.x;
+                                                        uint64_t seed, int eos, int bonus, AccPart *parts, int *arrivals) {
+    __shared__ int s_a, s_last;
+    __shared__ float sv[1024]; __shared__ int sx[1024];
+    __shared__ float sv2[1024]; __shared__ int sx2[1024]; __shared__ int s_any[1024];
+    const int b = blockIdx.x, nb = gridDim.y, part = blockIdx.y;
     if (st.finished[b]) {
-        if (threadIdx.x == 0) { out.accept_len[b] = 0; out.n_committed[b] = 0; }
+        if (threadIdx.x == 0 && part == 0) { out.accept_len[b] = 0; out.n_committed[b] = 0; }
         return;
     }
     const int *d = draft + b * k;
@@ -1659,40 +1666,58 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
     }
     __syncthreads();
     const int a = s_a;
-    int corr = -1;
-    if (a < k || bonus) {
-        const bool has_q = a < k;       // a drafted token stands at this position
-        const size_t rt = (size_t)b * kt + a, rd = (size_t)b * k + (has_q ? a : 0);
-        const float lt = tres[rt].lse, ld = has_q ? dres[rd].lse : 0.f;
-        const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
-        float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
-        for (int v = threadIdx.x; v < V; v += 1024) {
-            const float logp = tlogits[rt * V + v] * invT - lt;
-            const float gn = gumbel(key, (uint64_t)v);
-            if (has_q) {
-                const float logq = dlogits[rd * V + v] * invT - ld;
-                const float diff = expf(logp) - expf(logq);
-                if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
-            }
-            argmax_merge(bestp, bpi, logp + gn, v);
-        }
-        s_any[threadIdx.x] = any;
-        __syncthreads();
-        for (int off = 512; off > 0; off >>= 1) {
-            if (threadIdx.x < off) s_any[threadIdx.x] |= s_any[threadIdx.x + off];
-            __syncthreads();
-        }
-        const int use_resid = s_any[0];
-        sv[threadIdx.x] = use_resid ? best : bestp;
-        sx[threadIdx.x] = use_resid ? bi : bpi;
-        __syncthreads();
-        for (int off = 512; off > 0; off >>= 1) {
-            if (threadIdx.x < off) argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
-            __syncthreads();
-        }
-        corr = (sx[0] >= 0 && sx[0] < V) ? sx[0] : 0;   // all-NaN rows never update the index
+    if (!(a < k || bonus)) {   // k drafts accepted and no extra token: nothing to draw
+        if (threadIdx.x == 0 && part == 0) commit_tokens(st, out, b, k, a, -1, d, eos, bonus);
+        return;
     }
-    if (threadIdx.x == 0) commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
+    const bool has_q = a < k;       // a drafted token stands at this position
+    const size_t rt = (size_t)b * kt + a, rd = (size_t)b * k + (has_q ? a : 0);
+    const float lt = tres[rt].lse, ld = has_q ? dres[rd].lse : 0.f;
+    const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
+    float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
+    const int share = (V + nb - 1) / nb, v0 = part * share, v1 = min(V, v0 + share);
+    for (int v = v0 + threadIdx.x; v < v1; v += 1024) {
+        const float logp = tlogits[rt * V + v] * invT - lt;
+        const float gn = gumbel(key, (uint64_t)v);
+        if (has_q) {
+            const float logq = dlogits[rd * V + v] * invT - ld;
+            const float diff = expf(logp) - expf(logq);
+            if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+        }
+        argmax_merge(bestp, bpi, logp + gn, v);
+    }
+    s_any[threadIdx.x] = any; sv[threadIdx.x] = best; sx[threadIdx.x] = bi; sv2[threadIdx.x] = bestp; sx2[threadIdx.x] = bpi;
+    __syncthreads();
+    for (int off = 512; off > 0; off >>= 1) {
+        if (threadIdx.x < off) {
+            s_any[threadIdx.x] |= s_any[threadIdx.x + off];
+            argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
+            argmax_merge(sv2[threadIdx.x], sx2[threadIdx.x], sv2[threadIdx.x + off], sx2[threadIdx.x + off]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        AccPart *pp = parts + (size_t)b * nb + part;
+        __hip_atomic_store(&pp->best, sv[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&pp->bi, sx[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&pp->bestp, sv2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&pp->bpi, sx2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&pp->any, s_any[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (!arrive_last(arrivals + b, nb, &s_last)) return;
+    if (threadIdx.x == 0) {
+        int any_all = 0;
+        for (int p = 0; p < nb; ++p) any_all |= __hip_atomic_load(&parts[(size_t)b * nb + p].any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float wv = -INFINITY; int wi = 0x7fffffff;
+        for (int p = 0; p < nb; ++p) {
+            const AccPart *pp = parts + (size_t)b * nb + p;
+            const float cv = __hip_atomic_load(any_all ? &pp->best : &pp->bestp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int ci = __hip_atomic_load(any_all ? &pp->bi : &pp->bpi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            argmax_merge(wv, wi, cv, ci);
+        }
+        const int corr = (wi >= 0 && wi < V) ? wi : 0;   // all-NaN rows never update the index
+        commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
+    }
 }
 
 }  // namespace deer
