@@ -365,6 +365,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="qwen3_8b")
+    ap.add_argument("--batch", type=int, default=0, help="sequences per step instead of the workload's own number")
+    ap.add_argument("--prefix", type=int, default=0, help="prefix length instead of the workload's own")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--model-routing", action="store_true",
                     help="mixture targets: keep the random-init router's own (collapsed) routing instead of the uniform stand-in")
@@ -392,7 +394,11 @@ def main():
     import torch
     from paper_2512_15176_amd import DeerEngine, binding
 
-    cfg = di.CONFIGS[args.config]
+    cfg = dict(di.CONFIGS[args.config])
+    if args.batch:
+        cfg["batch"] = args.batch
+    if args.prefix:
+        cfg["prefix"] = args.prefix
     t, d, k, prefix, B = cfg["target"], cfg["drafter"], cfg["k"], cfg["prefix"], cfg["batch"]
     T = float(cfg["T"][0])
     long_prefix = prefix * B > 8192          # a real prefill of these would dominate the run

@@ -317,7 +317,15 @@ int choose_split(int N, int KS, int zgroups) {
 template <int EPI>
 int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     a.KS = K / 16;
-    const int MT = (ntiles % 2 == 0) ? 2 : 1;
+    // Row tiles go through a workgroup in pairs (the weights are read once per pair) unless the matrix is small:
+    // then every tile gets workgroups of its own, which find the weights in their XCD's L2, and the workgroup that
+    // finishes a column group runs one epilogue instead of two in a row.  Measured on MI355X: the 0.5B drafter's
+    // pass over two row tiles 2.26 -> 1.71 ms, over 16 tiles (batch 8) 3.73 -> 3.39 ms, over 32 tiles 5.56 -> 5.80 ms
+    // (pairs stay); matrices above 40 MB (the 8B shape's QKV, gate/up and down) lose at any tile count.
+    static const double mt1_bytes = getenv("DEER_MT1_BYTES") ? atof(getenv("DEER_MT1_BYTES")) : 4e7;
+    static const int mt1_tiles = getenv("DEER_MT1_TILES") ? atoi(getenv("DEER_MT1_TILES")) : 16;
+    const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && (double)a.N * K * 2.0 <= mt1_bytes);
+    const int MT = pairs ? 2 : 1;
     const int zg = ntiles / MT;
     a.rows_total = ntiles * 32;
     {   // many rows and enough 256 x 256 tiles to fill the chip: blocked for the matrix cores
