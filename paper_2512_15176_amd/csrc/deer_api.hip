@@ -413,7 +413,7 @@ int pass_occupancy() {
 // Which passes run as the persistent kernel: none unless asked for (deer_debug_pass_mode(1) or
 // DEER_PERSISTENT=1).  Measured on MI355X (batch 1, prefix 4096 / 1024): the 8B-shaped target pass takes
 // 4.70 ms as one persistent kernel against 4.61 ms as one kernel per operation, the 0.5B drafter 2.69 ms
-// against 2.29 ms.
+// against 1.71 ms.
 bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
     if (c->pass_mode != 1 || c->pass_blocks < 1 || c->prof_split) return false;
     if (m.c.n_experts || ntiles > 2 || (lm.on && (lm.n_tiles != 1 || lm.k_lo > 0))) return false;
