@@ -96,6 +96,60 @@ def test_eos_cuts_the_commit_and_finishes_the_sequence(weights):
     eng.close()
 
 
+def test_finished_sequence_beside_a_sampling_one(weights):
+    """T > 0 with one sequence already ended by EOS: it commits nothing more and keeps its length, while the live
+    sequence's acceptance tests and residual draws (its own generator stream, sequence index 1) follow the oracle."""
+    import torch
+    t, d, k, T = CFG["target"], CFG["drafter"], 8, 1.0
+    wt, wd = weights
+    dec = O.Decoder(t, wt.as_f32, np.float64, "bf16")
+    prompt = di.prompt_ids(t.vocab, 30, seq=12)
+    truth = O.ar_decode(dec, prompt, k)
+    eos = truth[2]
+    if eos in truth[:2]:
+        pytest.skip("the chosen continuation repeats its third token")
+    eng = make_engine(t, d, wt, wd, 2, 128, k, eos=eos)
+    other = di.prompt_ids(t.vocab, 21, seq=13)
+    live = make_pair(t, d, wt, wd, 128)
+    live.prefill(other)
+    eng.prefill([prompt, other])
+    # one greedy iteration: sequence 0 accepts its own continuation and is cut at the EOS token
+    dr = eng.draft_block(k, 0.0, 0).clone()
+    dr[0] = torch.tensor(truth[:k], dtype=torch.int32, device="cuda")
+    eng.verify_block(k, 0.0, dr)
+    acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
+    assert com[0] == truth[:3] and ncom[1] >= 1
+    live.draft_logits(k)                                  # the oracle's caches take the same rows as the engine's
+    live.verify_logits(dr[1].tolist())
+    live.commit(com[1])
+    len0 = int(eng.get_lengths()[0])
+    checked = 0
+    for it in range(4):
+        seed = 700 + it
+        eng.draft_block(k, T, seed)
+        rng = O.CounterRng(seed, 1)
+        j = len(live.prefix())
+        zd = live.draft_logits(k)
+        pert = [zd[i] / T + rng._gumbel(O.TAG_DRAFT, j + i, t.vocab) for i in range(k)]
+        y = [O.argmax_lowest(p) for p in pert]
+        eng.verify_block(k, T, torch.tensor([[0] * k, y], dtype=torch.int32, device="cuda"))
+        acc, com, ncom = eng.accept_and_commit(k, T, seed)
+        assert ncom[0] == 0 and com[0] == [] and int(eng.get_lengths()[0]) == len0
+        zt = live.verify_logits(y)
+        a, c = O.accept_block_sampling(O.log_softmax(zt / T), O.log_softmax(zd / T), y, rng, j)
+        want = y[:a] + ([] if c is None else [c])
+        if eos in want:
+            want = want[: want.index(eos) + 1]
+        if com[1] != want:
+            break           # a decision within rounding of a tie: the texts part here
+        live.commit(want)
+        checked += 1
+        if eos in want:
+            break
+    assert checked >= 2
+    eng.close()
+
+
 def test_sequence_runs_up_to_the_cache_capacity(weights):
     import torch
     from paper_2512_15176_amd import DeerError
