@@ -15,7 +15,8 @@
  *  - "dev" pointers are device (HBM) addresses on the context's device, "host" pointers are
  *    ordinary host memory.  The library NEVER allocates or frees device memory: the caller
  *    allocates the buffers whose sizes deer_query_sizes reports (e.g. as torch tensors), passes
- *    them to deer_init_models, and keeps them alive until deer_destroy.
+ *    them to deer_init_models, and keeps them alive until deer_destroy.  (Host side, a context
+ *    owns a few KB of page-locked memory through which deer_accept_and_commit's results arrive.)
  *  - All device work is enqueued on the hipStream_t given at init.  deer_draft_block and
  *    deer_verify_block return without waiting; deer_accept_and_commit and deer_prefill wait for
  *    the stream before they return (they hand results to the host).

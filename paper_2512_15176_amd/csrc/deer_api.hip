@@ -100,7 +100,9 @@ struct deer_ctx {
     int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
-    std::vector<char> h_ao;          // host staging of the acceptance results
+    std::vector<char> h_ao;          // host staging of the acceptance results (pageable; used only if pinning failed)
+    char *h_pin = nullptr;           // the same, page-locked: the copy lands without an intermediate staging copy
+    size_t h_pin_bytes = 0;
     std::string err;
     // persistent pass kernel
     int n_cus = 0;                   // compute units of the device
@@ -729,6 +731,12 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
         if (const char *e = getenv("DEER_GEMM_TILED_MIN")) c->tiled_min_tiles = std::max(0, atoi(e));
         (void)hipGetLastError();
     }
+    {   // a few KB of page-locked host memory for the acceptance results (host memory: the device buffers stay the caller's)
+        const size_t bytes = (size_t)((const char *)c->wk.ao.committed - (const char *)c->wk.ao.accept_len) + (size_t)p->max_batch * 32 * 4;
+        void *hp = nullptr;
+        if (hipHostMalloc(&hp, bytes, hipHostMallocDefault) == hipSuccess) { c->h_pin = (char *)hp; c->h_pin_bytes = bytes; }
+        else (void)hipGetLastError();
+    }
     *out = c;
     return DEER_OK;
 }
@@ -943,13 +951,14 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
         const char *d0 = (const char *)w.ao.accept_len;
         const size_t o_n = (const char *)w.ao.n_committed - d0, o_c = (const char *)w.ao.committed - d0;
         const size_t bytes = o_c + (size_t)B * cs * 4;
-        c->h_ao.resize(bytes);
-        HIPCHK(c, hipMemcpyAsync(c->h_ao.data(), d0, bytes, hipMemcpyDeviceToHost, c->stream));
+        char *host = c->h_pin;
+        if (!host || bytes > c->h_pin_bytes) { c->h_ao.resize(bytes); host = c->h_ao.data(); }
+        HIPCHK(c, hipMemcpyAsync(host, d0, bytes, hipMemcpyDeviceToHost, c->stream));
         if (int rc = pass_error_fetch(c)) return rc;
         HIPCHK(c, hipStreamSynchronize(c->stream));
-        memcpy(acc, c->h_ao.data(), (size_t)B * 4);
-        memcpy(ncom, c->h_ao.data() + o_n, (size_t)B * 4);
-        memcpy(committed, c->h_ao.data() + o_c, (size_t)B * cs * 4);
+        memcpy(acc, host, (size_t)B * 4);
+        memcpy(ncom, host + o_n, (size_t)B * 4);
+        memcpy(committed, host + o_c, (size_t)B * cs * 4);
     }
     if (int rc = pass_error_check(c)) return rc;
     for (int b = 0; b < B; ++b) {
@@ -972,6 +981,7 @@ int deer_destroy(deer_ctx *c) {
     if (!c) return DEER_EINVAL;
     (void)hipStreamSynchronize(c->stream);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    if (c->h_pin) (void)hipHostFree(c->h_pin);
     delete c;
     return DEER_OK;
 }
