@@ -326,7 +326,9 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     // (pairs stay); matrices above 40 MB (the 8B shape's QKV, gate/up and down) lose at any tile count.
     static const double mt1_bytes = getenv("DEER_MT1_BYTES") ? atof(getenv("DEER_MT1_BYTES")) : 4e7;
     static const int mt1_tiles = getenv("DEER_MT1_TILES") ? atoi(getenv("DEER_MT1_TILES")) : 16;
-    const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && (double)a.N * K * 2.0 <= mt1_bytes);
+    // (the 33.6 MB output projection of the 8B shape gains up to 8 tiles and loses at 16: matrix bytes x tiles is capped too)
+    const double w_bytes = (double)a.N * K * 2.0;
+    const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && w_bytes <= mt1_bytes && w_bytes * ntiles <= 7.0 * mt1_bytes);
     const int MT = pairs ? 2 : 1;
     const int zg = ntiles / MT;
     a.rows_total = ntiles * 32;
