@@ -1296,7 +1296,10 @@ struct AttnSmem {
     float2 ml[4 * 64];                       // parked (m, l) of the odd-parity waves
 };
 
-template <int HD>
+// FRAGS_EARLY (the attention kernel; the pass kernel has no registers to spare for it): all K fragments of a tile
+// are requested from LDS before the first product and the V fragments before the softmax, so the matrix pipe
+// does not wait for one LDS read per two products.
+template <int HD, bool FRAGS_EARLY = false>
 __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
                                           int max_seq, int b, int lim, float *part, int Hq, int Hkv, int NS,
@@ -1385,11 +1388,22 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
                     f32x16 sacc;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+                    uint4 kf[KSQ], vfr[HT * 2];
+                    if (FRAGS_EARLY) {
+#pragma unroll
+                        for (int s = 0; s < KSQ; ++s) kf[s] = fr[s * 64];
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
 #pragma unroll
                     for (int s = 0; s < KSQ; ++s) {
-                        const uint4 kf = fr[s * 64];
-                        sacc = mfma32(kf, qh[s], sacc);
-                        sacc = mfma32(kf, ql[s], sacc);
+                        if (!FRAGS_EARLY) kf[s] = fr[s * 64];
+                        sacc = mfma32(kf[s], qh[s], sacc);
+                        sacc = mfma32(kf[s], ql[s], sacc);
+                    }
+                    if (FRAGS_EARLY) {
+#pragma unroll
+                        for (int i = 0; i < HT * 2; ++i) vfr[i] = fr[(KSQ + i) * 64];
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                     // lane holds keys kt*32 + 16*half + r, r = 0..15, for query row qrow
                     const int key0 = kt * 32 + 16 * half;
@@ -1429,7 +1443,7 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
                     for (int tt = 0; tt < HT; ++tt)
 #pragma unroll
                         for (int s2 = 0; s2 < 2; ++s2) {
-                            const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
+                            const uint4 vf = FRAGS_EARLY ? vfr[tt * 2 + s2] : fr[(KSQ + tt * 2 + s2) * 64];
                             oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
                             if (ATT_P_LO) oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
                         }
@@ -1494,8 +1508,8 @@ __global__ __launch_bounds__(512) void k_attn(const uint4 *__restrict__ Qhi, con
                                               uint4 *__restrict__ xhi, uint4 *__restrict__ xlo) {
     __shared__ __attribute__((aligned(16))) AttnSmem as;
     const int t = blockIdx.y;
-    attn_item<HD>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, max_seq, tile_seq[t], row_limit[t * 32 + (threadIdx.x & 31)],
-                  part, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, blockIdx.x % Hkv, blockIdx.x / Hkv, t);
+    attn_item<HD, true>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, max_seq, tile_seq[t], row_limit[t * 32 + (threadIdx.x & 31)],
+                        part, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, blockIdx.x % Hkv, blockIdx.x / Hkv, t);
 }
 
 // Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
