@@ -22,6 +22,32 @@ static_assert(TG_NST >= 3 && TG_NST <= 6 && TG_KST * TG_NST <= 6, "stage buffers
 constexpr int TG_FRAGS = 24;    // fragments per k-step: 8 weight column tiles, 8 row tiles hi, 8 row tiles lo
 constexpr int TG_LPW = TG_KST * TG_FRAGS / 8;   // direct-to-LDS loads per wave and stage
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a register quad as the inline assembly sees it
+// LDS byte address of a __shared__ object
+__device__ __forceinline__ uint32_t lds_addr(const void *p) {
+    return (uint32_t)(size_t)(const void __attribute__((address_space(3))) *)p;
+}
+template <int OFF>
+__device__ __forceinline__ void lds_read16(u32x4 &v, uint32_t addr) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+}
+// one k-step's fragments of a wave: 4 weight column tiles, 2 row tiles (hi, lo)
+struct TiledFrags { u32x4 wf[4], xh[2], xl[2]; };
+// byte offsets inside a stage: fragment f of k-step kst at (kst * 24 + f) KB; sbw points at this wave's first weight
+// fragment, sbx at its first hi fragment (the lo fragments lie 8 KB further)
+template <int KOFF>
+__device__ __forceinline__ void tiled_read_frags(TiledFrags &f, uint32_t sbw, uint32_t sbx) {
+    lds_read16<KOFF + 0>(f.wf[0], sbw); lds_read16<KOFF + 1024>(f.wf[1], sbw);
+    lds_read16<KOFF + 2048>(f.wf[2], sbw); lds_read16<KOFF + 3072>(f.wf[3], sbw);
+    lds_read16<KOFF + 0>(f.xh[0], sbx); lds_read16<KOFF + 1024>(f.xh[1], sbx);
+    lds_read16<KOFF + 8192>(f.xl[0], sbx); lds_read16<KOFF + 9216>(f.xl[1], sbx);
+}
+// the fragments are valid after this point (they pass through the wait as operands, so no use can move above it)
+__device__ __forceinline__ void lds_wait8(TiledFrags &f) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f.wf[0]), "+v"(f.wf[1]), "+v"(f.wf[2]), "+v"(f.wf[3]), "+v"(f.xh[0]), "+v"(f.xh[1]), "+v"(f.xl[0]), "+v"(f.xl[1]));
+}
+
 struct TiledSmem {
     union {
         uint4 st[TG_NST][TG_KST * TG_FRAGS * 64];                       // 3 x 48 KB
@@ -114,24 +140,30 @@ __global__ __launch_bounds__(512) void k_gemm_tiled(const GemmArgs a, int ncg, i
         }
         barrier_keep_loads();   // all waves' shares are in LDS, and stage it - 1 has been read by all
         if (it + TG_NST - 1 < nst) stage((it + TG_NST - 1) % TG_NST, it + TG_NST - 1);
-        const uint4 *sb = sm.st[it % TG_NST] + lane;
+        // The fragments are read with LDS instructions the compiler does not see as such: before a read of memory
+        // that direct-to-LDS loads may write it waits for ALL loads in flight (vmcnt(0)), the stages requested
+        // ahead included, and the ring would never be more than one stage deep.  The counted wait and the
+        // barrier above are what orders these reads after the loads of their own stage.
+        const uint32_t sb = lds_addr(sm.st[it % TG_NST]) + lane * 16;
+        const uint32_t sbw = sb + wc * 4096, sbx = sb + 8192 + wr * 2048;
+        TiledFrags fa, fb;
+        tiled_read_frags<0>(fa, sbw, sbx);
+        lds_wait8(fa);
 #pragma unroll
         for (int kst = 0; kst < TG_KST; ++kst) {
-            uint4 wf[4], xh[2], xl[2];
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wf[nb] = sb[(kst * TG_FRAGS + wc * 4 + nb) * 64];
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                xh[mt] = sb[(kst * TG_FRAGS + 8 + wr * 2 + mt) * 64];
-                xl[mt] = sb[(kst * TG_FRAGS + 16 + wr * 2 + mt) * 64];
+            TiledFrags &cur = (kst & 1) ? fb : fa, &nxt = (kst & 1) ? fa : fb;
+            if (kst + 1 < TG_KST) {
+                if (kst == 0) tiled_read_frags<1 * TG_FRAGS * 1024>(nxt, sbw, sbx);
+                else if (kst == 1) tiled_read_frags<2 * TG_FRAGS * 1024>(nxt, sbw, sbx);
             }
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                 for (int nb = 0; nb < 4; ++nb) {
-                    acc[mt][nb] = mfma32(xh[mt], wf[nb], acc[mt][nb]);
-                    acc[mt][nb] = mfma32(xl[mt], wf[nb], acc[mt][nb]);
+                    acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, cur.xh[mt]), __builtin_bit_cast(uint4, cur.wf[nb]), acc[mt][nb]);
+                    acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, cur.xl[mt]), __builtin_bit_cast(uint4, cur.wf[nb]), acc[mt][nb]);
                 }
+            if (kst + 1 < TG_KST) lds_wait8(nxt);
         }
     }
     __syncthreads();   // the stage buffers have been read: the epilogue staging below reuses them
