@@ -117,8 +117,9 @@ __global__ __launch_bounds__(512) void k_gemm_tiled(const GemmArgs a, int ncg, i
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nb][r] = 0.f;
 
+    static_assert(TG_KST == 2 && TG_NST == 3, "the loop below is written for two k-steps per stage and three buffers");
 #pragma unroll
-    for (int i = 0; i < TG_NST - 1; ++i)
+    for (int i = 0; i < TG_NST; ++i)
         if (i < nst) stage(i, i);
     // RMSNorm factors of the workgroup's rows (their sums of squares were finished by the previous kernel)
     if (EPI != EPI_RESID) {
@@ -129,42 +130,49 @@ __global__ __launch_bounds__(512) void k_gemm_tiled(const GemmArgs a, int ncg, i
         }
     }
 
-    for (int it = 0; it < nst; ++it) {
-        // stage `it` has landed once at most the loads of the stages requested after it are outstanding
-        switch (min(TG_NST - 2, nst - 1 - it)) {
-            case 0: wait_loads<0>(); break;
-            case 1: wait_loads<TG_LPW>(); break;
-            case 2: wait_loads<2 * TG_LPW>(); break;
-            case 3: wait_loads<3 * TG_LPW>(); break;
-            default: wait_loads<4 * TG_LPW>(); break;
-        }
-        barrier_keep_loads();   // all waves' shares are in LDS, and stage it - 1 has been read by all
-        if (it + TG_NST - 1 < nst) stage((it + TG_NST - 1) % TG_NST, it + TG_NST - 1);
-        // The fragments are read with LDS instructions the compiler does not see as such: before a read of memory
-        // that direct-to-LDS loads may write it waits for ALL loads in flight (vmcnt(0)), the stages requested
-        // ahead included, and the ring would never be more than one stage deep.  The counted wait and the
-        // barrier above are what orders these reads after the loads of their own stage.
-        const uint32_t sb = lds_addr(sm.st[it % TG_NST]) + lane * 16;
-        const uint32_t sbw = sb + wc * 4096, sbx = sb + 8192 + wr * 2048;
-        TiledFrags fa, fb;
-        tiled_read_frags<0>(fa, sbw, sbx);
-        lds_wait8(fa);
+    // The fragments are read with LDS instructions the compiler does not see as such: before a read of memory
+    // that direct-to-LDS loads may write it waits for ALL loads in flight (vmcnt(0)), the stages requested
+    // ahead included, and the ring would never be more than one stage deep.  The counted waits and the
+    // barriers below are what orders these reads after the loads of their own stage.
+    // Schedule of stage `it` (steady state; two stages are on their way all the time):
+    //   read k-step 1 | multiply k-step 0 | wait: stage it+1 has landed | barrier: everybody has read stage it |
+    //   request stage it+3 into the buffer of stage it | read k-step 0 of stage it+1 | multiply k-step 1
+    // so the LDS reads of a k-step always run under the products of the one before, also across the barrier.
+    const uint32_t lane16 = lane * 16, wofs = wc * 4096, xofs = 8192 + wr * 2048;
+    auto mul16 = [&](const TiledFrags &f) {
 #pragma unroll
-        for (int kst = 0; kst < TG_KST; ++kst) {
-            TiledFrags &cur = (kst & 1) ? fb : fa, &nxt = (kst & 1) ? fa : fb;
-            if (kst + 1 < TG_KST) {
-                if (kst == 0) tiled_read_frags<1 * TG_FRAGS * 1024>(nxt, sbw, sbx);
-                else if (kst == 1) tiled_read_frags<2 * TG_FRAGS * 1024>(nxt, sbw, sbx);
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, f.xh[mt]), __builtin_bit_cast(uint4, f.wf[nb]), acc[mt][nb]);
+                acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, f.xl[mt]), __builtin_bit_cast(uint4, f.wf[nb]), acc[mt][nb]);
             }
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
-                    acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, cur.xh[mt]), __builtin_bit_cast(uint4, cur.wf[nb]), acc[mt][nb]);
-                    acc[mt][nb] = mfma32(__builtin_bit_cast(uint4, cur.xl[mt]), __builtin_bit_cast(uint4, cur.wf[nb]), acc[mt][nb]);
-                }
-            if (kst + 1 < TG_KST) lds_wait8(nxt);
+    };
+    TiledFrags fa, fb;
+    if (nst > 2) wait_loads<2 * TG_LPW>(); else if (nst > 1) wait_loads<TG_LPW>(); else wait_loads<0>();
+    barrier_keep_loads();   // stage 0 is in LDS
+    {
+        const uint32_t sb = lds_addr(sm.st[0]) + lane16;
+        tiled_read_frags<0>(fa, sb + wofs, sb + xofs);
+        lds_wait8(fa);
+    }
+    for (int it = 0; it < nst; ++it) {
+        const uint32_t sb = lds_addr(sm.st[it % TG_NST]) + lane16;
+        tiled_read_frags<TG_FRAGS * 1024>(fb, sb + wofs, sb + xofs);
+        mul16(fa);
+        __builtin_amdgcn_sched_barrier(0);   // the products are queued before the wave waits for its next fragments
+        lds_wait8(fb);
+        const bool more = it + 1 < nst;
+        if (more) {
+            if (it + 2 < nst) wait_loads<TG_LPW>(); else wait_loads<0>();   // stage it+1 has landed (it+2 may be on its way)
+            barrier_keep_loads();   // everybody's share of stage it+1 is in LDS, and everybody has read stage it
+            if (it + TG_NST < nst) stage(it % TG_NST, it + TG_NST);
+            const uint32_t sn = lds_addr(sm.st[(it + 1) % TG_NST]) + lane16;
+            tiled_read_frags<0>(fa, sn + wofs, sn + xofs);
         }
+        mul16(fb);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) lds_wait8(fa);
     }
     __syncthreads();   // the stage buffers have been read: the epilogue staging below reuses them
 
