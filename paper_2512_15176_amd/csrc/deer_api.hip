@@ -336,8 +336,10 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
         const int ncg = a.N / CG;
         const int tiles = ((ntiles + TG_RT - 1) / TG_RT) * ((ncg + 1) / 2);
         // measured: at 512 and 1024 rows (two and four row blocks) the streaming kernel with shared L2 lines is still
-        // ahead (config-5 verify 42.8 against 48.5 ms); from 2048 rows on the blocked kernel wins (prefill 133 against 167 ms)
-        const int min_rows_tiles = c->tiled_min_tiles >= 128 ? 64 : TG_RT;   // tests lower both thresholds
+        // ahead (config-5 verify 41.9 against 47.7 ms); from 1024 rows on the blocked kernel wins where it has 128 tiles
+        // (prefill 133 against 167 ms; two 512-token sequences recomputed per iteration 44.3 against 46.8 ms)
+        static const int rows_tiles = getenv("DEER_GEMM_TILED_ROWS") ? atoi(getenv("DEER_GEMM_TILED_ROWS")) : 32;
+        const int min_rows_tiles = c->tiled_min_tiles >= 128 ? rows_tiles : TG_RT;   // tests lower both thresholds
         if (c->tiled_min_tiles > 0 && EPI != EPI_ROUTER && ntiles >= min_rows_tiles && a.KS % TG_KST == 0 && tiles >= c->tiled_min_tiles) {
             a.S = 1; a.part = nullptr; a.counters = nullptr;
             ProfScope ps(c, 0, (double)a.N * K * 2.0);
