@@ -9,7 +9,7 @@ Everything is resident in HBM before the timed region starts.
 Because random-init weights accept (almost) nothing at T=0, committed tokens/s is reported under a
 stated accepted-length law: truncated geometric on a in {0..k} with mean k/4 (= `value`) and 3k/4.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the fields are described in the README).
 """
 from __future__ import annotations
 

@@ -490,7 +490,7 @@ __global__ __launch_bounds__(512) void k_pass(const PassArgs p) {
 
 
     // Placement check: the in-XCD exchange needs workgroup b on XCD b % 8, eight XCDs with equally many
-    // workgroups.  Every workgroup compares its XCC id; one barrier later all of them know the verdict.
+    // workgroups.  Every workgroup compares its XCC id; one barrier later all of them know the outcome.
     bool near = false;
     const int nb = opaque_s(p.nb);
     if (p.allow_near && (nb & 7) == 0) {
