@@ -323,12 +323,14 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     // then every tile gets workgroups of its own, which find the weights in their XCD's L2, and the workgroup that
     // finishes a column group runs one epilogue instead of two in a row.  Measured on MI355X: the 0.5B drafter's
     // pass over two row tiles 2.26 -> 1.71 ms, over 16 tiles (batch 8) 3.73 -> 3.39 ms, over 32 tiles 5.56 -> 5.80 ms
-    // (pairs stay); matrices above 40 MB (the 8B shape's QKV, gate/up and down) lose at any tile count.
-    static const double mt1_bytes = getenv("DEER_MT1_BYTES") ? atof(getenv("DEER_MT1_BYTES")) : 4e7;
+    // (pairs stay); of the 8B shape's matrices the 33.6 MB output projection gains up to 8 tiles and the 50.3 MB QKV
+    // projection up to 4 (batch 2 verify 5.99 -> 5.82 ms), gate/up and down lose at any tile count.
+    static const double mt1_bytes = getenv("DEER_MT1_BYTES") ? atof(getenv("DEER_MT1_BYTES")) : 5.1e7;
+    static const double mt1_product = getenv("DEER_MT1_PRODUCT") ? atof(getenv("DEER_MT1_PRODUCT")) : 2.8e8;
     static const int mt1_tiles = getenv("DEER_MT1_TILES") ? atoi(getenv("DEER_MT1_TILES")) : 16;
-    // (the 33.6 MB output projection of the 8B shape gains up to 8 tiles and loses at 16: matrix bytes x tiles is capped too)
+    // (matrix bytes x tiles is capped too: the output projection loses at 16 tiles)
     const double w_bytes = (double)a.N * K * 2.0;
-    const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && w_bytes <= mt1_bytes && w_bytes * ntiles <= 7.0 * mt1_bytes);
+    const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && w_bytes <= mt1_bytes && w_bytes * ntiles <= mt1_product);
     const int MT = pairs ? 2 : 1;
     const int zg = ntiles / MT;
     a.rows_total = ntiles * 32;
