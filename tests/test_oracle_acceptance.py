@@ -120,6 +120,29 @@ def test_alpha_identities():
 # ----------------------------------------------------------------------------------------------
 # sequence level: first-order tabular target, per-position tabular drafter
 # ----------------------------------------------------------------------------------------------
+def test_empty_residual_falls_back_to_the_target_law():
+    """gamma = 1 (p <= q everywhere): the residual of Eq. "resample" is empty and the Appendix leaves the draw free; the
+    oracle draws from p.  With p = q the branch is unreachable (alpha = 1, every draft accepted, any uniforms); it is
+    reached here with an un-normalised q = e^c p > p, where rejections do occur."""
+    rng0 = np.random.default_rng(3)
+    V, k = 7, 3
+    logp = O.log_softmax(rng0.normal(size=(k, V)))
+    assert np.array_equal(O.residual_logweights(logp[0], logp[0]), logp[0])
+    assert np.allclose(O.residual_distribution(logp[0], logp[0]), np.exp(logp[0]), atol=1e-15)
+    for seed in range(50):      # p = q: nothing is ever rejected
+        a, c = O.accept_block_sampling(logp, logp, [1, 2, 3], O.CounterRng(seed), 10)
+        assert (a, c) == (k, None)
+    logq = logp + 0.7           # p < q everywhere: alpha = e^-0.7 and an empty residual
+    rejected = 0
+    for seed in range(200):
+        rng = O.CounterRng(seed)
+        a, c = O.accept_block_sampling(logp, logq, [1, 2, 3], rng, 10)
+        if a < k:
+            rejected += 1
+            assert c == O.CounterRng(seed).categorical(logp[a], 10 + a, O.TAG_RESID)   # a draw from p at the rejected position
+    assert rejected > 100
+
+
 def _tables(V, k, seed):
     g = np.random.default_rng(seed)
     P = g.dirichlet(np.ones(V), size=V)            # p(x_t | x_{t-1})

@@ -155,32 +155,59 @@ def test_forward_invariant_under_constant_position_shift():
     assert np.allclose(z0, z1, atol=1e-9)
 
 
-def _pair(tiny, tiny_weights, cap=160):
+def _pair(tiny, tiny_weights, cap=160, kv_storage=None):
     wt, wd = tiny_weights
-    return O.TransformerPair(O.Decoder(tiny["target"], wt), O.Decoder(tiny["drafter"], wd),
+    return O.TransformerPair(O.Decoder(tiny["target"], wt, kv_storage=kv_storage), O.Decoder(tiny["drafter"], wd, kv_storage=kv_storage),
                              di.mask_token_id(tiny["target"].vocab), cap)
 
 
-def test_k1_verify_is_an_ordinary_ar_step(tiny, tiny_weights):
+# The three properties below hold for a cache kept in the compute precision and, unchanged, for a cache that stores
+# bf16 rows - provided a pass rounds its new K,V rows BEFORE it attends to them, so that a row is seen with the same
+# value by its own pass and by every later one (rounding only at the cache write would break the block-verify and
+# k = 1 identities: the in-pass rows would be unrounded, the cached ones rounded).
+KV_STORAGES = [None, "bf16"]
+
+
+def _is_bf16(x):
+    return np.array_equal(O.round_to_bf16(x), x)
+
+
+@pytest.mark.parametrize("kv_storage", KV_STORAGES)
+def test_k1_verify_is_an_ordinary_ar_step(tiny, tiny_weights, kv_storage):
     prompt = di.prompt_ids(tiny["target"].vocab, 20)
-    pair = _pair(tiny, tiny_weights)
+    pair = _pair(tiny, tiny_weights, kv_storage=kv_storage)
     pair.prefill(prompt)
     z = pair.verify_logits([5])          # k = 1: the single row is the pending token x_j
-    dec = O.Decoder(tiny["target"], tiny_weights[0])
+    dec = O.Decoder(tiny["target"], tiny_weights[0], kv_storage=kv_storage)
     cache = O.KVCache(tiny["target"], 32, np.float64)
     ref = dec.forward(prompt, np.arange(20), cache, O.causal_mask(20), 20)   # plain full causal pass
     assert np.allclose(z[0], ref[-1], atol=1e-12)
     assert np.allclose(pair.tc.K[:, :20], cache.K[:, :20], atol=1e-13)
     assert np.allclose(pair.tc.V[:, :20], cache.V[:, :20], atol=1e-13)
+    assert _is_bf16(pair.tc.K[:, :20]) == (kv_storage == "bf16") and _is_bf16(pair.tc.V[:, :20]) == (kv_storage == "bf16")
 
 
-def test_block_verify_equals_sequential_steps(tiny, tiny_weights):
+def test_bf16_cache_storage_changes_the_logits_measurably(tiny, tiny_weights):
+    """The storage branch is not a no-op: the same pass with rounded rows differs from the unrounded one by about
+    the rounding step of the rows (2^-9 relative), far above the 1e-12 of the identities above."""
+    prompt = di.prompt_ids(tiny["target"].vocab, 20)
+    zs = []
+    for kv_storage in KV_STORAGES:
+        pair = _pair(tiny, tiny_weights, kv_storage=kv_storage)
+        pair.prefill(prompt)
+        zs.append(pair.verify_logits([5, 6, 7]))
+    diff = np.abs(zs[0] - zs[1]).max()
+    assert 1e-7 < diff < 1e-2
+
+
+@pytest.mark.parametrize("kv_storage", KV_STORAGES)
+def test_block_verify_equals_sequential_steps(tiny, tiny_weights, kv_storage):
     prompt = di.prompt_ids(tiny["target"].vocab, 24)
     yhat = [int(t) for t in di.prompt_ids(tiny["target"].vocab, 8, seq=9)]
-    pair = _pair(tiny, tiny_weights)
+    pair = _pair(tiny, tiny_weights, kv_storage=kv_storage)
     pair.prefill(prompt)
     zb = pair.verify_logits(yhat)
-    dec = O.Decoder(tiny["target"], tiny_weights[0])
+    dec = O.Decoder(tiny["target"], tiny_weights[0], kv_storage=kv_storage)
     cache = O.KVCache(tiny["target"], 64, np.float64)
     dec.forward(prompt[:-1], np.arange(23), cache, O.causal_mask(23), 23, logits_rows=[])
     rows = [int(prompt[-1])] + yhat[:-1]
@@ -189,13 +216,41 @@ def test_block_verify_equals_sequential_steps(tiny, tiny_weights):
         assert np.allclose(zb[i], zi, atol=1e-12)
 
 
-def test_state_after_ragged_commits_equals_fresh_prefill(tiny, tiny_weights):
+class _RoundsAtCacheWriteOnly(O.Decoder):
+    """A planted mistake: rows are stored as bf16 but the pass that produces them attends to the unrounded values."""
+
+    def forward(self, ids, pos, cache, allowed_new, keep, logits_rows=None):
+        n_old = cache.n
+        z = super().forward(ids, pos, cache, allowed_new, keep, logits_rows)
+        cache.K[:, n_old:cache.n] = O.round_to_bf16(cache.K[:, n_old:cache.n])
+        cache.V[:, n_old:cache.n] = O.round_to_bf16(cache.V[:, n_old:cache.n])
+        return z
+
+
+def test_block_verify_identity_rejects_rounding_at_cache_write_only(tiny, tiny_weights):
+    prompt = di.prompt_ids(tiny["target"].vocab, 24)
+    yhat = [int(t) for t in di.prompt_ids(tiny["target"].vocab, 8, seq=9)]
+    dec = _RoundsAtCacheWriteOnly(tiny["target"], tiny_weights[0])
+    block_cache, step_cache = O.KVCache(tiny["target"], 64, np.float64), O.KVCache(tiny["target"], 64, np.float64)
+    for c in (block_cache, step_cache):
+        dec.forward(prompt[:-1], np.arange(23), c, O.causal_mask(23), 23, logits_rows=[])
+    rows = [int(prompt[-1])] + yhat[:-1]
+    zb = dec.forward(rows, np.arange(23, 31), block_cache, O.causal_mask(8), 8)
+    worst = 0.0
+    for i, t in enumerate(rows):
+        zi = dec.forward([t], [23 + i], step_cache, O.causal_mask(1), 1)[0]
+        worst = max(worst, float(np.abs(zb[i] - zi).max()))
+    assert worst > 1e-7      # one k-row pass is no longer k single steps
+
+
+@pytest.mark.parametrize("kv_storage", KV_STORAGES)
+def test_state_after_ragged_commits_equals_fresh_prefill(tiny, tiny_weights, kv_storage):
     V = tiny["target"].vocab
     prompt = di.prompt_ids(V, 16)
-    pair = _pair(tiny, tiny_weights)
+    pair = _pair(tiny, tiny_weights, kv_storage=kv_storage)
     pair.prefill(prompt)
     rng = O.CounterRng(4)
-    dec_t = O.Decoder(tiny["target"], tiny_weights[0])
+    dec_t = O.Decoder(tiny["target"], tiny_weights[0], kv_storage=kv_storage)
     forced = [0, 3, 8, 1, 5]             # accepted lengths to force at T=0 via injected drafts
     for it, a_want in enumerate(forced):
         truth = O.ar_decode(dec_t, pair.prefix(), 8)        # the target's own greedy continuation
@@ -205,7 +260,7 @@ def test_state_after_ragged_commits_equals_fresh_prefill(tiny, tiny_weights):
         res = O.deer_iteration(pair, 8, 0.0, rng, draft_override=block)
         assert res["accept_len"] == a_want
         assert res["committed"] == truth[: min(a_want + 1, 8)]
-    fresh = _pair(tiny, tiny_weights)
+    fresh = _pair(tiny, tiny_weights, kv_storage=kv_storage)
     fresh.prefill(pair.prefix())
     n = len(pair.prefix())
     assert pair.tc.n == fresh.tc.n == n - 1

@@ -124,6 +124,50 @@ def test_mix64_known_values():
         assert int(O.mix64(np.uint64(state))) == w
 
 
+def _published_splitmix64():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "splitmix64_seed0.txt")
+    return [int(l, 16) for l in open(path) if l.strip() and not l.startswith("#")]
+
+
+def test_uniforms_of_key_zero_are_the_published_splitmix64_stream():
+    # uniforms(key, idx) takes the top 23 bits of finaliser(key + (idx + 1) * golden): with key 0 that is output
+    # idx of the published seed-0 stream, so index offset, increment and bit selection are pinned from outside
+    want = _published_splitmix64()
+    u = O.uniforms(0, np.arange(len(want)))
+    for i, w in enumerate(want):
+        assert u[i] == ((w >> 41) + 0.5) / 2 ** 23
+
+
+def test_row_key_of_seed_zero_starts_from_the_published_stream():
+    # row_key(seed, tag, seq, pos) = finaliser(finaliser(seed + golden * tag) xor ((seq << 40) + pos)): with seed 0 the
+    # inner value is output tag - 1 of the published stream; the outer step is done here with Python integers
+    M = (1 << 64) - 1
+
+    def fin(z):
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
+        return z ^ (z >> 31)
+
+    want = _published_splitmix64()
+    for tag in (1, 2, 3):
+        assert int(O.row_key(0, tag, 0, 0)) == fin(want[tag - 1])
+        assert int(O.row_key(0, tag, 5, 77)) == fin(want[tag - 1] ^ ((5 << 40) + 77))
+
+
+def test_counter_rng_golden_values():
+    """Keys and 23-bit draws at stored points (tests/golden/counter_rng_golden.txt, written by the script beside it
+    from the oracle alone): a changed shift, constant, tag or index offset fails here."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "counter_rng_golden.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 8
+    for seed, tag, seq, pos, idx, key_hex, r in rows:
+        key = O.row_key(int(seed), int(tag), int(seq), int(pos))
+        assert int(key) == int(key_hex, 16)
+        assert float(O.uniforms(key, int(idx))) == (int(r) + 0.5) / 2 ** 23
+
+
 def test_gumbel_max_samples_the_categorical():
     from scipy.stats import chisquare
     w = np.array([0.5, 0.0, 0.2, 0.25, 0.05])
