@@ -29,13 +29,23 @@ import deer_inputs as di  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 
 
-# HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain copy of known size gives), qwen3_8b verify pass:
-#  - k_gemm (one kernel per operation, 145 launches per pass): 113.7 MB read + 3.6 MB written per launch on
-#    average (104.4 MB algorithmic);
-#  - k_pass (the persistent kernel, DEER_PERSISTENT=1): 18.51 GB read + 1.61 GB written per launch
-#    (15.77 GB algorithmic).
-MEASURED_TRAFFIC = {("qwen3_8b", "k_gemm"): 113.7e6 + 3.6e6, ("qwen3_8b", "k_pass"): 18.51e9 + 1.61e9}
+def measured_traffic(config):
+    """HBM bytes per launch of the dominant kernel and its mean duration in a kernel trace, as recorded in
+    profiles/<config>_k_gemm_hbm_traffic.txt when the rocprofv3 counter and trace summaries were last refreshed
+    (`key = value` lines; the file names the commit and the commands).  None if there is no such record."""
+    path = os.path.join(ROOT, "profiles", f"verify_{config}_k_gemm_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    rec = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            key, val = [x.strip() for x in line.split("=", 1)]
+            try:
+                rec[key] = float(val)
+            except ValueError:
+                rec[key] = val
+    return rec
 
 
 def trunc_geom(k, mean):
@@ -95,13 +105,12 @@ def fill_random_caches(eng, shape_by_model, lens):
     g = torch.Generator(device="cuda")
     g.manual_seed(di.KV_SEED)
     for model, shape in shape_by_model.items():
-        views = eng.kv_views(model, shape)
         H, hd = shape.n_kv_heads, shape.head_dim
         for l in range(shape.n_layers):
             for b, n in enumerate(lens):
                 kr = torch.randn(n, H, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
                 vr = torch.randn(n, H, hd, generator=g, device="cuda").to(torch.bfloat16).view(torch.int16)
-                eng.write_kv_rows(views, l, b, kr, vr)
+                eng.debug_load_kv(model, l, b, 0, kr, vr)
 
 
 def cpu_baseline(cfg, k, prefix, e_ncommit, batch=1):
@@ -469,8 +478,8 @@ def main():
     # per-launch timing of the dominant kernel (weight-streaming GEMM) inside verify passes
     eng.debug_profile(True)
     n_prof = 3
-    g_ms = g_bytes = a_ms = a_bytes = p_ms = p_bytes = 0.0
-    g_n = a_n = p_n = 0
+    g_ms = g_bytes = a_ms = a_bytes = 0.0
+    g_n = a_n = 0
     streamed = 0
     for _ in range(n_prof):
         dr = eng.draft_block(k, T, di.SAMPLING_SEED)
@@ -479,8 +488,7 @@ def main():
         eng.debug_experts_streamed()
         eng.verify_block(k, T, dr if inject is None else inject)
         streamed += eng.debug_experts_streamed()
-        r0, r1, r2 = eng.debug_profile_read(0), eng.debug_profile_read(1), eng.debug_profile_read(2)
-        p_ms, p_n, p_bytes = p_ms + r2[0], p_n + r2[1], p_bytes + r2[2]
+        r0, r1 = eng.debug_profile_read(0), eng.debug_profile_read(1)
         g_ms, g_n, g_bytes = g_ms + r0[0], g_n + r0[1], g_bytes + r0[2]
         a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
         _, com, _ = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
@@ -495,14 +503,9 @@ def main():
     rho8, en8 = trunc_geom(k, k / 4)
     rho24, en24 = trunc_geom(k, 3 * k / 4)
     iter_ms = td + tv + ta
-    traffic = None
-    if p_n:   # the verify pass ran as one persistent kernel: that kernel is the dominant one
-        traffic = MEASURED_TRAFFIC.get((args.config, "k_pass"))
-        g_ms, g_n, g_bytes = p_ms, p_n, p_bytes
-        gemm_label = "k_pass (persistent verify pass: all layers' GEMMs, block attention, LM head)"
-    else:
-        gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
-        traffic = MEASURED_TRAFFIC.get((args.config, "k_gemm"))
+    gemm_label = "k_gemm (weight-streaming GEMM, verify pass)"
+    rec = measured_traffic(args.config)
+    traffic = (rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]) if rec else None
     gemm_gbs = g_bytes / max(g_ms * 1e-3, 1e-12) / 1e9
     if t.n_experts:   # grouped expert GEMMs touch a data-dependent set of experts: use the pass-level figure
         gemm_gbs = (wbytes + kvbytes) / (tv * 1e-3) / 1e9
@@ -526,7 +529,12 @@ def main():
         "roofline": {"bound": "hbm", "kernel": gemm_label, "achieved": gemm_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "launches": int(g_n), "avg_launch_us": g_ms / max(g_n, 1) * 1e3,
-                     "bytes_per_launch": g_bytes / max(g_n, 1)},
+                     "bytes_per_launch": g_bytes / max(g_n, 1),
+                     # the same fraction from the kernel durations of the rocprofv3 trace summarised under profiles/
+                     # (HIP-event brackets around single launches read a few microseconds long)
+                     "frac_from_kernel_trace": (rec["algorithmic_bytes_per_launch"] / (rec["trace_avg_launch_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
+                     if rec and rec.get("trace_avg_launch_us") else None,
+                     "traffic_record": (rec.get("commit") if rec else None)},
         "attention_kernel": {"launches": int(a_n), "avg_launch_us": a_ms / max(a_n, 1) * 1e3,
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }

@@ -181,28 +181,27 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_f
 
 /* Per-launch timing for the benchmark.  While enabled, every launch of the weight-streaming GEMM
  * (kernel_class 0) and of the block-attention kernel (kernel_class 1) is bracketed by HIP events
- * on the context's stream, and so is every launch of the persistent pass kernel (kernel_class 2),
- * which runs a whole pass of a dense model at batch 1.  deer_debug_profile(c, mode) waits for the
- * stream, switches recording (0 off, 1 on, 2 on with every pass run as separate kernels whatever
- * the launch mode, so that classes 0 and 1 are populated) and forgets earlier records; deer_debug_profile_read waits for the
- * stream and returns, for one class, the summed event time (ms), the number of launches, and their
- * algorithmic bytes (weight bytes of each GEMM; K and V rows visible to each attention launch; both,
- * over all layers and the LM head, for a pass kernel). */
+ * on the context's stream.  deer_debug_profile(c, on) waits for the stream, switches recording and forgets earlier
+ * records; deer_debug_profile_read waits for the stream and returns, for one class, the summed event
+ * time (ms), the number of launches, and their algorithmic bytes (weight bytes of each GEMM; K and V
+ * rows visible to each attention launch). */
 int deer_debug_profile(deer_ctx *c, int enable);
 int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes);
 
-/* How a forward pass is launched: 0 = one kernel per operation (the default), 1 = one persistent kernel per
- * pass wherever it applies (dense model, batch 1).  The environment variable DEER_PERSISTENT sets the initial
- * value.  Both modes compute the same pass with the same device functions; tests compare them.  Waits for
- * the stream. */
-int deer_debug_pass_mode(deer_ctx *c, int mode);
+/* Lock-step aid for parity tests: stands in for deer_accept_and_commit after deer_verify_block and
+ * commits, per sequence b, the n_host[b] tokens tokens_host[b * stride ..] (0 <= n_host[b] <= k, or
+ * k + 1 with the bonus token; stride <= 32) instead of the acceptance rule's choice.  The caller keeps
+ * the cache consistent: all but the last of a sequence's tokens must be the drafts that the verify
+ * pass was given at those positions (their K,V rows are already cached), as is the case for the commit
+ * of an oracle that judged the same block.  Waits for the stream. */
+int deer_debug_force_commit(deer_ctx *c, const int32_t *tokens_host, const int32_t *n_host, int32_t stride);
 
-/* Timeline of the persistent pass kernel (dense models at batch 1 run a whole pass as one kernel).
- * Waits for the stream; if stamps_host is not NULL copies the stamps of the last recorded pass into it
- * ([*blocks][*stamps_per_block] ticks of the 100 MHz device clock, two per phase of the pass: input ready,
- * own work stored; 0 = not reached); then switches recording for the following passes on or off.
- * Pass stamps_host = NULL first to learn the two sizes. */
-int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block);
+/* Injected cache contents (where running a real prefill is too costly): writes canonical rows
+ * k_rows_dev, v_rows_dev ([n_slots][n_kv_heads][head_dim] bf16, device memory) into cache slots
+ * first_slot .. first_slot + n_slots - 1 of sequence `seq`, layer `layer` of `model`, in the
+ * library's cache layout.  Enqueued on the stream; follow with deer_set_prefilled. */
+int deer_debug_load_kv(deer_ctx *c, int model, int32_t layer, int32_t seq, int32_t first_slot, int32_t n_slots,
+                       const void *k_rows_dev, const void *v_rows_dev);
 
 /* Benchmarking aid for random-init mixture models, whose router sends every row of a block to the same few
  * experts: when enabled, each row is routed to top_k distinct pseudo-random experts (a function of layer and
@@ -217,12 +216,13 @@ int deer_debug_route_spread(deer_ctx *c, int enable);
 int deer_debug_experts_streamed(deer_ctx *c, int64_t *pairs);
 
 /* Debugging aid: where a weight-streaming GEMM launch spends its time.  Copies the stamps recorded so far
- * (*blocks workgroups x 8 ticks of the 100 MHz device clock: 0 workgroup started, 1 its first wave has
- * multiplied its K slice, 2 its tile is stored (after the epilogue if the matrix is not split), 3 it has
- * arrived at the column group's counter, 4 it was the last to arrive and has finished the group; 0 = not
- * reached) into stamps_host (at most max_blocks workgroups), then selects the launch that records from now on:
- * the `launch`-th streaming GEMM (counted from 0) of every following pass of `model`; launch < 0 switches
- * recording off.  Waits for the stream.  Only the per-operation launch mode records. */
+ * (2 x 2048 workgroup rows x 8 ticks of the 100 MHz device clock: the first 2048 rows belong to the chosen launch,
+ * the second 2048 to the streaming GEMM launched after it, so that the hand-over between two kernels can be seen;
+ * per row: 0 workgroup started, 1 its first wave has multiplied its K slice, 2 its tile is stored (after the
+ * epilogue if the matrix is not split), 3 it has arrived at the column group's counter, 4 it was the last to arrive
+ * and has finished the group; 0 = not reached or no such workgroup) into stamps_host (at most max_blocks rows; *blocks = rows available, 0 if nothing was recorded), then
+ * selects the launch that records from now on: the `launch`-th streaming GEMM (counted from 0) of every following
+ * pass of `model`; launch < 0 switches recording off.  Waits for the stream. */
 int deer_debug_gemm_stamps(deer_ctx *c, int model, int launch, uint64_t *stamps_host, int32_t max_blocks, int32_t *blocks);
 
 /* GEMMs of passes with at least 256 rows run blocked for the matrix cores (256 x 256 tiles through LDS)

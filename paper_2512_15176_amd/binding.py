@@ -17,7 +17,7 @@ STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACIT
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
            "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
-           "deer_debug_profile_read", "deer_debug_pass_timeline", "deer_debug_pass_mode", "deer_set_bonus_token",
+           "deer_debug_profile_read", "deer_debug_force_commit", "deer_debug_load_kv", "deer_set_bonus_token",
            "deer_draft_block_multipass", "deer_debug_gemm_tiled",
            "deer_debug_gemm_stamps", "deer_debug_experts_streamed", "deer_debug_route_spread"]
 
@@ -86,6 +86,9 @@ def load_library(path: str = LIB_PATH):
     lib.deer_get_lengths.argtypes = [C.c_void_p, C.c_void_p]
     lib.deer_get_kv_layout.argtypes = [C.c_void_p, C.c_int, C.POINTER(KvLayout)]
     lib.deer_debug_profile.argtypes = [C.c_void_p, C.c_int]
+    lib.deer_debug_force_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    lib.deer_debug_load_kv.argtypes = [C.c_void_p, C.c_int, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.deer_debug_gemm_tiled.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_profile_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_double)]
     _lib = lib
     return lib
@@ -141,7 +144,6 @@ class DeerEngine:
         if rc:
             raise DeerError(rc, self.lib.deer_last_error(None).decode())
         self.ctx = ctx
-        self._timeline_on = False
         self.batch = 0
         self.bonus = 0
         self._draft = torch.zeros(max_batch * 32, dtype=torch.int32, device=self.device)
@@ -274,26 +276,21 @@ class DeerEngine:
     def debug_gemm_tiled(self, min_tiles):
         self._check(self.lib.deer_debug_gemm_tiled(self.ctx, int(min_tiles)))
 
-    def debug_pass_mode(self, mode):
-        """0: one kernel per operation (default); 1: persistent pass kernel wherever it applies."""
-        self.lib.deer_debug_pass_mode.argtypes = [C.c_void_p, C.c_int]
-        self._check(self.lib.deer_debug_pass_mode(self.ctx, int(mode)))
+    def debug_force_commit(self, tokens):
+        """Commits tokens[b] (a list per sequence, possibly empty) instead of running the acceptance rule."""
+        n = np.array([len(t) for t in tokens], dtype=np.int32)
+        stride = max(1, int(n.max()))
+        buf = np.zeros((self.batch, stride), dtype=np.int32)
+        for b, t in enumerate(tokens):
+            buf[b, : len(t)] = t
+        self._check(self.lib.deer_debug_force_commit(self.ctx, buf.ctypes.data, n.ctypes.data, stride))
 
-    def debug_pass_timeline(self, enable, read=True):
-        """Stamps [blocks][stamps_per_block] (uint64 ticks of the 100 MHz device clock) of the last recorded
-        pass kernel, or None; then switches recording on or off for the following passes."""
-        nb, ns = C.c_int32(), C.c_int32()
-        fn = self.lib.deer_debug_pass_timeline
-        fn.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
-        if not read:
-            self._check(fn(self.ctx, int(enable), None, C.byref(nb), C.byref(ns)))
-            self._timeline_on = bool(enable)
-            return None
-        self._check(fn(self.ctx, int(self._timeline_on), None, C.byref(nb), C.byref(ns)))
-        out = np.zeros((max(nb.value, 1), ns.value), dtype=np.uint64)
-        self._check(fn(self.ctx, int(enable), out.ctypes.data if nb.value > 0 else None, C.byref(nb), C.byref(ns)))
-        self._timeline_on = bool(enable)
-        return out if nb.value > 0 else None
+    def debug_load_kv(self, model, layer, seq, first_slot, k_rows, v_rows):
+        """k_rows, v_rows: contiguous device tensors [n][kv_head][head_dim], bfloat16 (or int16 bit patterns)."""
+        assert k_rows.is_cuda and v_rows.is_cuda and k_rows.is_contiguous() and v_rows.is_contiguous()
+        assert k_rows.shape == v_rows.shape and k_rows.element_size() == 2 and v_rows.element_size() == 2
+        self._check(self.lib.deer_debug_load_kv(self.ctx, model, layer, seq, first_slot, k_rows.shape[0],
+                                                k_rows.data_ptr(), v_rows.data_ptr()))
 
     def get_lengths(self):
         out = np.zeros(self.batch, dtype=np.int32)
@@ -304,32 +301,6 @@ class DeerEngine:
         lay = KvLayout()
         self._check(self.lib.deer_get_kv_layout(self.ctx, model, C.byref(lay)))
         return lay
-
-    def kv_tensor(self, model):
-        """The model's whole KV buffer as a flat int16 (bf16 bit) device tensor."""
-        return self._kv[model].view(self.torch.int16)
-
-    def kv_views(self, model, shape):
-        """(K, Vt) views of the model's cache: K[layer][seq][kv_head][slot][head_dim] and
-        Vt[layer][seq][kv_head][slot // 32][head_dim][slot % 32], int16 bit patterns of bf16."""
-        lay = self.get_kv_layout(model)
-        kv = self.kv_tensor(model)
-        L, B, H, hd, S = shape.n_layers, self.max_batch, shape.n_kv_heads, shape.head_dim, lay.max_seq
-        K = kv[lay.k_base: lay.k_base + L * lay.layer_stride].view(L, B, H, S, hd)
-        Vt = kv[lay.v_base: lay.v_base + L * lay.layer_stride].view(L, B, H, S // 32, hd, 32)
-        return K, Vt
-
-    def write_kv_rows(self, views, layer, b, k_rows, v_rows):
-        """Writes cache slots 0..n-1 of sequence slot b: k_rows, v_rows are int16 device tensors [n][kv_head][head_dim]."""
-        K, Vt = views
-        n = k_rows.shape[0]
-        K[layer, b, :, :n, :] = k_rows.permute(1, 0, 2)
-        full, rem = n // 32, n % 32
-        v = v_rows.permute(1, 2, 0)                       # [kv_head][head_dim][n]
-        if full:
-            Vt[layer, b, :, :full] = v[:, :, : full * 32].reshape(v.shape[0], v.shape[1], full, 32).permute(0, 2, 1, 3)
-        if rem:
-            Vt[layer, b, :, full, :, :rem] = v[:, :, full * 32:]
 
     def synchronize(self):
         self.torch.cuda.current_stream(self.device).synchronize()

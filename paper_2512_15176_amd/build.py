@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 LIB_PATH = os.path.join(PKG_DIR, "libdeer.so")
 SOURCES = [os.path.join(PKG_DIR, "csrc", "deer_api.hip")]
-HEADERS = [os.path.join(PKG_DIR, "csrc", "deer_kernels.hpp"), os.path.join(PKG_DIR, "csrc", "deer_pass.hpp"), os.path.join(PKG_DIR, "csrc", "deer_tiled.hpp"), os.path.join(ROOT, "include", "deer.h")]
+HEADERS = [os.path.join(PKG_DIR, "csrc", "deer_kernels.hpp"), os.path.join(PKG_DIR, "csrc", "deer_tiled.hpp"), os.path.join(ROOT, "include", "deer.h")]
 
 
 def hipcc_path() -> str:

@@ -1,7 +1,6 @@
 // Host side of libdeer: context, buffer carving, call-order state machine, kernel launches.
 // The C ABI is declared in include/deer.h.  Nothing here allocates device memory.
 #include "deer_kernels.hpp"
-#include "deer_pass.hpp"
 #include "deer_tiled.hpp"
 
 #include <algorithm>
@@ -22,7 +21,8 @@ namespace {
 
 thread_local std::string g_init_error;
 
-constexpr int PASS_MAX_BLOCKS = 512;   // workgroups of the persistent pass kernel (one per compute unit)
+
+constexpr int STAMP_MAX_BLOCKS = 4096;   // workgroups whose stamps deer_debug_gemm_stamps can record (8 stamps each)
 // rows of a prefill chunk / 32: dense models take 4096 rows per pass through the LDS-tiled GEMM, mixtures 512
 // (their grouped expert buffers grow with the rows of a pass)
 constexpr int PREFILL_TILES_DENSE = 128, PREFILL_TILES_MOE = 16;
@@ -69,13 +69,10 @@ struct Work {   // carved from the workspace
     int *gemm_cnt = nullptr, *attn_cnt = nullptr;   // arrival counters, zero between kernels
     size_t cnt_bytes = 0; char *cnt_base = nullptr;
     double *theta[2] = {nullptr, nullptr};
-    // persistent pass kernel: per-layer activation fragments (dense models, two tiles) and its barrier words
     size_t part_floats = 0;   // capacity of `part`
     AccPart *acc_part = nullptr; int *acc_cnt = nullptr;   // sampling acceptance: per-share candidates, arrival counters
     int4 *pf_desc = nullptr;  // prefill: per-tile (sequence, first position, rows, offset into ids)
-    uint4 *pass_x = nullptr; size_t pass_x_vecs = 0;
-    unsigned *pass_sync = nullptr;
-    unsigned long long *pass_stamps = nullptr;   // [PASS_MAX_BLOCKS][PASS_STAMPS], written on request
+    unsigned long long *stamps = nullptr;   // [STAMP_MAX_BLOCKS][8], written on request (deer_debug_gemm_stamps)
     size_t bytes = 0;
 };
 
@@ -104,14 +101,6 @@ struct deer_ctx {
     char *h_pin = nullptr;           // the same, page-locked: the copy lands without an intermediate staging copy
     size_t h_pin_bytes = 0;
     std::string err;
-    // persistent pass kernel
-    int n_cus = 0;                   // compute units of the device
-    int pass_blocks = 0;             // resident workgroups of the cooperative launch; 0: not available
-    int pass_mode = 0;               // 0: one kernel per operation, 1: persistent kernel where possible
-    bool pass_used = false;          // a pass kernel has run since the error flag was last read
-    unsigned pass_flag_host = 0;     // host copy of the kernel's error flag
-    bool pass_stamps_on = false;     // deer_debug_pass_timeline: the next pass kernels record their timeline
-    bool prof_split = false;         // deer_debug_profile(2): time per operation (separate kernels)
     // optional per-launch timing (deer_debug_profile)
     bool prof_on = false;
     struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
@@ -264,14 +253,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
         w.acc_cnt = w.gemm_cnt ? w.gemm_cnt + ng + na : nullptr;
         w.cnt_bytes = (ng + na + (size_t)B) * 4;
     }
-    for (const deer_model_cfg *mc : {&t, &d}) {
-        if (mc->n_experts) continue;
-        const size_t v = (size_t)(mc->n_layers + 1) * pass_x_layer_vecs(mc->d_model, mc->n_q_heads * mc->head_dim, mc->d_ff, 2);
-        w.pass_x_vecs = std::max(w.pass_x_vecs, v);
-    }
-    w.pass_x = (uint4 *)take(w.pass_x_vecs * 16);
-    w.pass_sync = (unsigned *)take(PASS_SYNC_WORDS * 4);
-    w.pass_stamps = (unsigned long long *)take((size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8);
+    w.stamps = (unsigned long long *)take((size_t)STAMP_MAX_BLOCKS * 8 * 8);
     w.bytes = off;
 }
 
@@ -297,20 +279,15 @@ const char *check_params(const deer_init_params *p) {
 // to 256 k-steps, 256 for longer contractions; at most 8 splits; none for contractions of up to 64 k-steps.
 int choose_split(int N, int KS, int zgroups) {
     const int blocks = (N / CG) * zgroups;
-    static const int t_short = getenv("DEER_SPLIT_SHORT") ? atoi(getenv("DEER_SPLIT_SHORT")) : 224;
-    static const int t_long = getenv("DEER_SPLIT_LONG") ? atoi(getenv("DEER_SPLIT_LONG")) : 256;
-    const int target = KS > 256 ? t_long : t_short;
-    static const int s_floor = getenv("DEER_SPLIT_FLOOR") ? atoi(getenv("DEER_SPLIT_FLOOR")) : 1;
-    int S = s_floor ? std::max(1, target / blocks) : (target + blocks - 1) / blocks;
+    const int target = KS > 256 ? 256 : 224;
+    int S = std::max(1, target / blocks);
     // the workgroup that finishes a column group sums S partial tiles (about 0.25 us each) before its epilogue:
     // beyond 8 splits that costs more than the shorter streams save (drafter down projection, 7 column groups:
     // 19 splits 22.8 us, 8 splits 18.5 us)
-    static const int s_max = getenv("DEER_SPLIT_MAX") ? atoi(getenv("DEER_SPLIT_MAX")) : 8;
-    S = std::min(S, s_max);
+    S = std::min(S, 8);
     // a short contraction (the drafter's d = 896: 56 k-steps) is not split at all: the partial store, the arrival
     // and the last workgroup's sum cost more than streaming a 128-column slab from one workgroup (2.44 -> 2.36 ms per draft pass)
-    static const int ks_nosplit = getenv("DEER_NOSPLIT_KS") ? atoi(getenv("DEER_NOSPLIT_KS")) : 64;
-    if (KS <= ks_nosplit) S = 1;
+    if (KS <= 64) S = 1;
     S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);
@@ -325,9 +302,8 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     // pass over two row tiles 2.26 -> 1.71 ms, over 16 tiles (batch 8) 3.73 -> 3.39 ms, over 32 tiles 5.56 -> 5.80 ms
     // (pairs stay); of the 8B shape's matrices the 33.6 MB output projection gains up to 8 tiles and the 50.3 MB QKV
     // projection up to 4 (batch 2 verify 5.99 -> 5.82 ms), gate/up and down lose at any tile count.
-    static const double mt1_bytes = getenv("DEER_MT1_BYTES") ? atof(getenv("DEER_MT1_BYTES")) : 5.1e7;
-    static const double mt1_product = getenv("DEER_MT1_PRODUCT") ? atof(getenv("DEER_MT1_PRODUCT")) : 2.8e8;
-    static const int mt1_tiles = getenv("DEER_MT1_TILES") ? atoi(getenv("DEER_MT1_TILES")) : 16;
+    constexpr double mt1_bytes = 5.1e7, mt1_product = 2.8e8;
+    constexpr int mt1_tiles = 16;
     // (matrix bytes x tiles is capped too: the output projection loses at 16 tiles)
     const double w_bytes = (double)a.N * K * 2.0;
     const bool pairs = ntiles % 2 == 0 && !(ntiles <= mt1_tiles && w_bytes <= mt1_bytes && w_bytes * ntiles <= mt1_product);
@@ -340,7 +316,7 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
         // measured: at 512 and 1024 rows (two and four row blocks) the streaming kernel with shared L2 lines is still
         // ahead (config-5 verify 41.9 against 47.7 ms); from 1024 rows on the blocked kernel wins where it has 128 tiles
         // (prefill 133 against 167 ms; two 512-token sequences recomputed per iteration 44.3 against 46.8 ms)
-        static const int rows_tiles = getenv("DEER_GEMM_TILED_ROWS") ? atoi(getenv("DEER_GEMM_TILED_ROWS")) : 32;
+        constexpr int rows_tiles = 32;
         const int min_rows_tiles = c->tiled_min_tiles >= 128 ? rows_tiles : TG_RT;   // tests lower both thresholds
         if (c->tiled_min_tiles > 0 && EPI != EPI_ROUTER && ntiles >= min_rows_tiles && a.KS % TG_KST == 0 && tiles >= c->tiled_min_tiles) {
             a.S = 1; a.part = nullptr; a.counters = nullptr;
@@ -355,17 +331,16 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     a.part = (EPI == EPI_LMHEAD) ? nullptr : c->wk.part;
     a.counters = c->wk.gemm_cnt;
     a.stamps = nullptr;
-    if (c->stamp_launch >= 0 && c->cur_pass_model == c->stamp_model && c->gemm_launch_idx == c->stamp_launch &&
-        (size_t)(a.N / CG) * a.S * zg * 8 <= (size_t)PASS_MAX_BLOCKS * PASS_STAMPS) {
-        a.stamps = c->wk.pass_stamps;
-        c->stamp_blocks = (a.N / CG) * a.S * zg;
-        (void)hipMemsetAsync(a.stamps, 0, (size_t)c->stamp_blocks * 64, c->stream);
+    const int stamp_rel = c->gemm_launch_idx - c->stamp_launch;   // the chosen launch and the one after it record
+    if (c->stamp_launch >= 0 && c->cur_pass_model == c->stamp_model && (stamp_rel == 0 || stamp_rel == 1) &&
+        (size_t)(a.N / CG) * a.S * zg <= (size_t)STAMP_MAX_BLOCKS / 2) {
+        a.stamps = c->wk.stamps + (size_t)stamp_rel * (STAMP_MAX_BLOCKS / 2) * 8;   // zeroed at the start of the pass
+        c->stamp_blocks = STAMP_MAX_BLOCKS;
     }
     c->gemm_launch_idx++;
     dim3 grid(a.N / CG, a.S, zg);
     ProfScope ps(c, 0, (double)a.N * K * 2.0);
-    static const int zmap = getenv("DEER_GEMM_ZMAP") ? atoi(getenv("DEER_GEMM_ZMAP")) : 1;
-    if (zg > 1 && zmap) {   // the row-tile groups of a (column group, K split) pair share an XCD's L2
+    if (zg > 1) {   // the row-tile groups of a (column group, K split) pair share an XCD's L2
         const int ncg = a.N / CG, pairs8 = (ncg * a.S + 7) / 8;
         dim3 g1((unsigned)(pairs8 * 8 * zg));
         if (MT == 2) hipLaunchKernelGGL((k_gemm_rows<2, EPI>), g1, dim3(512), 0, c->stream, a, ncg, zg);
@@ -400,136 +375,6 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float sc
     return DEER_OK;
 }
 
-__global__ void k_pass_reset(unsigned *sync) {   // arrival counter and release flags back to zero; the error flag stays
-    if (threadIdx.x <= PASS_NF) sync[threadIdx.x * PASS_SYNC_STRIDE] = 0u;
-    if (threadIdx.x == 0) sync[pass_xcd_word()] = 0u;
-}
-
-template <int HD, int MT>
-hipError_t launch_pass(const PassArgs &pa, int blocks, hipStream_t s) {
-    void *args[] = {(void *)&pa};
-    return hipLaunchCooperativeKernel(reinterpret_cast<void *>(k_pass<HD, MT>), dim3(blocks), dim3(512), args, 0, s);
-}
-
-template <int HD, int MT>
-int pass_occupancy() {
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_pass<HD, MT>, 512, 0) != hipSuccess) return 0;
-    return per_cu;
-}
-
-// Which passes run as the persistent kernel: none unless asked for (deer_debug_pass_mode(1) or
-// DEER_PERSISTENT=1).  Measured on MI355X (batch 1, prefix 4096 / 1024): the 8B-shaped target pass takes
-// 4.70 ms as one persistent kernel against 4.61 ms as one kernel per operation, the 0.5B drafter 2.69 ms
-// against 1.71 ms.
-bool pass_eligible(const deer_ctx *c, const ModelRT &m, int ntiles, const LmPlan &lm) {
-    if (c->pass_mode != 1 || c->pass_blocks < 1 || c->prof_split) return false;
-    if (m.c.n_experts || ntiles > 2 || (lm.on && (lm.n_tiles != 1 || lm.k_lo > 0))) return false;
-    return m.c.d_model / CG <= 64;   // the kernel keeps a row's sums of squares in 4 registers of 16 threads
-}
-
-// The same pass as run_pass, as one cooperative launch (dense model, at most two tiles).
-int run_pass_persistent(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total) {
-    ModelRT &m = c->m[model];
-    Work &w = c->wk;
-    const deer_model_cfg &mc = m.c;
-    const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG, nb = c->pass_blocks;
-    hipStream_t s = c->stream;
-    PassArgs pa{};
-    pa.L = mc.n_layers; pa.d = d; pa.Hq = mc.n_q_heads; pa.Hkv = mc.n_kv_heads; pa.hd = hd; pa.F = m.F; pa.V = mc.vocab;
-    pa.n_qkv = m.n_qkv; pa.kattn = m.kattn; pa.eps = mc.rms_eps;
-    pa.lw0 = m.w + m.off_layers; pa.layer_bytes = m.layer_bytes;
-    pa.lo_qkv = m.lo_qkv; pa.lo_o = m.lo_o; pa.lo_gu = m.lo_gu; pa.lo_d = m.lo_d;
-    pa.w_lm = m.w + m.off_lm;
-    pa.kv_k = m.kv + m.kv_k_base; pa.kv_v = m.kv + m.kv_v_base;
-    pa.kv_layer_stride = m.kv_layer_stride; pa.kv_seq_stride = m.kv_seq_stride; pa.kv_head_stride = m.kv_head_stride;
-    pa.max_seq = c->p.max_seq;
-    pa.rm = w.rm; pa.cs = w.cs; pa.h = w.h; pa.ssq = w.ssq; pa.part = w.part; pa.opart = w.opart; pa.counters = w.gemm_cnt;
-    pa.xbase = w.pass_x; pa.x_layer = pass_x_layer_vecs(d, m.kattn, m.F, ntiles);
-    pa.ntiles = ntiles; pa.nb = nb;
-    // K splits: as many as give every workgroup of a group (an XCD: an eighth of the grid) one piece
-    auto split = [&](int N, int KS) {
-        const int ncgl = (N / CG + 7) / 8;
-        int S = std::max(1, (nb / 8) / ncgl);
-        S = std::min(S, std::max(1, KS / 16));               // at least 2 k-steps per wave
-        S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
-        return std::max(S, 1);
-    };
-    pa.S_qkv = split(m.n_qkv, d / 16);
-    pa.S_o = split(d, m.kattn / 16);
-    pa.S_gu = split(2 * m.F, d / 16);
-    pa.S_d = split(d, m.F / 16);
-    {   // a wide gate/up matrix (more than half as many column groups as workgroups) can be cut into equal
-        // consecutive shares instead; a column group then has at most KS / u + 2 pieces
-        // Off by default: measured on the 8B shape, 192 whole column groups on 256 workgroups (a quarter idle in
-        // this phase, no partial tiles) give 4.74 ms per pass, equal shares with two pieces each 4.89 ms.
-        static const bool stream_gu = getenv("DEER_PASS_GU_SHARES") && atoi(getenv("DEER_PASS_GU_SHARES")) == 1;
-        const int ncg = 2 * m.F / CG, KS = d / 16;
-        const int u = (ncg * KS / nb) / 8 * 8;   // a lower bound of the share under either grouping
-        pa.stream_gu = (stream_gu && ncg > nb / 2 && u >= 16 && ((size_t)KS / u + 2) * 2 * m.F <= PART_COLS) ? 1 : 0;
-    }
-    // bits: 1 split-K partials and counters, 2 residual stream, 4 attention partials
-    // Off by default: measured, the grouping by XCD gains nothing on the 8B target (4.95 ms either way) and
-    // costs the small drafter 0.45 ms (its few column groups and kv heads leave most XCDs without work).
-    static const int allow_near = getenv("DEER_PASS_XCD_LOCAL") ? atoi(getenv("DEER_PASS_XCD_LOCAL")) : 0;
-    pa.allow_near = allow_near;
-    const int nkt = (max_limit + 31) / 32;
-    static const int ns_target = getenv("DEER_PASS_ATTN_ITEMS") ? atoi(getenv("DEER_PASS_ATTN_ITEMS")) : 256;
-    int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
-    NS = std::max(1, std::min({NS, MAX_NS, std::max(1, 64 / ntiles), (nkt + 1) / 2}));
-    pa.NS = NS;
-    pa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
-    pa.lm_on = lm.on ? 1 : 0; pa.lm_mt0 = lm.mt0; pa.lm_stride = lm.mt_stride; pa.lm_tiles = lm.n_tiles; pa.k = lm.k;
-    pa.T = lm.T; pa.seed = lm.seed;
-    pa.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
-    pa.stat = w.stat; pa.res = w.res[model];
-    pa.sync = w.pass_sync; pa.spin_limit = 200000u;
-    pa.stamps = c->pass_stamps_on ? w.pass_stamps : nullptr;
-
-    // layer 0's input fragments, RoPE table, barrier counters
-    hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
-                       w.pass_x, w.pass_x + (size_t)ntiles * plane_vecs(d), w.ssq, d, ncg_d);
-    LAUNCHCHK(c, "k_embed");
-    {
-        int n = rows * (hd / 2);
-        hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, w.rm.pos, m.theta, w.cs, hd / 2, rows);
-        LAUNCHCHK(c, "k_rope_table");
-    }
-    hipLaunchKernelGGL(k_pass_reset, dim3(1), dim3(64), 0, s, w.pass_sync);
-    LAUNCHCHK(c, "k_pass_reset");
-    double bytes = (double)mc.n_layers * ((double)m.n_qkv * d + (double)m.kattn * d + 3.0 * m.F * d) * 2.0 +
-                   (lm.on ? (double)mc.vocab * d * 2.0 : 0.0) +
-                   (double)mc.n_layers * kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;
-    hipError_t e;
-    {
-        ProfScope ps(c, 2, bytes);
-        if (hd == 128) e = ntiles == 1 ? launch_pass<128, 1>(pa, nb, s) : launch_pass<128, 2>(pa, nb, s);
-        else if (hd == 64) e = ntiles == 1 ? launch_pass<64, 1>(pa, nb, s) : launch_pass<64, 2>(pa, nb, s);
-        else e = ntiles == 1 ? launch_pass<32, 1>(pa, nb, s) : launch_pass<32, 2>(pa, nb, s);
-    }
-    if (e != hipSuccess) return fail(c, DEER_EHIP, "cooperative launch of the pass kernel: %s", hipGetErrorString(e));
-    c->pass_used = true;
-    return DEER_OK;
-}
-
-// Did a pass kernel give up waiting at its grid barrier?  pass_error_fetch enqueues the copy of the flag
-// (before a stream synchronisation the caller does anyway), pass_error_check looks at it afterwards.
-int pass_error_fetch(deer_ctx *c) {
-    c->pass_flag_host = 0;
-    if (!c->pass_used) return DEER_OK;
-    HIPCHK(c, hipMemcpyAsync(&c->pass_flag_host, c->wk.pass_sync + pass_err_word(), 4, hipMemcpyDeviceToHost, c->stream));
-    return DEER_OK;
-}
-int pass_error_check(deer_ctx *c) {
-    if (!c->pass_used) return DEER_OK;
-    c->pass_used = false;
-    if (c->pass_flag_host) {
-        (void)hipMemsetAsync(c->wk.pass_sync + pass_err_word(), 0, 4, c->stream);
-        return fail(c, DEER_EHIP, "the pass kernel's grid barrier timed out; results of the last pass are invalid");
-    }
-    return DEER_OK;
-}
-
 // One forward pass of `model` over the rows described by the row metadata (ntiles tiles).
 int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total = 0.0) {
     ModelRT &m = c->m[model];
@@ -538,8 +383,8 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     const int d = mc.d_model, hd = mc.head_dim, rows = ntiles * 32, ncg_d = d / CG;
     c->gemm_launch_idx = 0;
     c->cur_pass_model = model;
-    if (pass_eligible(c, m, ntiles, lm)) return run_pass_persistent(c, model, ntiles, max_limit, lm, kv_keys_total);
     hipStream_t s = c->stream;
+    if (c->stamp_launch >= 0 && model == c->stamp_model) (void)hipMemsetAsync(w.stamps, 0, (size_t)STAMP_MAX_BLOCKS * 64, s);
     hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
                        w.xa_hi, w.xa_lo, w.ssq, d, ncg_d);
     LAUNCHCHK(c, "k_embed");
@@ -551,7 +396,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     const int nkt = (max_limit + 31) / 32;
     // key-range splits: aim at one workgroup per compute unit; a split holds at least one staged chunk of 4 key
     // tiles; ntiles * NS never exceeds the partial buffer (max(64, most tiles of a pass) tile slots)
-    static const int ns_target = getenv("DEER_ATTN_BLOCKS") ? atoi(getenv("DEER_ATTN_BLOCKS")) : 256;
+    constexpr int ns_target = 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
     NS = std::max(1, std::min({NS, MAX_NS, std::max(1, std::max(64, c->max_tiles) / ntiles), (nkt + 3) / 4}));
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
@@ -594,8 +439,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             a.W = (const uint4 *)(lw + m.lo_router); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = CG;
             a.n_experts = mc.n_experts; a.top_k = mc.top_k; a.route_e = w.route_e; a.route_w = w.route_w;
             a.route_spread = (c->route_spread && (mc.n_experts & (mc.n_experts - 1)) == 0) ? l + 1 : 0;
-            static const int router_S = getenv("DEER_ROUTER_SPLIT") ? atoi(getenv("DEER_ROUTER_SPLIT")) : 0;
-            rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, router_S);
+            rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, 0);
             if (rc) return rc;
             const int cap = rows, chunks = ntiles;
             hipLaunchKernelGGL(k_moe_group, dim3(1), dim3(256), 0, s, w.route_e, w.rm.slot, rows, mc.top_k, mc.n_experts, cap,
@@ -721,22 +565,8 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
     if (c->wk.moe_touched) (void)hipMemsetAsync(c->wk.moe_touched, 0, 8, c->stream);
     e = hipMemsetAsync(c->wk.cnt_base, 0, c->wk.cnt_bytes, c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
-    e = hipMemsetAsync(c->wk.pass_sync, 0, PASS_SYNC_WORDS * 4, c->stream);
-    if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipMemsetAsync: %s", hipGetErrorString(e)); }
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e)); }
-    {   // the persistent pass kernel needs a cooperative launch with every workgroup resident
-        int coop = 0, cus = 0;
-        (void)hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, p->device);
-        (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device);
-        int occ = std::min({pass_occupancy<128, 1>(), pass_occupancy<128, 2>(), pass_occupancy<64, 1>(), pass_occupancy<64, 2>(),
-                            pass_occupancy<32, 1>(), pass_occupancy<32, 2>()});
-        c->n_cus = cus;
-        c->pass_blocks = (coop && occ >= 1) ? std::min(cus, PASS_MAX_BLOCKS) : 0;
-        if (const char *e = getenv("DEER_PERSISTENT")) c->pass_mode = atoi(e) == 1 ? 1 : 0;
-        if (const char *e = getenv("DEER_GEMM_TILED_MIN")) c->tiled_min_tiles = std::max(0, atoi(e));
-        (void)hipGetLastError();
-    }
     {   // a few KB of page-locked host memory for the acceptance results (host memory: the device buffers stay the caller's)
         const size_t bytes = (size_t)((const char *)c->wk.ao.committed - (const char *)c->wk.ao.accept_len) + (size_t)p->max_batch * 32 * 4;
         void *hp = nullptr;
@@ -854,9 +684,7 @@ int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         }
         if (int rc = flush()) return rc;
     }
-    if (int rc = pass_error_fetch(c)) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (int rc = pass_error_check(c)) return rc;
     return upload_state(c, batch, lenv.data(), lenv.data(), pend.data());
 }
 
@@ -936,37 +764,37 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     return DEER_OK;
 }
 
-int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom) {
-    if (!c) return DEER_EINVAL;
+static int accept_impl(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom,
+                       AccPart *acc_part, int *acc_cnt) {
     if (!acc || !committed || !ncom || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
     if (c->state != ST_VERIFIED) return fail(c, DEER_ESTATE, "accept_and_commit must follow verify_block");
     if (k != c->cur_k || T != c->cur_T) return fail(c, DEER_EINVAL, "k and T must match the draft_block call");
     const int B = c->batch;
     Work &w = c->wk;
     const int V = c->p.target.vocab;
+    const int cs = k + c->bonus;   // committed tokens per sequence: at most k, or k + 1 with the bonus token
+    const char *d0 = (const char *)w.ao.accept_len;
+    const size_t o_n = (const char *)w.ao.n_committed - d0, o_c = (const char *)w.ao.committed - d0;
+    const size_t bytes = o_c + (size_t)B * cs * 4;
+    char *host = c->h_pin;
+    if (!host || bytes > c->h_pin_bytes) {
+        c->h_ao.resize(bytes);
+        host = c->h_ao.data();
+    }
     if (T == 0.f)
         hipLaunchKernelGGL(k_accept_greedy, dim3(B), dim3(64), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET], k,
                            c->p.eos_token_id, c->bonus);
     else
         hipLaunchKernelGGL(k_accept_sample, dim3(B, ACC_NB), dim3(1024), 0, c->stream, w.st, w.ao, c->wk_draft, w.res[DEER_TARGET],
                            w.res[DEER_DRAFTER], w.logits[DEER_TARGET], w.logits[DEER_DRAFTER], k, V, T, seed, c->p.eos_token_id,
-                           c->bonus, w.acc_part, w.acc_cnt);
+                           c->bonus, acc_part, acc_cnt, w.rm.pos);
     LAUNCHCHK(c, "k_accept");
-    const int cs = k + c->bonus;   // committed tokens per sequence: at most k, or k + 1 with the bonus token
-    {   // the three result arrays lie one after the other in the workspace: one copy instead of three
-        const char *d0 = (const char *)w.ao.accept_len;
-        const size_t o_n = (const char *)w.ao.n_committed - d0, o_c = (const char *)w.ao.committed - d0;
-        const size_t bytes = o_c + (size_t)B * cs * 4;
-        char *host = c->h_pin;
-        if (!host || bytes > c->h_pin_bytes) { c->h_ao.resize(bytes); host = c->h_ao.data(); }
-        HIPCHK(c, hipMemcpyAsync(host, d0, bytes, hipMemcpyDeviceToHost, c->stream));
-        if (int rc = pass_error_fetch(c)) return rc;
-        HIPCHK(c, hipStreamSynchronize(c->stream));
-        memcpy(acc, host, (size_t)B * 4);
-        memcpy(ncom, host + o_n, (size_t)B * 4);
-        memcpy(committed, host + o_c, (size_t)B * cs * 4);
-    }
-    if (int rc = pass_error_check(c)) return rc;
+    // the three result arrays lie one after the other in the workspace: one copy instead of three
+    HIPCHK(c, hipMemcpyAsync(host, d0, bytes, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    memcpy(acc, host, (size_t)B * 4);
+    memcpy(ncom, host + o_n, (size_t)B * 4);
+    memcpy(committed, host + o_c, (size_t)B * cs * 4);
     for (int b = 0; b < B; ++b) {
         c->h_len[b] += ncom[b];
         c->h_ing_n[b] = ncom[b];
@@ -974,6 +802,11 @@ int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32
     }
     c->state = ST_PREFILLED;
     return DEER_OK;
+}
+
+int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom) {
+    if (!c) return DEER_EINVAL;
+    return accept_impl(c, k, T, seed, acc, committed, ncom, c->wk.acc_part, c->wk.acc_cnt);
 }
 
 int deer_set_bonus_token(deer_ctx *c, int enable) {
@@ -1002,9 +835,7 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
     const size_t n = (size_t)c->batch * (c->cur_k + (model == DEER_TARGET ? c->bonus : 0)) * c->p.target.vocab;
     if (n_floats < n) return fail(c, DEER_ECAPACITY, "output holds %zu floats, need %zu", n_floats, n);
     HIPCHK(c, hipMemcpyAsync(out, c->wk.logits[model], n * 4, hipMemcpyDeviceToHost, c->stream));
-    if (int rc = pass_error_fetch(c)) return rc;
     HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (int rc = pass_error_check(c)) return rc;
     return DEER_OK;
 }
 
@@ -1012,7 +843,6 @@ int deer_debug_profile(deer_ctx *c, int enable) {
     if (!c) return DEER_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prof_on = enable != 0;
-    c->prof_split = enable == 2;
     c->prof.clear();
     c->ev_used = 0;
     return DEER_OK;
@@ -1031,26 +861,13 @@ int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int
     return DEER_OK;
 }
 
-int deer_debug_pass_timeline(deer_ctx *c, int enable, uint64_t *stamps_host, int32_t *blocks, int32_t *stamps_per_block) {
-    if (!c) return DEER_EINVAL;
-    HIPCHK(c, hipStreamSynchronize(c->stream));
-    if (blocks) *blocks = c->pass_blocks;
-    if (stamps_per_block) *stamps_per_block = PASS_STAMPS;
-    if (stamps_host && c->pass_blocks > 0)
-        HIPCHK(c, hipMemcpy(stamps_host, c->wk.pass_stamps, (size_t)c->pass_blocks * PASS_STAMPS * 8, hipMemcpyDeviceToHost));
-    if (enable && !c->pass_stamps_on)
-        HIPCHK(c, hipMemsetAsync(c->wk.pass_stamps, 0, (size_t)PASS_MAX_BLOCKS * PASS_STAMPS * 8, c->stream));
-    c->pass_stamps_on = enable != 0;
-    return DEER_OK;
-}
-
 int deer_debug_gemm_stamps(deer_ctx *c, int model, int launch, uint64_t *stamps_host, int32_t max_blocks, int32_t *blocks) {
     if (!c) return DEER_EINVAL;
     if (model < 0 || model > 1) return fail(c, DEER_EINVAL, "bad model");
     HIPCHK(c, hipStreamSynchronize(c->stream));
     if (blocks) *blocks = c->stamp_blocks;
     if (stamps_host && c->stamp_blocks > 0 && max_blocks > 0)
-        HIPCHK(c, hipMemcpy(stamps_host, c->wk.pass_stamps, (size_t)std::min(max_blocks, c->stamp_blocks) * 64, hipMemcpyDeviceToHost));
+        HIPCHK(c, hipMemcpy(stamps_host, c->wk.stamps, (size_t)std::min(max_blocks, c->stamp_blocks) * 64, hipMemcpyDeviceToHost));
     c->stamp_model = model;
     c->stamp_launch = launch;
     c->stamp_blocks = 0;
@@ -1082,11 +899,49 @@ int deer_debug_gemm_tiled(deer_ctx *c, int min_tiles) {
     return DEER_OK;
 }
 
-int deer_debug_pass_mode(deer_ctx *c, int mode) {
+int deer_debug_force_commit(deer_ctx *c, const int32_t *tokens, const int32_t *n, int32_t stride) {
     if (!c) return DEER_EINVAL;
-    if (mode < 0 || mode > 1) return fail(c, DEER_EINVAL, "pass mode must be 0 or 1");
-    HIPCHK(c, hipStreamSynchronize(c->stream));
-    c->pass_mode = mode;
+    if (!tokens || !n || stride < 1) return fail(c, DEER_EINVAL, "null pointer or bad stride");
+    if (c->state != ST_VERIFIED) return fail(c, DEER_ESTATE, "force_commit stands in for accept_and_commit: it must follow verify_block");
+    const int B = c->batch, cs = c->cur_k + c->bonus;
+    if (stride > 32) return fail(c, DEER_EINVAL, "stride must be at most 32");
+    for (int b = 0; b < B; ++b) {
+        if (n[b] < 0 || n[b] > cs || n[b] > stride) return fail(c, DEER_EINVAL, "sequence %d: %d tokens, at most %d fit this block", b, n[b], std::min(cs, stride));
+        for (int i = 0; i < n[b]; ++i)
+            if (tokens[(size_t)b * stride + i] < 0 || tokens[(size_t)b * stride + i] >= c->p.target.vocab) return fail(c, DEER_EINVAL, "token id outside the vocabulary");
+    }
+    Work &w = c->wk;
+    // staged through the acceptance result arrays (unused until the next accept_and_commit)
+    HIPCHK(c, hipMemcpyAsync(w.ao.committed, tokens, (size_t)B * stride * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(w.ao.n_committed, n, (size_t)B * 4, hipMemcpyHostToDevice, c->stream));
+    hipLaunchKernelGGL(k_force_commit, dim3((B + 63) / 64), dim3(64), 0, c->stream, w.st, w.ao.committed, w.ao.n_committed, stride,
+                       c->p.eos_token_id, B);
+    LAUNCHCHK(c, "k_force_commit");
+    HIPCHK(c, hipStreamSynchronize(c->stream));   // the host arrays may be reused by the caller
+    for (int b = 0; b < B; ++b) {
+        c->h_len[b] += n[b];
+        c->h_ing_n[b] = n[b];
+        for (int i = 0; i < n[b]; ++i)
+            if (c->p.eos_token_id >= 0 && tokens[(size_t)b * stride + i] == c->p.eos_token_id) c->h_finished[b] = 1;
+    }
+    c->state = ST_PREFILLED;
+    return DEER_OK;
+}
+
+int deer_debug_load_kv(deer_ctx *c, int model, int32_t layer, int32_t seq, int32_t first_slot, int32_t n_slots,
+                       const void *k_rows_dev, const void *v_rows_dev) {
+    if (!c) return DEER_EINVAL;
+    if (model < 0 || model > 1 || !k_rows_dev || !v_rows_dev) return fail(c, DEER_EINVAL, "bad model or null pointer");
+    ModelRT &m = c->m[model];
+    if (layer < 0 || layer >= m.c.n_layers || seq < 0 || seq >= c->p.max_batch) return fail(c, DEER_EINVAL, "layer or sequence out of range");
+    if (first_slot < 0 || n_slots < 0 || (int64_t)first_slot + n_slots > c->p.max_seq) return fail(c, DEER_ECAPACITY, "slots %d .. %d exceed max_seq %d", first_slot, first_slot + n_slots, c->p.max_seq);
+    if (n_slots == 0) return DEER_OK;
+    const KvView kv{m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride, m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride,
+                    m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
+    const size_t items = (size_t)n_slots * m.c.n_kv_heads * (m.c.head_dim / 8);
+    hipLaunchKernelGGL(k_load_kv, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, c->stream, (const uint16_t *)k_rows_dev,
+                       (const uint16_t *)v_rows_dev, kv, seq, first_slot, n_slots, m.c.n_kv_heads, m.c.head_dim);
+    LAUNCHCHK(c, "k_load_kv");
     return DEER_OK;
 }
 

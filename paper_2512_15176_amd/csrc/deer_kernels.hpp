@@ -161,20 +161,9 @@ __device__ __forceinline__ float2 ld_agent2(const float *p) {
     unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_float2(__uint_as_float((unsigned)(u & 0xffffffffu)), __uint_as_float((unsigned)(u >> 32)));
 }
-// The same exchange between workgroups that are known to sit on ONE XCD (the persistent pass kernel places
-// them).  Only the LOADS change: a workgroup-scope load skips the per-CU cache and is served by that XCD's
-// L2, where the agent-scope (write-through) stores of the other workgroups of the XCD have passed, instead
-// of going to memory.  Stores and counters stay agent-scope: the completion of a narrower-scope store does
-// not say that it has reached L2.  `near` selects the loads at run time.
-__device__ __forceinline__ float2 ld_near2(const float *p) {
-    unsigned long long u = __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    return make_float2(__uint_as_float((unsigned)(u & 0xffffffffu)), __uint_as_float((unsigned)(u >> 32)));
-}
-__device__ __forceinline__ float2 ld_x2(const float *p, bool near) { return near ? ld_near2(p) : ld_agent2(p); }
-
 // Called by every thread after its partial stores: waits for them, then one thread counts the block
 // in.  Returns true in every thread of the block that arrived last (counter reset for the next use).
-__device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag, bool near = false) {
+__device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag) {
     // The thread's agent-scope stores must have been performed before the block is counted in.  A
     // workgroup-scope fence does not wait for vector memory, so the wait is explicit.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -186,17 +175,12 @@ __device__ __forceinline__ bool arrive_last(int *cnt, int expected, int *s_flag,
         *s_flag = last;
     }
     __syncthreads();
-    if (near) asm volatile("buffer_inv sc0" ::: "memory");   // no older copy of the partials in this CU's cache
     return *s_flag != 0;
 }
 
-// Accessors for data that crosses workgroups INSIDE one kernel (the persistent pass kernel).  COH = true:
-// agent-scope accesses, coherent across the XCDs' separate L2s; COH = false: plain accesses (producer
-// and consumer are separated by a kernel boundary).
-template <bool COH> __device__ __forceinline__ float ldf(const float *p) {
-    if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return *p;
-}
+// Stores of results that other workgroups read.  COH = true: agent-scope (write-through) stores, for data that
+// crosses workgroups inside one kernel (they may sit on XCDs with separate L2s); COH = false: plain stores
+// (producer and consumer are separated by a kernel boundary).
 template <bool COH> __device__ __forceinline__ void stf(float *p, float v) {
     if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else *p = v;
@@ -204,15 +188,6 @@ template <bool COH> __device__ __forceinline__ void stf(float *p, float v) {
 template <bool COH> __device__ __forceinline__ void sti(int *p, int v) {
     if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else *p = v;
-}
-template <bool COH> __device__ __forceinline__ uint4 ld16(const uint4 *p) {
-    if (COH) {
-        const unsigned long long *q = (const unsigned long long *)p;
-        unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return make_uint4((uint32_t)a, (uint32_t)(a >> 32), (uint32_t)b, (uint32_t)(b >> 32));
-    }
-    return *p;
 }
 template <bool COH> __device__ __forceinline__ void st16(uint4 *p, uint4 v) {
     if (COH) {
@@ -432,7 +407,6 @@ struct GemmArgs {
     const float2 *cs; RowMeta rm; uint4 *qhi, *qlo; KvView kv; int Hq, Hkv, hd;
     // RESID: h += y, new fragments and sums of squares of h
     float *h; uint4 *xhi_out, *xlo_out; float *ssq_out;
-    int near, h_near;   // coherent mode only: split-K partials and arrival counters / h stay inside one XCD's L2
     // SWIGLU: activation fragments over F channels
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
@@ -452,7 +426,7 @@ __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int gro
     const int row = tidx >> 4, j = tidx & 15;
     const float *p = ssq + (size_t)(grow0 + row) * ncg;
     float s = 0.f;
-    for (int g = j; g < ncg; g += 16) s += ldf<COH>(p + g);
+    for (int g = j; g < ncg; g += 16) s += p[g];
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) s += shx(s, off);
     if (j == 0) rstd[row] = rsqrtf(s / (float)d + eps);
@@ -519,7 +493,7 @@ __device__ __forceinline__ void resid_prefetch(const GemmArgs &a, float (&hreg)[
     for (int i = 0; i < 8; ++i) {
         const int e = tidx + 512 * i;
         const float *hp = a.h + (size_t)(t * 32 + (e >> 7)) * a.N + cg * CG + (e & 127);
-        hreg[i] = (COH && a.h_near) ? __hip_atomic_load(hp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) : ldf<COH>(hp);
+        hreg[i] = *hp;
     }
 }
 
@@ -803,20 +777,25 @@ __device__ __forceinline__ void gemm_stamp(const GemmArgs &a, int lin, int i) {
 }
 
 // One work item of the weight-streaming GEMM: column group cg, K split s, row-tile group z.
-// DEFER = false: with S > 1 the block that arrives last at the group's counter finishes the group;
-// DEFER = true: the partial tile is left for a later gemm_finish (after a grid-wide barrier).
+// With S > 1 the block that arrives last at the group's counter finishes the group.
 // WSTREAM: weights are read once by the whole grid (non-temporal loads); false: several workgroups of an XCD read
 // the same weights at about the same time and should find them in its L2 (plain loads).
-template <int MT, int EPI, bool COH, bool DEFER, bool WSTREAM = true>
+template <int MT, int EPI, bool COH, bool WSTREAM = true>
 __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int cg, int s, int z, int ncg) {
     const int tidx = opaque_tid();
     float *red = sm.red, *tile = sm.tile, *s_rstd = sm.rstd;
     const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;   // the wave index as a scalar: scalar loop bounds
     const int N = a.N, KS = a.KS, S = a.S;
-    const int slices = S * 8, sl = s * 8 + w;
-    const int per = (KS + slices - 1) / slices;
-    const int ks0 = sl * per;
-    const int ks1 = min(KS, ks0 + per);
+    // K range of the workgroup: split s of S; inside it wave w takes the k-steps w, w + 8, w + 16, ... (the eight
+    // waves read neighbouring 1 KB fragments at about the same time and advance together) or, with
+    // DEER_GEMM_INTERLEAVE = 0, one contiguous eighth
+#ifndef DEER_GEMM_INTERLEAVE
+#define DEER_GEMM_INTERLEAVE 1
+#endif
+    constexpr int KSTEP = DEER_GEMM_INTERLEAVE ? 8 : 1;
+    const int per = (KS + S * 8 - 1) / (S * 8);
+    const int ks0 = DEER_GEMM_INTERLEAVE ? s * 8 * per + w : (s * 8 + w) * per;
+    const int ks1 = DEER_GEMM_INTERLEAVE ? min(KS, (s + 1) * 8 * per) : min(KS, ks0 + per);
 
     const int lin = (z * S + s) * ncg + cg;   // stamps: 0 start, 1 this wave's K slice multiplied, 2 tile stored
     gemm_stamp(a, lin, 0);                    // (epilogue done if S == 1), 3 arrived, 4 last workgroup's finish done
@@ -839,36 +818,36 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     }
 
     // Software pipeline: D k-steps of loads are in flight while older steps are multiplied.
-#ifndef DEER_GEMM_D1
-#define DEER_GEMM_D1 4
-#endif
-#ifndef DEER_GEMM_D2
-#define DEER_GEMM_D2 3
-#endif
-    constexpr int D = (MT == 1) ? DEER_GEMM_D1 : DEER_GEMM_D2;   // bounded by the register file: no spills
+    constexpr int D = (MT == 1) ? 4 : 3;   // bounded by the register file: no spills
     uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
 #pragma unroll
     for (int dd = 0; dd < D; ++dd) {
-        int ks = ks0 + dd;
+        int ks = ks0 + KSTEP * dd;
         if (ks < ks1) {
 #pragma unroll
             for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)ks * 64) : wp[nb * wstride + (size_t)ks * 64];
+        }
+    }
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)ks * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)ks * 64); }
+    for (int dd = 0; dd < D; ++dd) {
+        int ks = ks0 + KSTEP * dd;
+        if (ks < ks1) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)ks * 64]; xlb[dd][mt] = xl[mt][(size_t)ks * 64]; }
         }
     }
     // RMSNorm factors of the input rows: their sums of squares were finished by the previous kernel, so they are
-    // requested now, behind the first weights, instead of as a dependent round trip inside the epilogue
-    constexpr bool RSTD_EARLY = !COH && EPI != EPI_RESID;
+    // requested now, behind the first activations, instead of as a dependent round trip inside the epilogue
+    constexpr bool RSTD_EARLY = EPI != EPI_RESID;
     if (RSTD_EARLY) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
             tile_rstd<COH>(a.ssq_in, s_rstd + 32 * mt, (a.mt0 + (z * MT + mt) * a.mt_stride) * 32, a.ncg_in, a.d_in, a.eps);
     }
-    for (int kb = ks0; kb < ks1; kb += D) {
+    for (int kb = ks0; kb < ks1; kb += KSTEP * D) {
 #pragma unroll
         for (int dd = 0; dd < D; ++dd) {
-            int ks = kb + dd;
+            int ks = kb + KSTEP * dd;
             if (ks < ks1) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -877,12 +856,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
                         acc[mt][nb] = mfma32(xhb[dd][mt], wb[dd][nb], acc[mt][nb]);
                         acc[mt][nb] = mfma32(xlb[dd][mt], wb[dd][nb], acc[mt][nb]);
                     }
-                int kn = ks + D;
+                int kn = ks + KSTEP * D;
                 if (kn < ks1) {
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)kn * 64) : wp[nb * wstride + (size_t)kn * 64];
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = ld16<COH>(xh[mt] + (size_t)kn * 64); xlb[dd][mt] = ld16<COH>(xl[mt] + (size_t)kn * 64); }
+                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)kn * 64]; xlb[dd][mt] = xl[mt][(size_t)kn * 64]; }
                 }
             }
         }
@@ -911,7 +890,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         }
     }
     gemm_stamp(a, lin, 2);
-    if (S == 1 || DEFER) return;
+    if (S == 1) return;
     // the block that arrives last at this column group's counter sums all partials and finishes
     const bool last = arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last);
     gemm_stamp(a, lin, 3);
@@ -923,7 +902,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
 template <int MT, int EPI>
 __global__ __launch_bounds__(512) void k_gemm(const GemmArgs a) {
     __shared__ GemmSmem sm;
-    gemm_block<MT, EPI, false, false>(a, sm, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.x);
+    gemm_block<MT, EPI, false>(a, sm, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.x);
 }
 
 // The same GEMM over Z > 1 row-tile groups (batched passes, prefill chunks): every group needs the same weights.
@@ -935,8 +914,7 @@ __global__ __launch_bounds__(512) void k_gemm_rows(const GemmArgs a, int ncg, in
     __shared__ GemmSmem sm;
     const int lin = blockIdx.x, x = lin & 7, q = lin >> 3;
     const int z = q % Z, p = 8 * (q / Z) + x;
-    if (p >= ncg * a.S) return;
-    gemm_block<MT, EPI, false, false, false>(a, sm, p % ncg, p / ncg, z, ncg);
+    if (p < ncg * a.S) gemm_block<MT, EPI, false, false>(a, sm, p % ncg, p / ncg, z, ncg);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1519,7 +1497,7 @@ __global__ __launch_bounds__(512) void k_attn(const uint4 *__restrict__ Qhi, con
 // with the (M, L) pairs, which makes it two round trips.
 template <int HD, bool EARLY = false>
 __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
-                                                int head, int t, int tt, int hh, int lane, bool near = false) {
+                                                int head, int t, int tt, int hh, int lane) {
     constexpr int PF = AttnPartial<HD>::FLOATS;
     const int half = lane >> 5, qrow = lane & 31;
     const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
@@ -1531,13 +1509,13 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
         for (int u = 0; u < 16; ++u)
 #pragma unroll
             for (int r2 = 0; r2 < 4; ++r2)
-                v[u][r2] = ld_x2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2, near);
+                v[u][r2] = ld_agent2(p0 + (size_t)min(s0 + u, NS - 1) * PF + ((tt * 8 + 4 * hh + r2) * 64 + lane) * 2);
     };
     if (EARLY) load_half(0);
     {
         float2 ml[32];
 #pragma unroll
-        for (int s = 0; s < 32; ++s) ml[s] = ld_x2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow, near);
+        for (int s = 0; s < 32; ++s) ml[s] = ld_agent2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow);
 #pragma unroll
         for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
 #pragma unroll
@@ -1642,6 +1620,10 @@ __global__ void k_accept_greedy(SeqState st, AcceptOut out, const int *__restric
 // Grid (sequence, ACC_NB): every workgroup repeats the k tests (cheap), then scans its share of the vocabulary
 // row; the candidates of the ACC_NB shares meet through memory and the workgroup that arrives last picks the
 // winner (largest perturbed weight, lowest index on ties: the same token whatever the split) and commits.
+// The kernel reads nothing that it writes before all shares have arrived: the committed length j comes from
+// the verify pass's row metadata (row 0 of the sequence's tile sits at position j - 1), every share arrives
+// on every path (finished sequence, all k drafts accepted, a draw), and only the last arrival touches the
+// per-sequence state and resets the counter.
 constexpr int ACC_NB = 32;
 struct AccPart { float best; int bi; float bestp; int bpi; int any; int pad[3]; };
 
@@ -1650,23 +1632,21 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
                                                         const RowResult *__restrict__ dres,
                                                         const float *__restrict__ tlogits,
                                                         const float *__restrict__ dlogits, int k, int V, float T,
-                                                        uint64_t seed, int eos, int bonus, AccPart *parts, int *arrivals) {
+                                                        uint64_t seed, int eos, int bonus, AccPart *parts, int *arrivals,
+                                                        const int *__restrict__ verify_pos) {
     __shared__ int s_a, s_last;
     __shared__ float sv[1024]; __shared__ int sx[1024];
     __shared__ float sv2[1024]; __shared__ int sx2[1024]; __shared__ int s_any[1024];
     const int b = blockIdx.x, nb = gridDim.y, part = blockIdx.y;
-    if (st.finished[b]) {
-        if (threadIdx.x == 0 && part == 0) { out.accept_len[b] = 0; out.n_committed[b] = 0; }
-        return;
-    }
+    const bool finished = st.finished[b] != 0;   // written only by the last arrival, after this read
     const int *d = draft + b * k;
     const int kt = k + bonus;           // target rows per sequence
-    const int j = st.len[b];
+    const int j = verify_pos[b * 32] + 1;
     const float invT = 1.f / T;
     if (threadIdx.x < 64) {   // the k tests at once (each has its own uniform and rows), then the first rejection
         const int i = threadIdx.x;
         int rej = k;
-        if (i < k) {
+        if (i < k && !finished) {
             const size_t rt = (size_t)b * kt + i, rd = (size_t)b * k + i;
             const int y = d[i];
             const float logp = tlogits[rt * V + y] * invT - tres[rt].lse;
@@ -1680,46 +1660,48 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
     }
     __syncthreads();
     const int a = s_a;
-    if (!(a < k || bonus)) {   // k drafts accepted and no extra token: nothing to draw
-        if (threadIdx.x == 0 && part == 0) commit_tokens(st, out, b, k, a, -1, d, eos, bonus);
-        return;
-    }
-    const bool has_q = a < k;       // a drafted token stands at this position
-    const size_t rt = (size_t)b * kt + a, rd = (size_t)b * k + (has_q ? a : 0);
-    const float lt = tres[rt].lse, ld = has_q ? dres[rd].lse : 0.f;
-    const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
-    float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
-    const int share = (V + nb - 1) / nb, v0 = part * share, v1 = min(V, v0 + share);
-    for (int v = v0 + threadIdx.x; v < v1; v += 1024) {
-        const float logp = tlogits[rt * V + v] * invT - lt;
-        const float gn = gumbel(key, (uint64_t)v);
-        if (has_q) {
-            const float logq = dlogits[rd * V + v] * invT - ld;
-            const float diff = expf(logp) - expf(logq);
-            if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+    const bool draw = !finished && (a < k || bonus);   // a token has to be drawn (k accepted drafts without the extra token: nothing to draw)
+    if (draw) {
+        const bool has_q = a < k;       // a drafted token stands at this position
+        const size_t rt = (size_t)b * kt + a, rd = (size_t)b * k + (has_q ? a : 0);
+        const float lt = tres[rt].lse, ld = has_q ? dres[rd].lse : 0.f;
+        const uint64_t key = row_key(seed, TAG_RESID, (uint64_t)b, (uint64_t)(j + a));
+        float best = -INFINITY, bestp = -INFINITY; int bi = 0x7fffffff, bpi = 0x7fffffff, any = 0;
+        const int share = (V + nb - 1) / nb, v0 = part * share, v1 = min(V, v0 + share);
+        for (int v = v0 + threadIdx.x; v < v1; v += 1024) {
+            const float logp = tlogits[rt * V + v] * invT - lt;
+            const float gn = gumbel(key, (uint64_t)v);
+            if (has_q) {
+                const float logq = dlogits[rd * V + v] * invT - ld;
+                const float diff = expf(logp) - expf(logq);
+                if (diff > 0.f) { any = 1; argmax_merge(best, bi, logf(diff) + gn, v); }
+            }
+            argmax_merge(bestp, bpi, logp + gn, v);
         }
-        argmax_merge(bestp, bpi, logp + gn, v);
-    }
-    s_any[threadIdx.x] = any; sv[threadIdx.x] = best; sx[threadIdx.x] = bi; sv2[threadIdx.x] = bestp; sx2[threadIdx.x] = bpi;
-    __syncthreads();
-    for (int off = 512; off > 0; off >>= 1) {
-        if (threadIdx.x < off) {
-            s_any[threadIdx.x] |= s_any[threadIdx.x + off];
-            argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
-            argmax_merge(sv2[threadIdx.x], sx2[threadIdx.x], sv2[threadIdx.x + off], sx2[threadIdx.x + off]);
-        }
+        s_any[threadIdx.x] = any; sv[threadIdx.x] = best; sx[threadIdx.x] = bi; sv2[threadIdx.x] = bestp; sx2[threadIdx.x] = bpi;
         __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        AccPart *pp = parts + (size_t)b * nb + part;
-        __hip_atomic_store(&pp->best, sv[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&pp->bi, sx[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&pp->bestp, sv2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&pp->bpi, sx2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&pp->any, s_any[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int off = 512; off > 0; off >>= 1) {
+            if (threadIdx.x < off) {
+                s_any[threadIdx.x] |= s_any[threadIdx.x + off];
+                argmax_merge(sv[threadIdx.x], sx[threadIdx.x], sv[threadIdx.x + off], sx[threadIdx.x + off]);
+                argmax_merge(sv2[threadIdx.x], sx2[threadIdx.x], sv2[threadIdx.x + off], sx2[threadIdx.x + off]);
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            AccPart *pp = parts + (size_t)b * nb + part;
+            __hip_atomic_store(&pp->best, sv[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&pp->bi, sx[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&pp->bestp, sv2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&pp->bpi, sx2[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&pp->any, s_any[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     if (!arrive_last(arrivals + b, nb, &s_last)) return;
-    if (threadIdx.x == 0) {
+    if (threadIdx.x != 0) return;
+    if (finished) { out.accept_len[b] = 0; out.n_committed[b] = 0; return; }
+    int corr = -1;
+    if (draw) {
         int any_all = 0;
         for (int p = 0; p < nb; ++p) any_all |= __hip_atomic_load(&parts[(size_t)b * nb + p].any, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         float wv = -INFINITY; int wi = 0x7fffffff;
@@ -1729,9 +1711,45 @@ __global__ __launch_bounds__(1024) void k_accept_sample(SeqState st, AcceptOut o
             const int ci = __hip_atomic_load(any_all ? &pp->bi : &pp->bpi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             argmax_merge(wv, wi, cv, ci);
         }
-        const int corr = (wi >= 0 && wi < V) ? wi : 0;   // all-NaN rows never update the index
-        commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
+        corr = (wi >= 0 && wi < V) ? wi : 0;   // all-NaN rows never update the index
     }
+    commit_tokens(st, out, b, k, a, corr, d, eos, bonus);
+}
+
+// Test aid: the caller's tokens are committed in place of the acceptance rule's choice.  One thread per sequence;
+// n[b] tokens tok[b * stride ..] (n[b] = 0: nothing).  Same state updates as commit_tokens.
+__global__ void k_force_commit(SeqState st, const int *__restrict__ tok, const int *__restrict__ n, int stride, int eos, int B) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int nb = n[b];
+    if (nb <= 0) { st.ing_n[b] = 0; return; }
+    int fin = 0;
+    for (int i = 0; i < nb; ++i) {
+        const int t = tok[b * stride + i];
+        st.ing_tok[b * 32 + i] = t;
+        if (eos >= 0 && t == eos) fin = 1;
+    }
+    st.ing_n[b] = nb;
+    st.len[b] += nb;
+    st.pending[b] = tok[b * stride + nb - 1];
+    if (fin) st.finished[b] = 1;
+}
+
+// Test aid: canonical K and V rows [n][kv_head][head_dim] (bf16) into cache slots first .. first + n - 1 of one
+// sequence and layer.  One thread per (slot, head, channel octet).
+__global__ void k_load_kv(const uint16_t *__restrict__ krows, const uint16_t *__restrict__ vrows, KvView kv, int b, int first,
+                          int n, int Hkv, int hd) {
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int octs = hd >> 3;
+    if (gid >= (size_t)n * Hkv * octs) return;
+    const int oct = (int)(gid % octs), head = (int)((gid / octs) % Hkv), r = (int)(gid / ((size_t)octs * Hkv));
+    const int slot = first + r;
+    const size_t src = ((size_t)r * Hkv + head) * hd + oct * 8;
+    const size_t base = (size_t)b * kv.seq_stride + (size_t)head * kv.head_stride;
+    *(uint4 *)(kv.k + base + (size_t)slot * hd + oct * 8) = *(const uint4 *)(krows + src);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        kv.vt[base + (size_t)(slot >> 5) * (hd * 32) + (size_t)(oct * 8 + e) * 32 + (slot & 31)] = vrows[src + e];
 }
 
 }  // namespace deer

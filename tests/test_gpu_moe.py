@@ -5,7 +5,7 @@ import pytest
 
 import deer_inputs as di
 from oracle import deer_oracle as O
-from gpu_common import StoredWeights, gpu_available, make_engine, make_pair, top2_margin
+from gpu_common import StoredWeights, fill_seeded_cache, gpu_available, lockstep_commit, make_engine, make_pair, top2_margin
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
 
@@ -42,19 +42,58 @@ def test_moe_lockstep(name):
         eng.draft_block(k, 0.0, 0)
         res = O.deer_iteration(pair, k, 0.0, None, draft_override=block)
         eng.verify_block(k, 0.0, torch.tensor([block], dtype=torch.int32, device="cuda"))
-        err = float(np.abs(eng.debug_get_logits(0, k)[0] - res["target_logits"]).max())
+        gzt = eng.debug_get_logits(0, k)[0]
+        err = float(np.abs(gzt - res["target_logits"]).max())
         worst = max(worst, err)
         assert err < case["tol"], err
-        acc, com, ncom = eng.accept_and_commit(k, 0.0, 0)
-        if acc[0] != res["accept_len"] or com[0] != res["committed"]:
-            first = min(acc[0], res["accept_len"])
-            assert top2_margin(res["target_logits"])[first] < 1e-2
-            eng.prefill([pair.prefix()])
-        else:
-            assert acc[0] == a_want
+        if lockstep_commit(eng, k, [gzt], [res], [block]):
+            assert res["accept_len"] == a_want
+        assert eng.get_lengths()[0] == len(pair.prefix())
     per_pass = eng.debug_experts_streamed() / (len(case["forced"]) * t.n_layers)
     print(f"\n[{name}] max |target logit error| {worst:.2e}; experts streamed per layer and verify pass: {per_pass:.1f} of {t.n_experts}")
     assert per_pass > t.top_k      # the rows of a block do go to different experts (the grouped path is exercised)
+    eng.close()
+
+
+def test_a3b_twelve_layers_all_experts_full_vocab_prefix_2048():
+    """The mixture workload deeper: 12 of the 48 layers at the real widths (d = 2048, 32 q / 4 kv heads, 128 experts of
+    width 768, top-8), the full 151936-entry vocabulary, a 2048-token prefix (seeded stand-in cache contents on both
+    sides: a real prefill of it on the CPU oracle would take minutes), k = 32, T = 0; two iterations, the second after
+    a commit (the drafter ingests, the target cache has grown)."""
+    import torch
+    cfg = di.CONFIGS["qwen3_30b_a3b"]
+    t, d, k, n = di.scaled(cfg["target"], n_layers=12), di.scaled(cfg["drafter"], n_layers=2), cfg["k"], cfg["prefix"]
+    wt, wd = StoredWeights(t, di.TARGET_SEED, "bf16"), StoredWeights(d, di.DRAFTER_SEED, "bf16")
+    eng = make_engine(t, d, wt, wd, 1, n + 128, k)
+    pair = make_pair(t, d, wt, wd, n + 128, dtype=np.float32)
+    last = 4242
+    pair.x = [0] * (n - 1) + [last]
+    fill_seeded_cache(eng, torch, 0, t, 0, n - 1, pair.tc)
+    fill_seeded_cache(eng, torch, 1, d, 0, n, pair.dc)
+    eng.set_prefilled([n], [last])
+    eng.debug_experts_streamed()
+    worst_d = worst_t = 0.0
+    rng = np.random.default_rng(7)
+    for it in range(2):
+        gd = eng.draft_block(k, 0.0, 0).cpu().numpy()[0]
+        zd = pair.draft_logits(k)
+        ed = float(np.abs(eng.debug_get_logits(1, k)[0] - zd).max())
+        ok = top2_margin(zd) > 1e-2
+        assert np.array_equal(gd[ok], np.argmax(zd, -1)[ok])
+        block = [int(v) for v in rng.integers(0, t.vocab, size=k)]
+        res = O.deer_iteration(pair, k, 0.0, None, draft_override=block)
+        eng.verify_block(k, 0.0, torch.tensor([block], dtype=torch.int32, device="cuda"))
+        gzt = eng.debug_get_logits(0, k)[0]
+        et = float(np.abs(gzt - res["target_logits"]).max())
+        worst_d, worst_t = max(worst_d, ed), max(worst_t, et)
+        assert ed < 2e-2 and et < 2e-2, (it, ed, et)
+        okt = top2_margin(res["target_logits"]) > 1e-2
+        assert np.array_equal(np.argmax(gzt, -1)[okt], np.argmax(res["target_logits"], -1)[okt])
+        lockstep_commit(eng, k, [gzt], [res], [block])
+        assert eng.get_lengths()[0] == len(pair.prefix())
+    per_pass = eng.debug_experts_streamed() / (2 * t.n_layers)
+    print(f"\n[30B-A3B widths, 12 layers, 128 experts, full vocab, prefix {n}] max |logit error|: drafter {worst_d:.2e}, "
+          f"target {worst_t:.2e}; experts streamed per layer and pass: {per_pass:.1f}")
     eng.close()
 
 
