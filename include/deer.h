@@ -159,6 +159,18 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_toke
 int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed,
                            int32_t *accept_len_host, int32_t *committed_host, int32_t *n_committed_host);
 
+/* deer_accept_and_commit for callers that must not allocate device memory or have the library use scratch
+ * of the caller's sizing (code under HIP graph capture around it, tight serving loops, harnesses that forbid
+ * hipMalloc).  Same arguments, results, state rules and errors as deer_accept_and_commit; the sampling
+ * kernel's scratch (per-share candidates and arrival counters) lives in a static device array inside the
+ * library (65.8 KB per GPU, held until the process ends) instead of the workspace, and the call makes no
+ * hipMalloc / hipFree and no host allocation.  Limit: at most 64 sequences in the batch (DEER_ECAPACITY
+ * beyond).  All contexts on one GPU share that array: calls that overlap on one GPU (two contexts on
+ * different streams) race; calls one after the other are fine (the counters are cleared at the start of
+ * every call).  Waits for the stream. */
+int deer_accept_and_commit_static(deer_ctx *c, int32_t k, float T, uint64_t seed,
+                                  int32_t *accept_len_host, int32_t *committed_host, int32_t *n_committed_host);
+
 /* Bonus token (an extension beside Alg. 1, off by default; Appendix, Theorem: its induction step is a
  * draw from p_AR given an exactly distributed prefix, which holds for one more position).  When enabled,
  * deer_verify_block feeds k + 1 rows [x_j, y^_1 .. y^_k] (draft_tokens_dev is read in full) and

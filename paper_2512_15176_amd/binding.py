@@ -15,7 +15,7 @@ DEER_F32, DEER_BF16 = 0, 1
 TENSOR_IDS = {"embed": 1, "lm_head": 2, "wq": 3, "wk": 4, "wv": 5, "wo": 6, "wg": 7, "wu": 8, "wd": 9, "router": 10}
 STATUS = {0: "DEER_OK", -1: "DEER_EINVAL", -2: "DEER_ESTATE", -3: "DEER_ECAPACITY", -4: "DEER_EHIP", -5: "DEER_EVERSION"}
 EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_prefill", "deer_set_prefilled",
-           "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_destroy", "deer_last_error",
+           "deer_draft_block", "deer_verify_block", "deer_accept_and_commit", "deer_accept_and_commit_static", "deer_destroy", "deer_last_error",
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
            "deer_debug_profile_read", "deer_debug_force_commit", "deer_debug_load_kv", "deer_set_bonus_token",
            "deer_draft_block_multipass", "deer_debug_gemm_tiled",
@@ -77,6 +77,7 @@ def load_library(path: str = LIB_PATH):
     lib.deer_draft_block_multipass.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32, C.c_void_p]
     lib.deer_verify_block.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_void_p]
     lib.deer_accept_and_commit.argtypes = [C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.deer_accept_and_commit_static.argtypes = lib.deer_accept_and_commit.argtypes
     lib.deer_destroy.argtypes = [C.c_void_p]
     lib.deer_debug_route_spread.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_experts_streamed.argtypes = [C.c_void_p, C.c_void_p]
@@ -234,11 +235,13 @@ class DeerEngine:
         self._check(self.lib.deer_set_bonus_token(self.ctx, int(bool(enable))))
         self.bonus = int(bool(enable))
 
-    def accept_and_commit(self, k, T=0.0, seed=0):
+    def accept_and_commit(self, k, T=0.0, seed=0, static=False):
+        """static=True: the entry point whose kernel scratch is the library's static device array."""
         acc = np.zeros(self.batch, dtype=np.int32)
         ncom = np.zeros(self.batch, dtype=np.int32)
         com = np.zeros((self.batch, k + self.bonus), dtype=np.int32)
-        self._check(self.lib.deer_accept_and_commit(self.ctx, k, T, seed, acc.ctypes.data, com.ctypes.data, ncom.ctypes.data))
+        fn = self.lib.deer_accept_and_commit_static if static else self.lib.deer_accept_and_commit
+        self._check(fn(self.ctx, k, T, seed, acc.ctypes.data, com.ctypes.data, ncom.ctypes.data))
         return acc, [com[b, : ncom[b]].tolist() for b in range(self.batch)], ncom
 
     # -- inspection ------------------------------------------------------------------------------

@@ -17,6 +17,18 @@
 
 using namespace deer;
 
+// Scratch of deer_accept_and_commit_static, the entry point that allocates nothing: the per-share candidates of the
+// sampling acceptance kernel (ACC_NB entries per sequence) followed by one arrival counter per sequence.  Every GPU
+// the library runs on holds its own copy until the process ends.
+constexpr int STATIC_MAX_BATCH = 64;
+constexpr size_t STATIC_PART_BYTES = (size_t)STATIC_MAX_BATCH * ACC_NB * sizeof(AccPart);
+constexpr size_t STATIC_SCRATCH_BYTES = STATIC_PART_BYTES + (size_t)STATIC_MAX_BATCH * sizeof(int);
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+// The array's name is a host-side stand-in, not a device address: host code uses the address that
+// hipGetSymbolAddress gives, resolved once per device (with that device current) by deer_init_models.
+constexpr int MAX_DEVICES = 64;
+static void *g_scratch_ptr[MAX_DEVICES] = {};
+
 namespace {
 
 thread_local std::string g_init_error;
@@ -95,6 +107,7 @@ struct deer_ctx {
     int stamp_model = 0, stamp_launch = -1, stamp_blocks = 0, gemm_launch_idx = 0, cur_pass_model = 0;
     int route_spread = 0;            // deer_debug_route_spread: synthetic uniform routing for mixture models
     int bonus = 0;                   // 1: verify k + 1 rows, commit one more target token after k accepted drafts
+    void *static_scratch = nullptr;  // this device's copy of `scratch`
     const int *wk_draft = nullptr;   // draft buffer of the last verify_block
     std::vector<int> h_len, h_ing_n, h_finished;
     std::vector<char> h_ao;          // host staging of the acceptance results (pageable; used only if pinning failed)
@@ -544,6 +557,15 @@ int deer_init_models(const deer_init_params *p, const deer_buffers *bufs, const 
     c->stream = (hipStream_t)p->hip_stream;
     hipError_t e = hipSetDevice(p->device);
     if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipSetDevice: %s", hipGetErrorString(e)); }
+    if (p->device >= 0 && p->device < MAX_DEVICES) {   // this device's address of the static scratch array
+        if (!g_scratch_ptr[p->device]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) { delete c; return fail(nullptr, DEER_EHIP, "hipGetSymbolAddress: %s", hipGetErrorString(e)); }
+            g_scratch_ptr[p->device] = ptr;
+        }
+        c->static_scratch = g_scratch_ptr[p->device];
+    }
     for (int i = 0; i < 2; ++i) {
         plan_model(c->m[i], i == 0 ? p->target : p->drafter, p->max_batch, p->max_seq);
         c->m[i].w = (char *)bufs->weights[i];
@@ -764,8 +786,10 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     return DEER_OK;
 }
 
+// Shared by the two acceptance entry points: acc_part / acc_cnt are the sampling kernel's scratch (from the
+// caller's workspace, or the library's static array).
 static int accept_impl(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom,
-                       AccPart *acc_part, int *acc_cnt) {
+                       AccPart *acc_part, int *acc_cnt, bool no_alloc) {
     if (!acc || !committed || !ncom || k < 1 || k > c->p.max_k || !(T >= 0.f)) return fail(c, DEER_EINVAL, "bad k, T or null pointer");
     if (c->state != ST_VERIFIED) return fail(c, DEER_ESTATE, "accept_and_commit must follow verify_block");
     if (k != c->cur_k || T != c->cur_T) return fail(c, DEER_EINVAL, "k and T must match the draft_block call");
@@ -778,6 +802,7 @@ static int accept_impl(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *
     const size_t bytes = o_c + (size_t)B * cs * 4;
     char *host = c->h_pin;
     if (!host || bytes > c->h_pin_bytes) {
+        if (no_alloc) return fail(c, DEER_ECAPACITY, "no page-locked result buffer was set up at init");
         c->h_ao.resize(bytes);
         host = c->h_ao.data();
     }
@@ -806,7 +831,22 @@ static int accept_impl(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *
 
 int deer_accept_and_commit(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom) {
     if (!c) return DEER_EINVAL;
-    return accept_impl(c, k, T, seed, acc, committed, ncom, c->wk.acc_part, c->wk.acc_cnt);
+    return accept_impl(c, k, T, seed, acc, committed, ncom, c->wk.acc_part, c->wk.acc_cnt, false);
+}
+
+int deer_accept_and_commit_static(deer_ctx *c, int32_t k, float T, uint64_t seed, int32_t *acc, int32_t *committed, int32_t *ncom) {
+    if (!c) return DEER_EINVAL;
+    if (c->batch > STATIC_MAX_BATCH) return fail(c, DEER_ECAPACITY, "the static scratch holds %d sequences, the batch has %d", STATIC_MAX_BATCH, c->batch);
+    if (!c->static_scratch) return fail(c, DEER_EHIP, "the static scratch was not resolved for device %d", c->p.device);
+    AccPart *part = (AccPart *)c->static_scratch;
+    int *cnt = (int *)((char *)c->static_scratch + STATIC_PART_BYTES);
+    if (T > 0.f && c->state == ST_VERIFIED) {
+        // the array keeps the last call's contents: the arrival counters of this batch start at zero (a fill kernel,
+        // not a memset node); stale candidates are overwritten before the last arrival reads them
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(STATIC_MAX_BATCH), 0, c->stream, (uint32_t *)cnt, 0u, (size_t)c->batch);
+        LAUNCHCHK(c, "k_fill_u32");
+    }
+    return accept_impl(c, k, T, seed, acc, committed, ncom, part, cnt, true);
 }
 
 int deer_set_bonus_token(deer_ctx *c, int enable) {
