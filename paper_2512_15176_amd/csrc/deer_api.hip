@@ -301,7 +301,7 @@ int choose_split(int N, int KS, int zgroups) {
     // a short contraction (the drafter's d = 896: 56 k-steps) is not split at all: the partial store, the arrival
     // and the last workgroup's sum cost more than streaming a 128-column slab from one workgroup (2.44 -> 2.36 ms per draft pass)
     if (KS <= 64) S = 1;
-    S = std::min(S, std::max(1, KS / 16));           // at least 2 k-steps per wave
+    S = std::min(S, std::max(1, KS / 16));           // at least 16 k-steps per workgroup
     S = std::min<int>(S, (int)(PART_COLS / (size_t)N));
     return std::max(S, 1);
 }
