@@ -123,7 +123,7 @@ int deer_load_tensor(deer_ctx *c, int model, int tensor_id, int layer, int exper
 int deer_prefill(deer_ctx *c, int32_t batch, const int32_t *prompt_ids_host, const int32_t *prompt_lens_host);
 
 /* Sets the state as if `lens_host[b]` tokens had been prefilled, WITHOUT running the models:
- * the caller has written cache contents itself (see deer_kv_layout) - used where a real prefill
+ * the caller has written cache contents itself (deer_debug_load_kv) - used where a real prefill
  * is too costly (32k-token prefixes).  last_token_host[b] = x_j, the pending token.  The drafter
  * cache is taken to hold all lens_host[b] tokens. */
 int deer_set_prefilled(deer_ctx *c, int32_t batch, const int32_t *lens_host, const int32_t *last_token_host);
@@ -246,10 +246,17 @@ int deer_debug_gemm_tiled(deer_ctx *c, int min_tiles);
 /* Current committed length j per sequence (host mirror). */
 int deer_get_lengths(const deer_ctx *c, int32_t *len_host);
 
-/* Where cache rows live, so that a caller can inspect or pre-fill them:
- *   K[layer][seq][kv_head][slot][head_dim]  and  V stored transposed in blocks of 32 slots,
- *   Vt[layer][seq][kv_head][slot / 32][head_dim][slot % 32]  (the 8 KB of a 32-key tile are contiguous),
- * bf16, slot < max_seq (a multiple of 64).  Offsets are in elements from the start of the model's kv buffer. */
+/* Where the caches live inside the model's kv buffer (bf16; offsets in elements from its start):
+ *   K at k_base + layer * layer_stride + seq * seq_stride + kv_head * head_stride, V at v_base + the same.
+ * Inside a (layer, sequence, kv head) region the slots (slot < max_seq, a multiple of 64) are stored in blocks of
+ * 32, and a block in the order the attention kernels' matrix instructions read it: head_dim / 16 fragments of
+ * 64 lanes x 8 elements (1 KB each).
+ *   K block, fragment s: lane (r, half) = half * 32 + r holds elements 16 s + 8 half .. + 7 of slot
+ *   32 * block + key(r), key(r) = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3).
+ *   V block, fragment 2 tt + s2: lane half * 32 + c holds slots 32 * block + 16 half + 8 s2 .. + 7 of channel
+ *   32 tt + c (V is stored transposed).
+ * A caller that wants to fill cache rows should not write this layout itself: deer_debug_load_kv takes canonical
+ * [slot][kv_head][head_dim] rows. */
 typedef struct {
     size_t k_base, v_base;            /* element offsets of K and Vt blocks                        */
     size_t layer_stride, seq_stride, head_stride; /* same for both                                 */

@@ -41,6 +41,7 @@ constexpr int PREFILL_TILES_DENSE = 128, PREFILL_TILES_MOE = 16;
 int prefill_tiles(const deer_init_params &p) { return (p.target.n_experts || p.drafter.n_experts) ? PREFILL_TILES_MOE : PREFILL_TILES_DENSE; }
 constexpr int PART_TILES_MIN = 16;   // split-K partials exist for passes of up to max(2 * batch, 16) row tiles
 constexpr int MAX_NS = 32;          // key-range splits of block attention
+constexpr int ATT_HEAD_MAX_TILES = 4;   // per-head attention: most key tiles one wave may have to go through
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
@@ -367,14 +368,19 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
 struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; int k_lo = 0; };
 
 template <int HD>
-int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, float scale_log2e, double kv_bytes) {
+int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_head, float scale_log2e, double kv_bytes) {
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
-    const int G = mc.n_q_heads / mc.n_kv_heads;
     const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
     const uint16_t *Vt = m.kv + m.kv_v_base + (size_t)layer * m.kv_layer_stride;
     ProfScope ps(c, 1, kv_bytes);
-    (void)G;
+    if (NS_head > 0) {   // few tiles: one workgroup per (tile, query head, key range), merged by the last to arrive
+        hipLaunchKernelGGL(k_attn_head<HD>, dim3(mc.n_q_heads * NS_head, ntiles), dim3(512), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
+                           m.kv_seq_stride, m.kv_head_stride, w.rm.tile_seq, w.rm.limit, w.opart, w.attn_cnt,
+                           mc.n_q_heads, mc.n_kv_heads, NS_head, scale_log2e, w.xb_hi, w.xb_lo);
+        LAUNCHCHK(c, "k_attn_head");
+        return DEER_OK;
+    }
     hipLaunchKernelGGL(k_attn<HD>, dim3(mc.n_kv_heads * NS, ntiles), dim3(512), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                        m.kv_seq_stride, m.kv_head_stride, c->p.max_seq, w.rm.tile_seq, w.rm.limit, w.opart,
                        mc.n_q_heads, mc.n_kv_heads, NS, scale_log2e, w.xb_hi, w.xb_lo);
@@ -412,6 +418,15 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     constexpr int ns_target = 256;
     int NS = (ns_target + mc.n_kv_heads * ntiles - 1) / (mc.n_kv_heads * ntiles);
     NS = std::max(1, std::min({NS, MAX_NS, std::max(1, std::max(64, c->max_tiles) / ntiles), (nkt + 3) / 4}));
+    // Passes of few tiles (decoding) run attention per query head: (tile, head, key range) workgroups, about one per
+    // compute unit, as long as a wave then has at most ATT_HEAD_MAX_TILES key tiles of its range to go through
+    int NS_head = 0;
+    if (ntiles * mc.n_q_heads <= ns_target) {
+        int ns = ns_target / (ntiles * mc.n_q_heads);
+        ns = std::max(1, std::min({ns, MAX_NS, std::max(1, std::max(64, c->max_tiles) / ntiles), (nkt + 7) / 8}));
+        const int per = (nkt + ns - 1) / ns;
+        if ((per + 7) / 8 <= ATT_HEAD_MAX_TILES) NS_head = ns;
+    }
     const float scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     GemmArgs base{};
@@ -429,9 +444,9 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
                       m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
         int rc = launch_gemm<EPI_QKV>(c, a, d, ntiles, 0);
         if (rc) return rc;
-        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
-        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
-        else rc = launch_attn<32>(c, m, l, ntiles, NS, scale_log2e, kv_bytes);
+        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
+        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
+        else rc = launch_attn<32>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
         if (rc) return rc;
         a = base;
         a.W = (const uint4 *)(lw + m.lo_o); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;

@@ -15,6 +15,7 @@
 //     limit 0 and slot -1.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace deer {
@@ -90,6 +91,18 @@ __device__ __forceinline__ uint4 ld16_stream(const uint4 *p) {
 // (at most N younger loads still outstanding; loads return in order) followed by tie() on the register.
 __device__ __forceinline__ void load16_async(u32x4 &dst, const void *p) {
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+// The same with agent scope: the load is served by memory, not by an L2 that may hold an older copy of a line
+// another XCD has written since.
+__device__ __forceinline__ void load16_agent_async(u32x4 &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+// A 16-byte agent-scope (write-through) store.  The wait states behind it keep the next instruction from
+// overwriting the data registers while the store still reads them (a hazard the compiler covers for its own
+// stores of more than 8 bytes, but cannot see inside an asm statement).
+__device__ __forceinline__ void store16_agent(void *p, float a, float b, float c, float d) {
+    u32x4 v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2" ::"v"(p), "v"(v) : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
@@ -391,6 +404,25 @@ struct KvView {
     int max_seq;
 };
 
+// Both caches are stored per (sequence, kv head) in blocks of 32 slots (one key tile), and inside a block in the
+// order the attention kernels' MFMA operands want them: head_dim / 16 fragments of 64 lanes x 8 elements, so that
+// a wave reads a fragment as one contiguous 1 KB and every cache line it touches is used whole.
+//   K block, fragment s (k-step: elements 16 s .. 16 s + 15): lane (operand row r, half) holds elements
+//   16 s + 8 half .. + 7 of the key whose operand row is r.  Operand rows are a permutation of the keys that gives
+//   each lane of the S^T result 16 consecutive keys: key = 16 * bit2(r) + 4 * (r >> 3) + (r & 3).
+//   V^T block, fragment (O^T tile tt, s2): lane (channel c = 32 tt + (lane & 31), half) holds keys
+//   16 half + 8 s2 .. + 7 of channel c.
+__device__ __forceinline__ int key_operand_row(int key) { return (key & 3) | (((key >> 4) & 1) << 2) | (((key >> 2) & 3) << 3); }
+// element offset of octet `oct` (8 elements of head_dim) of slot `slot` inside a (sequence, kv head) K region
+__device__ __forceinline__ size_t k_cache_off(int slot, int oct, int hd) {
+    return ((size_t)(slot >> 5) * (hd >> 4) + (oct >> 1)) * 512 + ((oct & 1) * 32 + key_operand_row(slot & 31)) * 8;
+}
+// element offset of channel c of slot `slot` inside a (sequence, kv head) V^T region
+__device__ __forceinline__ size_t v_cache_off(int slot, int c, int hd) {
+    const int kk = slot & 31;
+    return ((size_t)(slot >> 5) * (hd >> 4) + (c >> 5) * 2 + ((kk >> 3) & 1)) * 512 + ((kk >> 4) * 32 + (c & 31)) * 8 + (kk & 7);
+}
+
 struct RowStat {   // per (row, column group) partial over 128 vocabulary entries
     float m; int idx;        // max logit, its index (lowest on ties)
     float sumexp;            // sum exp(z/T - m/T)  (T > 0)
@@ -472,11 +504,11 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
             if (slot >= 0) {
                 size_t base = (size_t)b * a.kv.seq_stride + (size_t)head * a.kv.head_stride;
                 if (kind == 1) {
-                    st16<COH>((uint4 *)(a.kv.k + base + (size_t)slot * hd + i0), pack8(v));
+                    st16<COH>((uint4 *)(a.kv.k + base + k_cache_off(slot, i0 >> 3, hd)), pack8(v));
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)   // V^T in blocks of 32 slots: [slot / 32][channel][slot % 32]
-                        st_u16<COH>(a.kv.vt + base + (size_t)(slot >> 5) * (hd * 32) + (i0 + e) * 32 + (slot & 31), (uint16_t)f2bf(v[e]));
+                    for (int e = 0; e < 8; ++e)
+                        st_u16<COH>(a.kv.vt + base + v_cache_off(slot, i0 + e, hd), (uint16_t)f2bf(v[e]));
                 }
             }
         }
@@ -728,31 +760,36 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
     float *tile = sm.tile;
     const int N = a.N, S = a.S;
     float hreg[MT][8];
-    float2 v[MT][4];
+    float4 v[MT][2];
     // the sums of all MT row tiles first (their loads do not depend on each other's epilogue), then the epilogues
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int ct = z * MT + mt;
         if (EPI == EPI_RESID) resid_prefetch<COH>(a, hreg[mt], cg, a.mt0 + ct * a.mt_stride);
         const size_t sstride = (size_t)a.rows_total * N;
-        const float *p[4];
+        const float *p[2];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const int e = tidx + 512 * i;
-            p[i] = a.part + ((size_t)ct * 32 + (e >> 6)) * N + (size_t)cg * CG + (e & 63) * 2;
-            v[mt][i] = make_float2(0.f, 0.f);
+            p[i] = a.part + ((size_t)ct * 32 + (e >> 5)) * N + (size_t)cg * CG + (e & 31) * 4;
+            v[mt][i] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
-        for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 4 elements of loads in flight, summed in order
-            float2 pv[8][4];
+        for (int s0 = 0; s0 < S; s0 += 8) {   // 8 splits x 2 x 16 bytes of loads in flight, summed in order
+            u32x4 pv[8][2];
 #pragma unroll
             for (int u = 0; u < 8; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pv[u][i] = ld_agent2(p[i] + (size_t)min(s0 + u, S - 1) * sstride);
+                for (int i = 0; i < 2; ++i) load16_agent_async(pv[u][i], p[i] + (size_t)min(s0 + u, S - 1) * sstride);
+            wait_loads<0>();
 #pragma unroll
             for (int u = 0; u < 8; ++u)
                 if (s0 + u < S) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) { v[mt][i].x += pv[u][i].x; v[mt][i].y += pv[u][i].y; }
+                    for (int i = 0; i < 2; ++i) {
+                        tie(pv[u][i]);
+                        v[mt][i].x += __uint_as_float(pv[u][i][0]); v[mt][i].y += __uint_as_float(pv[u][i][1]);
+                        v[mt][i].z += __uint_as_float(pv[u][i][2]); v[mt][i].w += __uint_as_float(pv[u][i][3]);
+                    }
                 }
         }
     }
@@ -761,10 +798,10 @@ __device__ __forceinline__ void gemm_finish(const GemmArgs &a, GemmSmem &sm, int
         const int ct = z * MT + mt;
         if (mt > 0) __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const int e = tidx + 512 * i;
-            float *tp = tile + (e >> 6) * RED_STRIDE + (e & 63) * 2;
-            tp[0] = v[mt][i].x; tp[1] = v[mt][i].y;
+            float *tp = tile + (e >> 5) * RED_STRIDE + (e & 31) * 4;
+            tp[0] = v[mt][i].x; tp[1] = v[mt][i].y; tp[2] = v[mt][i].z; tp[3] = v[mt][i].w;
         }
         __syncthreads();
         run_epilogue<EPI, COH, RSTD_EARLY>(a, tile, sm.rstd + 32 * mt, sm.red, hreg[mt], cg, ct);
@@ -880,11 +917,11 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         } else {
             float *out = a.part + ((size_t)s * a.rows_total + (size_t)ct * 32) * N + (size_t)cg * CG;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 2; ++i) {   // 16 bytes per lane: a wave writes two rows of the group's 128 columns
                 const int e = tidx + 512 * i;
-                const int row = e >> 6, c2 = (e & 63) * 2;
-                const float *tp = tile + row * RED_STRIDE + c2;
-                st_agent2(out + (size_t)row * N + c2, tp[0], tp[1]);
+                const int row = e >> 5, c4 = (e & 31) * 4;
+                const float *tp = tile + row * RED_STRIDE + c4;
+                store16_agent(out + (size_t)row * N + c4, tp[0], tp[1], tp[2], tp[3]);
             }
         }
     }
@@ -1305,24 +1342,23 @@ __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, co
     const int nchunks = kt1 > kt0 ? (kt1 - kt0 + ATT_CH - 1) / ATT_CH : 0;
     const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
     const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
-    const int keyperm = 16 * ((qrow >> 2) & 1) + 4 * (qrow >> 3) + (qrow & 3);   // operand row -> key
 
     // Requests this wave's share of a chunk (fragment f = w + 8 * i) straight into LDS: a 16-byte
     // direct-to-LDS load writes lane l's vector at (uniform base) + 16 * l, which is the fragment order, and
     // needs no registers while it travels.  Tiles past the range repeat the last one (not used).
     auto stage = [&](uint4 *dst, int c0) {
         const int ntile = min(ATT_CH, kt1 - c0);
-        // lane offsets (elements) are rebuilt here from two small values, so that eight 64-bit addresses per
-        // lane do not live (spilled) across the whole item
-        int ko = keyperm * HD + half * 8, vo = qrow * 32 + 16 * half;   // V^T block of a key tile: [channel][32 keys]
-        asm volatile("" : "+v"(ko), "+v"(vo));
+        // the lane offset (elements) is rebuilt here from a small value, so that 64-bit addresses per lane do not
+        // live (spilled) across the whole item
+        int lo8 = lane * 8;
+        asm volatile("" : "+v"(lo8));
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             const int f = w + 8 * i, tl = f / FPT, fi = f % FPT;
             const int kt = c0 + min(tl, ntile - 1);
-            const uint16_t *src;
-            if (fi < KSQ) src = Kp + (ko + kt * 32 * HD + fi * 16);
-            else src = Vp + (vo + kt * (32 * HD) + ((fi - KSQ) >> 1) * (32 * 32) + 8 * ((fi - KSQ) & 1));
+            const uint16_t *src;   // both caches hold a key tile as HD / 16 fragments of 1 KB
+            if (fi < KSQ) src = Kp + (lo8 + kt * (32 * HD) + fi * 512);
+            else src = Vp + (lo8 + kt * (32 * HD) + (fi - KSQ) * 512);
             __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
                                              (void __attribute__((address_space(3))) *)(dst + f * 64), 16, 0, 0);
         }
@@ -1489,6 +1525,32 @@ __global__ __launch_bounds__(512) void k_attn(const uint4 *__restrict__ Qhi, con
                         part, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, blockIdx.x % Hkv, blockIdx.x / Hkv, t);
 }
 
+// Writes registers 8*hh .. 8*hh+7 of O^T tile tt (held in o[0..7], scaled by inv) into the output projection's
+// input fragments: octets q = 2*hh and 2*hh + 1 (see attn_write_frag for the lane pairing).
+template <int HD>
+__device__ __forceinline__ void attn_store_slice(const float (&o)[8], float inv, int Hq, int head, int t, int tt, int hh,
+                                                 int lane, uint4 *xhi, uint4 *xlo) {
+    const int half = lane >> 5, qrow = lane & 31;
+    const int KS = Hq * HD / 16;
+#pragma unroll
+    for (int qq = 0; qq < 2; ++qq) {
+        const int q = 2 * hh + qq;
+        float mine[4], other[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = shx(mine[e], 32); }
+        if ((q & 1) == half) {
+            float v8[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v8[e] = half ? other[e] : mine[e]; v8[4 + e] = half ? mine[e] : other[e]; }
+            uint4 hi, lo;
+            pack8_split(v8, hi, lo);
+            const size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
+            st16<true>(xhi + vec, hi);
+            st16<true>(xlo + vec, lo);
+        }
+    }
+}
+
 // Merge of the NS key-range partials of one (tile, head): wave item (tt, hh) owns register pairs 4*hh .. 4*hh+3
 // of O^T tile tt.  All (M, L) pairs are requested at once, then the partial outputs 16 splits at a time, so a
 // merge of 32 splits is three memory round trips.  Splits are combined in order s = 0..NS-1.  NS <= 32.
@@ -1536,26 +1598,7 @@ __device__ __forceinline__ void attn_merge_item(const float *part, int NS, int H
                 for (int r2 = 0; r2 < 4; ++r2) { o[2 * r2] += f[s0 + u] * v[u][r2].x; o[2 * r2 + 1] += f[s0 + u] * v[u][r2].y; }
         }
     }
-    // registers 8*hh .. 8*hh+7 of tile tt: octets q = 2*hh and 2*hh + 1 (see attn_write_frag)
-    const float inv = L > 0.f ? 1.f / L : 0.f;
-    const int KS = Hq * HD / 16;
-#pragma unroll
-    for (int qq = 0; qq < 2; ++qq) {
-        const int q = 2 * hh + qq;
-        float mine[4], other[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { mine[e] = o[4 * qq + e] * inv; other[e] = shx(mine[e], 32); }
-        if ((q & 1) == half) {
-            float v8[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { v8[e] = half ? other[e] : mine[e]; v8[4 + e] = half ? mine[e] : other[e]; }
-            uint4 hi, lo;
-            pack8_split(v8, hi, lo);
-            const size_t vec = (size_t)t * KS * 64 + frag_vec(qrow, head * (HD / 8) + tt * 4 + q);
-            st16<true>(xhi + vec, hi);
-            st16<true>(xlo + vec, lo);
-        }
-    }
+    attn_store_slice<HD>(o, L > 0.f ? 1.f / L : 0.f, Hq, head, t, tt, hh, lane, xhi, xlo);
 }
 
 // grid: one wave per (tile, head, O^T tile, half): 256 threads = 4 wave items per block
@@ -1567,6 +1610,308 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
     if (j >= n_items) return;
     const int hh = j & 1, tt = (j >> 1) % HT, head = (j / (2 * HT)) % Hq, t = j / (2 * HT * Hq);
     attn_merge_item<HD, true>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, tt, hh, threadIdx.x & 63);
+}
+
+// Merge of the NS key-range partials of one (tile, head) written by attn_head_item: wave item (tt, hh) owns registers
+// 8*hh .. 8*hh+7 of O^T tile tt, which a partial holds as two register quads of 1 KB per wave.  All (M, L) pairs and the
+// outputs of the first 8 ranges are requested together (one round trip for up to 8 ranges); ranges are combined in
+// order s = 0..NS-1.  NS <= 32.
+template <int HD>
+__device__ __forceinline__ void attn_head_merge(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
+                                                int head, int t, int tt, int hh, int lane) {
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    const int qrow = lane & 31;
+    const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
+    const float *po = p0 + ((tt * 2 + hh) * 2 * 64 + lane) * 4;
+    u32x4 v[8][2];
+    auto request = [&](int s0) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (s0 + u < NS) {
+                load16_agent_async(v[u][0], po + (size_t)(s0 + u) * PF);
+                load16_agent_async(v[u][1], po + (size_t)(s0 + u) * PF + 256);
+            }
+    };
+    float f[32];
+    float M = -INFINITY, L = 0.f;
+    {
+        float2 ml[32];
+#pragma unroll
+        for (int s = 0; s < 32; ++s) ml[s] = ld_agent2(p0 + (size_t)min(s, NS - 1) * PF + 32 * HD + 2 * qrow);
+        request(0);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) if (s < NS) M = fmaxf(M, ml[s].x);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            f[s] = (s >= NS || ml[s].x == -INFINITY) ? 0.f : exp2f((ml[s].x - M) * scale_log2e);
+            L += f[s] * ml[s].y;
+        }
+    }
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+    for (int s0 = 0; s0 < 32; s0 += 8) {
+        if (s0 < NS) {
+            if (s0 > 0) request(s0);
+            wait_loads<0>();
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < NS) {
+                    tie(v[u][0]); tie(v[u][1]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        o[e] += f[s0 + u] * __uint_as_float(v[u][0][e]);
+                        o[4 + e] += f[s0 + u] * __uint_as_float(v[u][1][e]);
+                    }
+                }
+        }
+    }
+    attn_store_slice<HD>(o, L > 0.f ? 1.f / L : 0.f, Hq, head, t, tt, hh, lane, xhi, xlo);
+}
+
+// ------------------------------------------------------------------------------------------
+// Block attention for passes of few row tiles (decoding: draft and verify passes of small batches), one
+// (row tile, query head, key range) item per workgroup.  Against k_attn + k_attn_merge this spreads a pass of
+// one tile over every compute unit with 8 key ranges instead of 32, so the partial results are a quarter as
+// large, and needs no second kernel: the last workgroup of a head to arrive merges the ranges itself.
+//  - All eight waves serve the same head; wave w takes the key tiles w, w + 8, ... of the range and keeps
+//    its own running (m, l, O).  No barrier inside the key loop: a wave's tiles are its own.
+//  - A wave has two key tiles on their way at any time: one lands in its private LDS slot (direct-to-LDS
+//    loads, no registers while they travel), the next one in registers; tiles alternate between the two.
+//  - Q (hi and lo planes of the head) is staged once in LDS and shared by the waves.
+//  - The eight running states are combined through LDS (every wave parks its O in its own slot, then wave
+//    (tt, hh) sums register group hh of O^T tile tt over the eight copies in wave order); with one key range
+//    the result is final, otherwise it is this range's partial and the ranges meet at an arrival counter.
+// The kv heads of the K/V cache are shared by the G query heads of a group through the L2 of their XCD:
+// workgroup ids cycle through the kv heads first, so with 8 kv heads every XCD serves one of them.
+// ------------------------------------------------------------------------------------------
+template <int HD>
+struct AttnHeadSmem {
+    uint4 slot[8][(HD / 8) * 64];   // per wave: one key tile (K k-step fragments, then V^T fragments); later its parked O
+    uint4 q[(HD / 8) * 64];         // Q fragments of the head: hi plane, then lo plane
+    float2 ml[8 * 64];              // parked (m, l) per wave and lane
+    int last;
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_head_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
+                                               const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
+                                               int b, int lim, float *part, int *counters, int Hq, int Hkv, int NS,
+                                               float scale_log2e, uint4 *xhi, uint4 *xlo, AttnHeadSmem<HD> &as, int head,
+                                               int split, int t) {
+    constexpr int HT = HD / 32, KSQ = HD / 16, FPT = KSQ + 2 * HT;   // fragments (1 KB each) per key tile
+    constexpr int PF = AttnPartial<HD>::FLOATS;
+    const int tidx = opaque_tid();
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;
+    const int half = lane >> 5, qrow = lane & 31;
+    int maxlim = lim, minlim = lim;
+#pragma unroll
+    for (int off = 1; off < 32; off <<= 1) {
+        maxlim = max(maxlim, shx(maxlim, off));
+        minlim = min(minlim, shx(minlim, off));
+    }
+    maxlim = __builtin_amdgcn_readfirstlane(maxlim);
+    minlim = __builtin_amdgcn_readfirstlane(minlim);
+    const int nkt = (maxlim + 31) >> 5;
+    const int per = (nkt + NS - 1) / opaque_s(NS);
+    const int kt0 = split * per, kt1 = min(nkt, kt0 + per);
+    const int first = kt0 + w;                                  // this wave's tiles: first, first + 8, ...
+    const int n = first < kt1 ? (kt1 - first + 7) >> 3 : 0;
+    const int kvh = head / (Hq / opaque_s(Hkv));
+    const uint16_t *Kp = Kc + (size_t)b * seq_stride + (size_t)kvh * head_stride;
+    const uint16_t *Vp = Vt + (size_t)b * seq_stride + (size_t)kvh * head_stride;
+    uint4 *myslot = as.slot[w];
+
+    // fragment f of key tile kt as this lane reads it: K k-step f, or V^T (O^T tile, key half) pair f - KSQ
+    auto frag_src = [&](int kt, int f) -> const uint16_t * {   // both caches hold a key tile as HD / 16 fragments of 1 KB
+        int lo8 = lane * 8;
+        asm volatile("" : "+v"(lo8));
+        if (f < KSQ) return Kp + (lo8 + kt * (32 * HD) + f * 512);
+        return Vp + (lo8 + kt * (32 * HD) + (f - KSQ) * 512);
+    };
+    auto issue_lds = [&](int kt) {
+#pragma unroll
+        for (int f = 0; f < FPT; ++f)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)frag_src(kt, f),
+                                             (void __attribute__((address_space(3))) *)(myslot + f * 64), 16, 0, 0);
+    };
+    u32x4 rf[FPT];   // the key tile that travels in registers
+    auto issue_reg = [&](int kt) {
+#pragma unroll
+        for (int f = 0; f < FPT; ++f) load16_async(rf[f], frag_src(kt, f));
+    };
+
+    // Q first (every later wait covers it), then this wave's first two key tiles
+    {
+        const size_t qb = ((size_t)(t * Hq + head) * KSQ) * 64 + lane;
+        for (int f = w; f < 2 * KSQ; f += 8) {
+            const uint4 *src = f < KSQ ? Qhi + qb + (size_t)f * 64 : Qlo + qb + (size_t)(f - KSQ) * 64;
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)src,
+                                             (void __attribute__((address_space(3))) *)(as.q + f * 64), 16, 0, 0);
+        }
+    }
+    if (n > 0) issue_lds(first);
+    if (n > 1) issue_reg(first + 8);
+    if (n > 1) wait_loads<2 * FPT>(); else if (n == 1) wait_loads<FPT>(); else wait_loads<0>();
+    barrier_keep_loads();   // Q of every wave's share is in LDS
+
+    f32x16 oacc[HT];
+#pragma unroll
+    for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[tt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const uint4 *qf = as.q + lane;
+
+    // one key tile: S^T = K Q^T, running softmax, O^T += V^T P^T; FROM_LDS: fragments from the slot, else from rf
+    auto tile = [&](auto from_lds, int kt) {
+        constexpr bool FROM_LDS = decltype(from_lds)::value;
+        const uint4 *fr = myslot + lane;
+        f32x16 sacc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSQ; ++s) {
+            const uint4 qh = qf[s * 64], ql = qf[(KSQ + s) * 64];
+            if (FROM_LDS) {
+                const uint4 kf = fr[s * 64];
+                sacc = mfma32(kf, qh, sacc);
+                sacc = mfma32(kf, ql, sacc);
+            } else {
+                sacc = mfma32(rf[s], qh, sacc);
+                sacc = mfma32(rf[s], ql, sacc);
+            }
+        }
+        const int key0 = kt * 32 + 16 * half;   // lane holds keys key0 + r, r = 0..15, for query row qrow
+        if (kt * 32 + 32 > minlim) {            // only tiles that reach some row's limit need the mask
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (key0 + r >= lim) sacc[r] = -INFINITY;
+        }
+        float mx = sacc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+        mx = fmaxf(mx, shx(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        float pr[16];
+        if (m_new == -INFINITY) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) pr[r] = 0.f;
+        } else {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);   // m_run = -inf -> 0
+            const float mb = m_new * scale_log2e;
+            float ls = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { pr[r] = __builtin_amdgcn_exp2f(sacc[r] * scale_log2e - mb); ls += pr[r]; }
+            l_run = l_run * alpha + ls;
+            m_run = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.f)) {   // the running max moved for some row
+#pragma unroll
+                for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[tt][r] *= alpha;
+            }
+        }
+        uint4 ph[2], pl[2];
+        pack8_split(pr, ph[0], pl[0]);
+        pack8_split(pr + 8, ph[1], pl[1]);
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                if (FROM_LDS) {
+                    const uint4 vf = fr[(KSQ + tt * 2 + s2) * 64];
+                    oacc[tt] = mfma32(vf, ph[s2], oacc[tt]);
+                    if (ATT_P_LO) oacc[tt] = mfma32(vf, pl[s2], oacc[tt]);
+                } else {
+                    oacc[tt] = mfma32(rf[KSQ + tt * 2 + s2], ph[s2], oacc[tt]);
+                    if (ATT_P_LO) oacc[tt] = mfma32(rf[KSQ + tt * 2 + s2], pl[s2], oacc[tt]);
+                }
+            }
+    };
+
+    // loads return in order: Q, tile 0 (LDS), tile 1 (registers), tile 2 (LDS, requested after tile 0 was used), ...
+    for (int i = 0; i < n; i += 2) {
+        if (i + 1 < n) wait_loads<FPT>(); else wait_loads<0>();
+        tile(std::true_type{}, first + 8 * i);
+        if (i + 2 < n) {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the slot has been read
+            issue_lds(first + 8 * (i + 2));
+        }
+        if (i + 1 < n) {
+            if (i + 2 < n) wait_loads<FPT>(); else wait_loads<0>();
+#pragma unroll
+            for (int f = 0; f < FPT; ++f) tie(rf[f]);
+            tile(std::false_type{}, first + 8 * (i + 1));
+            if (i + 3 < n) issue_reg(first + 8 * (i + 3));
+        }
+    }
+
+    // park (m, l) and O; the slot is this wave's own, its loads have landed and its reads are done
+    const float l_tot = l_run + shx(l_run, 32);
+    as.ml[w * 64 + lane] = make_float2(m_run, l_tot);
+    {
+        float4 *ox = (float4 *)myslot;
+#pragma unroll
+        for (int tt = 0; tt < HT; ++tt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                ox[(tt * 4 + q) * 64 + lane] = make_float4(oacc[tt][4 * q], oacc[tt][4 * q + 1], oacc[tt][4 * q + 2], oacc[tt][4 * q + 3]);
+    }
+    __syncthreads();
+    if (w < 2 * HT) {   // wave (tt, hh): registers 8*hh .. 8*hh+7 of O^T tile tt, summed over the waves in order
+        const int tt = w >> 1, hh = w & 1;
+        float2 ml[8];
+        float M = -INFINITY, L = 0.f, f[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { ml[u] = as.ml[u * 64 + lane]; M = fmaxf(M, ml[u].x); }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            f[u] = (ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ml[u].x - M) * scale_log2e);
+            L += f[u] * ml[u].y;
+        }
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float4 *ox = (const float4 *)as.slot[u];
+            const float4 a0 = ox[(tt * 4 + 2 * hh) * 64 + lane], a1 = ox[(tt * 4 + 2 * hh + 1) * 64 + lane];
+            o[0] += f[u] * a0.x; o[1] += f[u] * a0.y; o[2] += f[u] * a0.z; o[3] += f[u] * a0.w;
+            o[4] += f[u] * a1.x; o[5] += f[u] * a1.y; o[6] += f[u] * a1.z; o[7] += f[u] * a1.w;
+        }
+        if (NS == 1) {
+            attn_store_slice<HD>(o, L > 0.f ? 1.f / L : 0.f, Hq, head, t, tt, hh, lane, xhi, xlo);
+        } else {
+            // this range's partial: O as [(tt, hh)][register quad j][lane][4] (a wave writes 1 KB at a time), then
+            // (M, L)[32 rows]
+            float *pp = part + ((size_t)(t * Hq + head) * NS + split) * PF;
+            store16_agent(pp + (((tt * 2 + hh) * 2 + 0) * 64 + lane) * 4, o[0], o[1], o[2], o[3]);
+            store16_agent(pp + (((tt * 2 + hh) * 2 + 1) * 64 + lane) * 4, o[4], o[5], o[6], o[7]);
+            if (w == 0 && half == 0) st_agent2(pp + 32 * HD + 2 * qrow, M, L);
+        }
+    }
+    if (NS == 1) return;
+    // the key range that arrives last at the head's counter merges all of them
+    if (!arrive_last(counters + t * Hq + head, NS, &as.last)) return;
+    if (w < 2 * HT) attn_head_merge<HD>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, w >> 1, w & 1, lane);
+}
+
+// grid: x = kv_head + Hkv * (head in group + G * split), y = pass tile; 512 threads
+template <int HD>
+__global__ __launch_bounds__(512) void k_attn_head(const uint4 *__restrict__ Qhi, const uint4 *__restrict__ Qlo,
+                                                   const uint16_t *__restrict__ Kc, const uint16_t *__restrict__ Vt,
+                                                   size_t seq_stride, size_t head_stride,
+                                                   const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
+                                                   float *__restrict__ part, int *__restrict__ counters, int Hq, int Hkv,
+                                                   int NS, float scale_log2e, uint4 *__restrict__ xhi,
+                                                   uint4 *__restrict__ xlo) {
+    __shared__ __attribute__((aligned(16))) AttnHeadSmem<HD> as;
+    const int t = blockIdx.y;
+    const int G = Hq / Hkv, kvh = blockIdx.x % Hkv, r = blockIdx.x / Hkv;
+    attn_head_item<HD>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, tile_seq[t], row_limit[t * 32 + (threadIdx.x & 31)], part,
+                       counters, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, kvh * G + r % G, r / G, t);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1745,10 +2090,9 @@ __global__ void k_load_kv(const uint16_t *__restrict__ krows, const uint16_t *__
     const int slot = first + r;
     const size_t src = ((size_t)r * Hkv + head) * hd + oct * 8;
     const size_t base = (size_t)b * kv.seq_stride + (size_t)head * kv.head_stride;
-    *(uint4 *)(kv.k + base + (size_t)slot * hd + oct * 8) = *(const uint4 *)(krows + src);
+    *(uint4 *)(kv.k + base + k_cache_off(slot, oct, hd)) = *(const uint4 *)(krows + src);
 #pragma unroll
-    for (int e = 0; e < 8; ++e)
-        kv.vt[base + (size_t)(slot >> 5) * (hd * 32) + (size_t)(oct * 8 + e) * 32 + (slot & 31)] = vrows[src + e];
+    for (int e = 0; e < 8; ++e) kv.vt[base + v_cache_off(slot, oct * 8 + e, hd)] = vrows[src + e];
 }
 
 }  // namespace deer
