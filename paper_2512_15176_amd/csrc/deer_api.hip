@@ -41,7 +41,7 @@ constexpr int PREFILL_TILES_DENSE = 128, PREFILL_TILES_MOE = 16;
 int prefill_tiles(const deer_init_params &p) { return (p.target.n_experts || p.drafter.n_experts) ? PREFILL_TILES_MOE : PREFILL_TILES_DENSE; }
 constexpr int PART_TILES_MIN = 16;   // split-K partials exist for passes of up to max(2 * batch, 16) row tiles
 constexpr int MAX_NS = 32;          // key-range splits of block attention
-constexpr int ATT_HEAD_MAX_TILES = 4;   // per-head attention: most key tiles one wave may have to go through
+constexpr int ATT_HEAD_MAX_TILES = 12;   // per-head attention: most key tiles one wave may have to go through (equal or better up to 9, measured)
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
 size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
