@@ -360,6 +360,8 @@ def run_gemm_stamps(args):
                 eng.verify_block(k, 0.0, dr)
                 eng.accept_and_commit(k, 0.0, 0)
             st = eng.debug_gemm_stamps(model, -1)
+            st = st[: st.shape[0] // 2]               # the chosen launch (the second half holds the launch after it)
+            st = st[st[:, 0] > 0].astype(np.float64)   # the workgroups that ran
             rel = (st - st[:, 0].min()) * 0.01
             rel[st == 0] = np.nan
             med = lambda c: float(np.nanmedian(rel[:, c])) if np.any(~np.isnan(rel[:, c])) else float("nan")
