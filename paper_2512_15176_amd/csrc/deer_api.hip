@@ -41,6 +41,7 @@ constexpr int PREFILL_TILES_DENSE = 128, PREFILL_TILES_MOE = 16;
 int prefill_tiles(const deer_init_params &p) { return (p.target.n_experts || p.drafter.n_experts) ? PREFILL_TILES_MOE : PREFILL_TILES_DENSE; }
 constexpr int PART_TILES_MIN = 16;   // split-K partials exist for passes of up to max(2 * batch, 16) row tiles
 constexpr int MAX_NS = 32;          // key-range splits of block attention
+constexpr int NARROW_MAX_D = 1024;  // residual width up to which a dense model's O projection runs in 32-column workgroups
 constexpr int ATT_HEAD_MAX_TILES = 12;   // per-head attention: most key tiles one wave may have to go through (equal or better up to 9, measured)
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
@@ -49,6 +50,7 @@ size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 struct ModelRT {
     deer_model_cfg c{};
     int n_qkv = 0, kattn = 0, F = 0;   // fused QKV width, Hq*hd, FFN width used by GEMMs
+    int ssq_sub = 1;   // sums of squares of the residual stream per 128-column group (1) or per 32-column block (4)
     // weights (device)
     char *w = nullptr;
     size_t off_embed = 0, off_lm = 0, off_layers = 0, layer_bytes = 0;
@@ -192,6 +194,8 @@ void plan_model(ModelRT &m, const deer_model_cfg &c, int max_batch, int max_seq)
     m.n_qkv = (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     m.kattn = c.n_q_heads * c.head_dim;
     m.F = c.n_experts ? c.d_ff_expert : c.d_ff;
+    // a small dense model runs its unsplit residual GEMMs in 32-column workgroups (k_gemm_resid32)
+    m.ssq_sub = (!c.n_experts && c.d_model <= NARROW_MAX_D) ? 4 : 1;
     size_t d = c.d_model;
     m.off_embed = 0;
     m.off_lm = align_up((size_t)c.vocab * d * 2);
@@ -237,7 +241,7 @@ void plan_work(Work &w, const deer_init_params &p, char *base) {
     w.cs = (float2 *)take((size_t)MAXR * 64 * sizeof(float2));
     w.theta[0] = (double *)take(64 * 8); w.theta[1] = (double *)take(64 * 8);
     w.h = (float *)take((size_t)MAXR * dmax * 4);
-    w.ssq = (float *)take((size_t)MAXR * (dmax / CG) * 4);
+    w.ssq = (float *)take((size_t)MAXR * std::max<size_t>(dmax / CG, std::min<size_t>(dmax, NARROW_MAX_D) / 32) * 4);
     w.xa_hi = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024); w.xa_lo = (uint4 *)take((size_t)MAXT * (dmax / 16) * 1024);
     w.xb_hi = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024); w.xb_lo = (uint4 *)take((size_t)MAXT * (kb / 16) * 1024);
     w.q_hi = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024); w.q_lo = (uint4 *)take((size_t)MAXT * (kattn / 16) * 1024);
@@ -307,6 +311,17 @@ int choose_split(int N, int KS, int zgroups) {
     return std::max(S, 1);
 }
 
+// deer_debug_gemm_stamps: the chosen launch and the one after it record their workgroups' stamps, each in its half of
+// the buffer (zeroed at the start of the pass); null for every other launch or one with too many workgroups.
+unsigned long long *stamp_buffer(deer_ctx *c, size_t workgroups) {
+    const int stamp_rel = c->gemm_launch_idx - c->stamp_launch;
+    if (c->stamp_launch < 0 || c->cur_pass_model != c->stamp_model || (stamp_rel != 0 && stamp_rel != 1) ||
+        workgroups > (size_t)STAMP_MAX_BLOCKS / 2)
+        return nullptr;
+    c->stamp_blocks = STAMP_MAX_BLOCKS;
+    return c->wk.stamps + (size_t)stamp_rel * (STAMP_MAX_BLOCKS / 2) * 8;
+}
+
 template <int EPI>
 int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     a.KS = K / 16;
@@ -340,17 +355,26 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
             return DEER_OK;
         }
     }
+    if ((EPI == EPI_RESID || (EPI == EPI_QKV && a.hd <= 64 && 64 % a.hd == 0 && a.N % 64 == 0)) && a.ssq_sub == 4 && MT == 1 &&
+        force_S <= 0 && a.KS <= 64) {
+        // an unsplit GEMM of a small model: one workgroup per row tile and 32-column weight block (residual GEMM) or
+        // 64-column pair of blocks (QKV: whole heads)
+        a.S = 1; a.part = nullptr; a.counters = nullptr;
+        const int ngrp = EPI == EPI_RESID ? a.N / 32 : a.N / 64;
+        a.stamps = stamp_buffer(c, (size_t)ngrp * ntiles);
+        c->gemm_launch_idx++;
+        ProfScope ps(c, 0, (double)a.N * K * 2.0);
+        const dim3 g1((unsigned)(((ngrp + 7) / 8) * 8 * ntiles));
+        if (EPI == EPI_RESID) hipLaunchKernelGGL((k_gemm_narrow<1, EPI_RESID>), g1, dim3(512), 0, c->stream, a, ngrp, ntiles);
+        else hipLaunchKernelGGL((k_gemm_narrow<2, EPI_QKV>), g1, dim3(512), 0, c->stream, a, ngrp, ntiles);
+        LAUNCHCHK(c, "k_gemm_narrow");
+        return DEER_OK;
+    }
     a.S = force_S > 0 ? force_S : choose_split(a.N, a.KS, zg);
     while (a.S > 1 && (size_t)a.S * a.rows_total * a.N > c->wk.part_floats) --a.S;   // partials must fit their buffer
     a.part = (EPI == EPI_LMHEAD) ? nullptr : c->wk.part;
     a.counters = c->wk.gemm_cnt;
-    a.stamps = nullptr;
-    const int stamp_rel = c->gemm_launch_idx - c->stamp_launch;   // the chosen launch and the one after it record
-    if (c->stamp_launch >= 0 && c->cur_pass_model == c->stamp_model && (stamp_rel == 0 || stamp_rel == 1) &&
-        (size_t)(a.N / CG) * a.S * zg <= (size_t)STAMP_MAX_BLOCKS / 2) {
-        a.stamps = c->wk.stamps + (size_t)stamp_rel * (STAMP_MAX_BLOCKS / 2) * 8;   // zeroed at the start of the pass
-        c->stamp_blocks = STAMP_MAX_BLOCKS;
-    }
+    a.stamps = stamp_buffer(c, (size_t)(a.N / CG) * a.S * zg);
     c->gemm_launch_idx++;
     dim3 grid(a.N / CG, a.S, zg);
     ProfScope ps(c, 0, (double)a.N * K * 2.0);
@@ -405,7 +429,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     hipStream_t s = c->stream;
     if (c->stamp_launch >= 0 && model == c->stamp_model) (void)hipMemsetAsync(w.stamps, 0, (size_t)STAMP_MAX_BLOCKS * 64, s);
     hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
-                       w.xa_hi, w.xa_lo, w.ssq, d, ncg_d);
+                       w.xa_hi, w.xa_lo, w.ssq, d, ncg_d, m.ssq_sub);
     LAUNCHCHK(c, "k_embed");
     {
         int n = rows * (hd / 2);
@@ -431,7 +455,8 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     const double kv_bytes = kv_keys_total * mc.n_kv_heads * hd * 2.0 * 2.0;   // K and V rows read per layer
     GemmArgs base{};
     base.mt0 = 0; base.mt_stride = 1;
-    base.ssq_in = w.ssq; base.ncg_in = ncg_d; base.d_in = d; base.eps = mc.rms_eps;
+    base.ssq_in = w.ssq; base.ncg_in = ncg_d * m.ssq_sub; base.d_in = d; base.eps = mc.rms_eps;
+    base.ssq_sub = m.ssq_sub;
     base.cs = w.cs; base.rm = w.rm; base.qhi = w.q_hi; base.qlo = w.q_lo;
     base.Hq = mc.n_q_heads; base.Hkv = mc.n_kv_heads; base.hd = hd;
     base.h = w.h; base.xhi_out = w.xa_hi; base.xlo_out = w.xa_lo; base.ssq_out = w.ssq;

@@ -366,7 +366,7 @@ __device__ __forceinline__ void tile_to_frag(const float *tile, uint4 *xhi, uint
 // embedding gather: h[row] = E[tok[row]] (bf16 table), plus fragment planes and sum of squares
 __global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ tok,
                                                float *__restrict__ h, uint4 *__restrict__ xhi, uint4 *__restrict__ xlo,
-                                               float *__restrict__ ssq, int d, int ncg) {
+                                               float *__restrict__ ssq, int d, int ncg, int ssq_sub) {
     __shared__ float tile[32 * RED_STRIDE];
     int cg = blockIdx.x, t = blockIdx.y;
     for (int e = threadIdx.x; e < 32 * CG; e += 256) {
@@ -378,10 +378,12 @@ __global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, c
     }
     __syncthreads();
     tile_to_frag(tile, xhi, xlo, (size_t)t * (d / 16) * 64, cg * CG);
-    if (threadIdx.x < 32) {
+    // sums of squares per row and column group, or (ssq_sub == 4) per 32-column block of it
+    if (threadIdx.x < 32 * ssq_sub) {
+        const int row = threadIdx.x & 31, blk = threadIdx.x >> 5, wdt = CG / ssq_sub;
         float s = 0.f;
-        for (int c = 0; c < CG; ++c) { float v = tile[threadIdx.x * RED_STRIDE + c]; s += v * v; }
-        ssq[(size_t)(t * 32 + threadIdx.x) * ncg + cg] = s;
+        for (int c = 0; c < wdt; ++c) { float v = tile[row * RED_STRIDE + blk * wdt + c]; s += v * v; }
+        ssq[(size_t)(t * 32 + row) * (ncg * ssq_sub) + cg * ssq_sub + blk] = s;
     }
 }
 
@@ -439,6 +441,7 @@ struct GemmArgs {
     const float2 *cs; RowMeta rm; uint4 *qhi, *qlo; KvView kv; int Hq, Hkv, hd;
     // RESID: h += y, new fragments and sums of squares of h
     float *h; uint4 *xhi_out, *xlo_out; float *ssq_out;
+    int ssq_sub;   // 1: one sum of squares per row and 128-column group; 4: one per 32-column block (narrow launches)
     // SWIGLU: activation fragments over F channels
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
@@ -465,16 +468,19 @@ __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int gro
 }
 
 // QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
-template <bool COH>
+// The tile holds columns cg * WIDTH .. + WIDTH - 1 with row stride STRIDE.  WIDTH is a multiple of head_dim, so that
+// a head, and with it every rotation pair, lies inside one tile.
+template <bool COH, int WIDTH = CG, int STRIDE = RED_STRIDE>
 __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
     const int tidx = opaque_tid();
     const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
     const int half_hd = hd >> 1;
     const int b = a.rm.tile_seq[t];
-    for (int item = tidx; item < 512; item += 512) {   // GEMM workgroups have 512 threads
+    constexpr int RED_STRIDE = STRIDE;   // the row stride of this tile
+    for (int item = tidx; item < 4 * WIDTH; item += 512) {   // GEMM workgroups have 512 threads
         const int row = item & 31, oct = item >> 5;
         const int grow = t * 32 + row;
-        const int col0 = cg * CG + oct * 8;        // first of 8 columns, all in one head
+        const int col0 = cg * WIDTH + oct * 8;     // first of 8 columns, all in one head
         const int kind = col0 < Hq * hd ? 0 : (col0 < (Hq + Hkv) * hd ? 1 : 2);
         const int hc = col0 - (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd));
         const int head = hc / hd, i0 = hc % hd;
@@ -558,7 +564,13 @@ __device__ __forceinline__ void epi_resid(const GemmArgs &a, float *tile, float 
         if ((tidx & 63) < 32) scratch[(tidx >> 6) * 32 + row] = ss;   // [8 waves][32 rows]
     }
     __syncthreads();
-    if (tidx < 32) {
+    if (a.ssq_sub == 4) {   // wave w holds the octets 2w, 2w + 1: waves 2b, 2b + 1 make 32-column block b
+        if (tidx < 128) {
+            const int row = tidx & 31, blk = tidx >> 5;
+            stf<COH>(a.ssq_out + (size_t)(t * 32 + row) * (N / 32) + cg * 4 + blk,
+                     scratch[(2 * blk) * 32 + row] + scratch[(2 * blk + 1) * 32 + row]);
+        }
+    } else if (tidx < 32) {
         float s2 = 0.f;
 #pragma unroll
         for (int w = 0; w < 8; ++w) s2 += scratch[w * 32 + tidx];   // fixed order
@@ -956,6 +968,142 @@ __global__ __launch_bounds__(512) void k_gemm_rows(const GemmArgs a, int ncg, in
 // ------------------------------------------------------------------------------------------
 // mixture-of-experts FFN: (row, expert) pairs are grouped per expert, every touched expert's weights
 // are streamed once, and the 8 weighted expert outputs of a row are summed in routing order.
+// ------------------------------------------------------------------------------------------
+// Unsplit GEMMs of a small model in narrow workgroups: NB = 1 (32 columns) for the residual GEMM (O projection),
+// NB = 2 (64 columns: whole heads of up to 64 channels) for the QKV projection.
+// A 128-column workgroup pulls all of K for four weight blocks and both activation planes through one compute
+// unit's L1 (343 KB at K = 896, 64 bytes per clock), and a matrix of 896 columns gives only 7 of them per row
+// tile: the launch is bound by those few L1s, then by one SIMD's 112 products and a 128 KB sum through LDS.  Here a
+// workgroup owns NB 32-column weight blocks (171 KB through its L1 for one block, 28 products per SIMD, a 32 KB
+// sum), and four (two) times as many compute units take part.  Same operand layouts, same order of summation over
+// the waves (w = 0..7) and over a wave's k-steps (w, w + 8, ...) as in the wide kernel.
+// grid: 1-D, ids 8 apart on one XCD: the Z row tiles of column group p get the ids 8 * ((p / 8) * Z + z) + p % 8.
+// Sums of squares are written per 32-column block (GemmArgs::ssq_sub == 4 for every kernel of that model).
+// ------------------------------------------------------------------------------------------
+template <int NB>
+struct GemmNarrowSmem {
+    float red[8 * NB * 4 * 64 * 4];   // [wave][register quad][lane][4]
+    float tile[32 * (32 * NB + 1)];
+    float ssp[2 * 32];
+    float rstd[32];
+};
+
+template <int NB, int EPI>
+__global__ __launch_bounds__(512) void k_gemm_narrow(const GemmArgs a, int ngrp, int Z) {
+    static_assert((EPI == EPI_RESID && NB == 1) || (EPI == EPI_QKV && NB == 2), "epilogues exist for these two forms");
+    constexpr int TS = 32 * NB + 1;   // row stride of the tile in LDS
+    __shared__ GemmNarrowSmem<NB> sm;
+    const int lin = blockIdx.x, x8 = lin & 7, q8 = lin >> 3;
+    const int z = q8 % Z, p = 8 * (q8 / Z) + x8;
+    if (p >= ngrp) return;
+    const int tidx = opaque_tid();
+    const int w = __builtin_amdgcn_readfirstlane(tidx >> 6), lane = tidx & 63;
+    const int N = a.N, KS = a.KS;
+    const int t = a.mt0 + z * a.mt_stride;
+    const int slin = z * ngrp + p;   // stamps: 0 start, 1 this wave's k-steps multiplied, 2 epilogue done
+    gemm_stamp(a, slin, 0);
+    const uint4 *wp = a.W + (size_t)(p * NB) * KS * 64 + lane;
+    const size_t wstride = (size_t)KS * 64;   // between column blocks
+    const uint4 *xh = a.Xhi + (size_t)t * KS * 64 + lane, *xl = a.Xlo + (size_t)t * KS * 64 + lane;
+    constexpr int D = NB == 1 ? 8 : 7;   // k-steps of loads in flight per wave (K = 896: all seven of a wave at once)
+    uint4 wb[D][NB], xhb[D], xlb[D];
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd) {
+        const int ks = w + 8 * dd;
+        if (ks < KS) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)ks * 64];
+            xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
+        }
+    }
+    float hreg[2];   // RESID: old h of this thread's elements e = tidx + 512 i: row e >> 5, column e & 31
+    if (EPI == EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int e = tidx + 512 * i;
+            hreg[i] = a.h[(size_t)(t * 32 + (e >> 5)) * N + p * 32 + (e & 31)];
+        }
+    } else {   // RMSNorm factors of the input rows, requested behind the first operands
+        tile_rstd<false>(a.ssq_in, sm.rstd, t * 32, a.ncg_in, a.d_in, a.eps);
+    }
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
+    for (int kb = w; kb < KS; kb += 8 * D) {
+#pragma unroll
+        for (int dd = 0; dd < D; ++dd) {
+            const int ks = kb + 8 * dd;
+            if (ks < KS) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    acc[nb] = mfma32(xhb[dd], wb[dd][nb], acc[nb]);
+                    acc[nb] = mfma32(xlb[dd], wb[dd][nb], acc[nb]);
+                }
+                const int kn = ks + 8 * D;
+                if (kn < KS) {
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) wb[dd][nb] = wp[nb * wstride + (size_t)kn * 64];
+                    xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
+                }
+            }
+        }
+    }
+    gemm_stamp(a, slin, 1);
+    // sum of the 8 waves in the order w = 0..7: wave s < 4 NB sums register quad s & 3 of block s >> 2 and writes
+    // its rows 8 q + 4 half + 0..3
+    float4 *red4 = (float4 *)sm.red;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            red4[(w * 4 * NB + nb * 4 + q) * 64 + lane] = make_float4(acc[nb][4 * q], acc[nb][4 * q + 1], acc[nb][4 * q + 2], acc[nb][4 * q + 3]);
+    __syncthreads();
+    if (w < 4 * NB) {
+        float4 sum = red4[w * 64 + lane];
+#pragma unroll
+        for (int ww = 1; ww < 8; ++ww) {
+            const float4 v = red4[(ww * 4 * NB + w) * 64 + lane];
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        float *tp = sm.tile + (8 * (w & 3) + 4 * (lane >> 5)) * TS + (w >> 2) * 32 + (lane & 31);
+        tp[0] = sum.x; tp[TS] = sum.y; tp[2 * TS] = sum.z; tp[3 * TS] = sum.w;
+    }
+    __syncthreads();
+    if (EPI == EPI_QKV) {
+        epi_qkv<false, 32 * NB, TS>(a, sm.tile, sm.rstd, p, t);
+    } else {
+        // h += y; new fragment planes of h; sums of squares of the block's 32 columns
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int e = tidx + 512 * i;
+            const int row = e >> 5, col = e & 31;
+            const float v = hreg[i] + sm.tile[row * TS + col];
+            a.h[(size_t)(t * 32 + row) * N + p * 32 + col] = v;
+            sm.tile[row * TS + col] = v;
+        }
+        __syncthreads();
+        if (tidx < 128) {   // (row, octet) items: wave 0 has octets 0 and 1, wave 1 octets 2 and 3
+            const int row = tidx & 31, oct = tidx >> 5;
+            const float *tp = sm.tile + row * TS + oct * 8;
+            uint4 hi, lo;
+            pack8_split(tp, hi, lo);
+            const size_t v = (size_t)t * (N / 16) * 64 + frag_vec(row, p * 4 + oct);
+            a.xhi_out[v] = hi;
+            a.xlo_out[v] = lo;
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += tp[e] * tp[e];
+            ss += shx(ss, 32);
+            if ((tidx & 63) < 32) sm.ssp[(tidx >> 6) * 32 + row] = ss;
+        }
+        __syncthreads();
+        if (tidx < 32) a.ssq_out[(size_t)(t * 32 + tidx) * (N / 32) + p] = sm.ssp[tidx] + sm.ssp[32 + tidx];
+    }
+    gemm_stamp(a, slin, 2);
+}
+
 // ------------------------------------------------------------------------------------------
 // one block: cnt[e], and for pair i of expert e the pass row and its routing slot
 __global__ __launch_bounds__(256) void k_moe_group(const int *__restrict__ route_e, const int *__restrict__ row_slot,
@@ -1614,8 +1762,8 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float *__restrict__ pa
 
 // Merge of the NS key-range partials of one (tile, head) written by attn_head_item: wave item (tt, hh) owns registers
 // 8*hh .. 8*hh+7 of O^T tile tt, which a partial holds as two register quads of 1 KB per wave.  All (M, L) pairs and the
-// outputs of the first 8 ranges are requested together (one round trip for up to 8 ranges); ranges are combined in
-// order s = 0..NS-1.  NS <= 32.
+// outputs of the first 8 ranges (16 with head_dim <= 64) are requested together: one round trip for that many ranges;
+// ranges are combined in order s = 0..NS-1.  NS <= 32.
 template <int HD>
 __device__ __forceinline__ void attn_head_merge(const float *part, int NS, int Hq, float scale_log2e, uint4 *xhi, uint4 *xlo,
                                                 int head, int t, int tt, int hh, int lane) {
@@ -1623,10 +1771,11 @@ __device__ __forceinline__ void attn_head_merge(const float *part, int NS, int H
     const int qrow = lane & 31;
     const float *p0 = part + (size_t)(t * Hq + head) * NS * PF;
     const float *po = p0 + ((tt * 2 + hh) * 2 * 64 + lane) * 4;
-    u32x4 v[8][2];
+    constexpr int CH = HD <= 64 ? 16 : 8;   // ranges whose outputs are requested together (registers: 8 per range)
+    u32x4 v[CH][2];
     auto request = [&](int s0) {
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
+        for (int u = 0; u < CH; ++u)
             if (s0 + u < NS) {
                 load16_agent_async(v[u][0], po + (size_t)(s0 + u) * PF);
                 load16_agent_async(v[u][1], po + (size_t)(s0 + u) * PF + 256);
@@ -1651,12 +1800,12 @@ __device__ __forceinline__ void attn_head_merge(const float *part, int NS, int H
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
 #pragma unroll
-    for (int s0 = 0; s0 < 32; s0 += 8) {
+    for (int s0 = 0; s0 < 32; s0 += CH) {
         if (s0 < NS) {
             if (s0 > 0) request(s0);
             wait_loads<0>();
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
+            for (int u = 0; u < CH; ++u)
                 if (s0 + u < NS) {
                     tie(v[u][0]); tie(v[u][1]);
 #pragma unroll
