@@ -178,6 +178,7 @@ const char *check_model(const deer_model_cfg &c) {
     if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128) return "head_dim must be 32, 64 or 128";
     if (c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
     if (c.d_model % CG) return "d_model must be a multiple of 128";
+    if (c.d_model > 8192) return "d_model above 8192 is not supported (64 column groups of sums of squares per row)";
     if (((c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim) % CG) return "fused QKV width must be a multiple of 128";
     if ((c.n_q_heads * c.head_dim) % 16) return "n_q_heads*head_dim must be a multiple of 16";
     if (c.vocab % CG) return "vocab must be a multiple of 128";

@@ -90,8 +90,19 @@ __device__ __forceinline__ uint4 ld16_stream(const uint4 *p) {
 // load at a loop header): the load is issued here and its result may only be read after wait_loads<N>()
 // (at most N younger loads still outstanding; loads return in order) followed by tie() on the register.
 __device__ __forceinline__ void load16_async(u32x4 &dst, const void *p) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
 }
+// the same, marked non-temporal (data read once per pass: weights)
+__device__ __forceinline__ void load16_stream_async(u32x4 &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off nt" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void load4_async(float &dst, const void *p) {
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void tie(float &r) { asm volatile("" : "+v"(r)); }
+// at most `steps` x PER loads may still be outstanding (steps <= 4)
+template <int PER>
+__device__ __forceinline__ void wait_steps(int steps);
 // The same with agent scope: the load is served by memory, not by an L2 that may hold an older copy of a line
 // another XCD has written since.
 __device__ __forceinline__ void load16_agent_async(u32x4 &dst, const void *p) {
@@ -106,6 +117,15 @@ __device__ __forceinline__ void store16_agent(void *p, float a, float b, float c
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+template <int PER>
+__device__ __forceinline__ void wait_steps(int steps) {
+    static_assert(4 * PER <= 63, "the counter has six bits");
+    if (steps <= 0) wait_loads<0>();
+    else if (steps == 1) wait_loads<PER>();
+    else if (steps == 2) wait_loads<2 * PER>();
+    else if (steps == 3) wait_loads<3 * PER>();
+    else wait_loads<4 * PER>();
+}
 __device__ __forceinline__ void tie(u32x4 &r) { asm volatile("" : "+v"(r)); }
 
 // Workgroup barrier for loops that keep direct-to-LDS loads in flight across it: __syncthreads() waits for every
@@ -865,38 +885,70 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
         xl[mt] = a.Xlo + tl * KS * 64 + lane;
     }
 
-    // Software pipeline: D k-steps of loads are in flight while older steps are multiplied.
-    constexpr int D = (MT == 1) ? 4 : 3;   // bounded by the register file: no spills
-    uint4 wb[D][4], xhb[D][MT], xlb[D][MT];
-#pragma unroll
-    for (int dd = 0; dd < D; ++dd) {
-        int ks = ks0 + KSTEP * dd;
-        if (ks < ks1) {
-#pragma unroll
-            for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)ks * 64) : wp[nb * wstride + (size_t)ks * 64];
-        }
-    }
-#pragma unroll
-    for (int dd = 0; dd < D; ++dd) {
-        int ks = ks0 + KSTEP * dd;
-        if (ks < ks1) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)ks * 64]; xlb[dd][mt] = xl[mt][(size_t)ks * 64]; }
-        }
-    }
+    // Software pipeline: D k-steps of loads are in flight while older steps are multiplied.  The loads are issued and
+    // waited for by hand (load16_async / wait_steps): left to the compiler, the loop waits for ALL outstanding loads once
+    // per trip (its count of conditional loads across the back edge is not exact), which empties the pipeline every D
+    // k-steps (8B verify pass 4.35 -> 4.26 ms).
+    constexpr int D = (MT == 1) ? 4 : 3;   // bounded by the register file: no spills.  (Deeper, 5 or 6 k-steps, or the
+    // loads of k-step j + D requested before the products of k-step j through one more buffer: measured, not faster.)
+    constexpr int NSLOT = D;
+    constexpr int LPS = 4 + 2 * MT;        // loads per k-step
+    u32x4 wb[NSLOT][4], xhb[NSLOT][MT], xlb[NSLOT][MT];
+    const int n = ks0 < ks1 ? (ks1 - ks0 + KSTEP - 1) / KSTEP : 0;   // this wave's k-steps: ks0, ks0 + 8, ...
     // RMSNorm factors of the input rows: their sums of squares were finished by the previous kernel, so they are
-    // requested now, behind the first activations, instead of as a dependent round trip inside the epilogue
+    // requested first and turned into factors once the first k-step has arrived, instead of as a dependent round
+    // trip inside the epilogue.  Thread (row, j) = (tidx >> 4, tidx & 15) holds the groups j, j + 16, ...
     constexpr bool RSTD_EARLY = EPI != EPI_RESID;
+    constexpr int RSQ = 4;                 // groups per thread: ncg_in <= 64 (the host checks d_model <= 8192)
+    float sq[MT][RSQ];
+    const int nsq = RSTD_EARLY ? (a.ncg_in + 15) >> 4 : 0;
     if (RSTD_EARLY) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-            tile_rstd<COH>(a.ssq_in, s_rstd + 32 * mt, (a.mt0 + (z * MT + mt) * a.mt_stride) * 32, a.ncg_in, a.d_in, a.eps);
-    }
-    for (int kb = ks0; kb < ks1; kb += KSTEP * D) {
+        for (int mt = 0; mt < MT; ++mt) {
+            const float *sp = a.ssq_in + (size_t)((a.mt0 + (z * MT + mt) * a.mt_stride) * 32 + (tidx >> 4)) * a.ncg_in;
 #pragma unroll
-        for (int dd = 0; dd < D; ++dd) {
-            int ks = kb + KSTEP * dd;
-            if (ks < ks1) {
+            for (int i = 0; i < RSQ; ++i)
+                if (i < nsq) load4_async(sq[mt][i], sp + min((tidx & 15) + 16 * i, a.ncg_in - 1));
+        }
+    }
+    auto request = [&](int sl, int ks) {   // sl is a constant once the callers' loops are unrolled
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            if (WSTREAM) load16_stream_async(wb[sl][nb], wp + nb * wstride + (size_t)ks * 64);
+            else load16_async(wb[sl][nb], wp + nb * wstride + (size_t)ks * 64);
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            load16_async(xhb[sl][mt], xh[mt] + (size_t)ks * 64);
+            load16_async(xlb[sl][mt], xl[mt] + (size_t)ks * 64);
+        }
+    };
+#pragma unroll
+    for (int dd = 0; dd < D; ++dd)
+        if (dd < n) request(dd, ks0 + KSTEP * dd);
+    for (int j0 = 0; j0 < n; j0 += NSLOT) {
+#pragma unroll
+        for (int dd = 0; dd < NSLOT; ++dd) {
+            const int j = j0 + dd;
+            if (j < n) {
+                // loads requested after those of k-step j: the k-steps up to j + D - 1
+                wait_steps<LPS>(min(D - 1, n - 1 - j));
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) tie(wb[dd][nb]);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) { tie(xhb[dd][mt]); tie(xlb[dd][mt]); }
+                if (RSTD_EARLY && j == 0) {   // the sums of squares were requested before every k-step: they are here
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        float ssum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < RSQ; ++i)
+                            if (i < nsq) { tie(sq[mt][i]); if ((tidx & 15) + 16 * i < a.ncg_in) ssum += sq[mt][i]; }
+#pragma unroll
+                        for (int off = 1; off < 16; off <<= 1) ssum += shx(ssum, off);
+                        if ((tidx & 15) == 0) s_rstd[32 * mt + (tidx >> 4)] = rsqrtf(ssum / (float)a.d_in + a.eps);
+                    }
+                }
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -904,14 +956,21 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
                         acc[mt][nb] = mfma32(xhb[dd][mt], wb[dd][nb], acc[mt][nb]);
                         acc[mt][nb] = mfma32(xlb[dd][mt], wb[dd][nb], acc[mt][nb]);
                     }
-                int kn = ks + KSTEP * D;
-                if (kn < ks1) {
-#pragma unroll
-                    for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = WSTREAM ? ld16_stream(wp + nb * wstride + (size_t)kn * 64) : wp[nb * wstride + (size_t)kn * 64];
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) { xhb[dd][mt] = xh[mt][(size_t)kn * 64]; xlb[dd][mt] = xl[mt][(size_t)kn * 64]; }
-                }
+                if (j + D < n) request(dd, ks0 + KSTEP * (j + D));
             }
+        }
+    }
+    if (RSTD_EARLY && n == 0) {   // a wave without k-steps (short K ranges) still owes its rows' factors
+        wait_loads<0>();
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float ssum = 0.f;
+#pragma unroll
+            for (int i = 0; i < RSQ; ++i)
+                if (i < nsq) { tie(sq[mt][i]); if ((tidx & 15) + 16 * i < a.ncg_in) ssum += sq[mt][i]; }
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) ssum += shx(ssum, off);
+            if ((tidx & 15) == 0) s_rstd[32 * mt + (tidx >> 4)] = rsqrtf(ssum / (float)a.d_in + a.eps);
         }
     }
 
@@ -1193,20 +1252,22 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
         xh = a.Xhi + off; xl = a.Xlo + off;
     }
     const bool live = myrow >= 0;
-    const uint4 z4 = make_uint4(0u, 0u, 0u, 0u);
-    constexpr int D = 4;
-    uint4 wb[D][4], xhb[D], xlb[D];
+    const u32x4 z4 = {0u, 0u, 0u, 0u};
+    // D k-steps of loads in flight, issued and waited for by hand (see gemm_block)
+    constexpr int D = 4, LPS = 6;
+    u32x4 wb[D][4], xhb[D], xlb[D];
+    const int nst = max(0, ks1 - ks0);   // this wave's k-steps
+    auto request = [&](int sl, const uint4 *wp, int ks) {   // sl is a constant once the callers' loops are unrolled
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) load16_stream_async(wb[sl][nb], wp + nb * wstride + (size_t)ks * 64);
+        load16_async(xhb[sl], xh + (size_t)ks * 64);
+        load16_async(xlb[sl], xl + (size_t)ks * 64);
+    };
     auto first_loads = [&](int cg) {
         const uint4 *wp = a.W + (size_t)ex * a.wexp_stride + ((size_t)(cg * 4) * KS) * 64 + lane;
 #pragma unroll
-        for (int dd = 0; dd < D; ++dd) {
-            int ks = ks0 + dd;
-            if (ks < ks1) {
-#pragma unroll
-                for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)ks * 64);
-                xhb[dd] = xh[(size_t)ks * 64]; xlb[dd] = xl[(size_t)ks * 64];
-            }
-        }
+        for (int dd = 0; dd < D; ++dd)
+            if (dd < nst) request(dd, wp, ks0 + dd);
     };
     const int cg_first = blockIdx.x * MOE_CGS;
     first_loads(cg_first);
@@ -1220,23 +1281,22 @@ __global__ __launch_bounds__(512) void k_gemm_moe(const MoeArgs a) {
         for (int nb = 0; nb < 4; ++nb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nb][r] = 0.f;
-        for (int kb = ks0; kb < ks1; kb += D) {
+        for (int j0 = 0; j0 < nst; j0 += D) {
 #pragma unroll
             for (int dd = 0; dd < D; ++dd) {
-                int ks = kb + dd;
-                if (ks < ks1) {
-                    const uint4 ah = live ? xhb[dd] : z4, al = live ? xlb[dd] : z4;
+                const int j = j0 + dd;
+                if (j < nst) {
+                    wait_steps<LPS>(min(D - 1, nst - 1 - j));   // the k-steps requested after step j
+#pragma unroll
+                    for (int nb = 0; nb < 4; ++nb) tie(wb[dd][nb]);
+                    tie(xhb[dd]); tie(xlb[dd]);
+                    const u32x4 ah = live ? xhb[dd] : z4, al = live ? xlb[dd] : z4;
 #pragma unroll
                     for (int nb = 0; nb < 4; ++nb) {
                         acc[nb] = mfma32(ah, wb[dd][nb], acc[nb]);
                         acc[nb] = mfma32(al, wb[dd][nb], acc[nb]);
                     }
-                    int kn = ks + D;
-                    if (kn < ks1) {
-#pragma unroll
-                        for (int nb = 0; nb < 4; ++nb) wb[dd][nb] = ld16_stream(wp + nb * wstride + (size_t)kn * 64);
-                        xhb[dd] = xh[(size_t)kn * 64]; xlb[dd] = xl[(size_t)kn * 64];
-                    }
+                    if (j + D < nst) request(dd, wp, ks0 + j + D);
                 }
             }
         }
