@@ -390,7 +390,9 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
     return DEER_OK;
 }
 
-struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; int k_lo = 0; };
+// draw: the pass samples its rows' tokens (Gumbel-max over the perturbed logits): the drafter's pass at T > 0; the target's
+// rows only need the maximum and the sum of exponentials
+struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; int k_lo = 0; bool draw = false; };
 
 template <int HD>
 int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_head, float scale_log2e, double kv_bytes) {
@@ -420,7 +422,10 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_h
 }
 
 // One forward pass of `model` over the rows described by the row metadata (ntiles tiles).
-int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total = 0.0) {
+// rows: the pass's rows are described by a PassRows (draft, verify): one launch works them out, gathers the embeddings
+// and fills the RoPE table; null: the row metadata is in place already (prefill).
+int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm, double kv_keys_total = 0.0,
+             const PassRows *rows_desc = nullptr) {
     ModelRT &m = c->m[model];
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
@@ -429,10 +434,14 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     c->cur_pass_model = model;
     hipStream_t s = c->stream;
     if (c->stamp_launch >= 0 && model == c->stamp_model) (void)hipMemsetAsync(w.stamps, 0, (size_t)STAMP_MAX_BLOCKS * 64, s);
-    hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
-                       w.xa_hi, w.xa_lo, w.ssq, d, ncg_d, m.ssq_sub);
-    LAUNCHCHK(c, "k_embed");
-    {
+    if (rows_desc) {
+        hipLaunchKernelGGL(k_pass_begin, dim3(ncg_d + 1, ntiles), dim3(256), 0, s, *rows_desc, w.rm, (const uint16_t *)(m.w + m.off_embed),
+                           w.h, w.xa_hi, w.xa_lo, w.ssq, d, ncg_d, m.ssq_sub, m.theta, w.cs, hd / 2);
+        LAUNCHCHK(c, "k_pass_begin");
+    } else {
+        hipLaunchKernelGGL(k_embed, dim3(ncg_d, ntiles), dim3(256), 0, s, (const uint16_t *)(m.w + m.off_embed), w.rm.tok, w.h,
+                           w.xa_hi, w.xa_lo, w.ssq, d, ncg_d, m.ssq_sub);
+        LAUNCHCHK(c, "k_embed");
         int n = rows * (hd / 2);
         hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, s, w.rm.pos, m.theta, w.cs, hd / 2, rows);
         LAUNCHCHK(c, "k_rope_table");
@@ -527,7 +536,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         GemmArgs a = base;
         a.W = (const uint4 *)(m.w + m.off_lm); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = V;
         a.mt0 = lm.mt0; a.mt_stride = lm.mt_stride;
-        a.k = lm.k; a.k_lo = lm.k_lo; a.T = lm.T; a.seed = lm.seed; a.stat = w.stat; a.ncg_v = V / CG;
+        a.k = lm.k; a.k_lo = lm.k_lo; a.T = lm.T; a.seed = lm.seed; a.draw = lm.draw ? 1 : 0; a.stat = w.stat; a.ncg_v = V / CG;
         a.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
         int rc = launch_gemm<EPI_LMHEAD>(c, a, d, lm.n_tiles, 1);
         if (rc) return rc;
@@ -784,11 +793,11 @@ int deer_draft_block_multipass(deer_ctx *c, int32_t k, float T, uint64_t seed, i
         const int lo = (k * (s - 1) + n_passes - 1) / n_passes, hi = (k * s + n_passes - 1) / n_passes;
         if (hi == lo) continue;
         const int tps = any_ing ? 2 : 1;
-        hipLaunchKernelGGL(k_rows_draft, dim3(B), dim3(64), 0, c->stream, w.st, w.rm, k, c->p.mask_token_id, tps, c->p.drafter.vocab,
-                           draft_dev, lo);
-        LAUNCHCHK(c, "k_rows_draft");
-        LmPlan lm{true, 0, tps, B, k, T, seed, lo};
-        int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm, keys);
+        PassRows pr{};
+        pr.draft_pass = 1; pr.st = w.st; pr.tokens = draft_dev; pr.k = k; pr.nrows = 0; pr.vocab = c->p.drafter.vocab;
+        pr.mask_id = c->p.mask_token_id; pr.tiles_per_seq = tps; pr.n_fixed = lo;
+        LmPlan lm{true, 0, tps, B, k, T, seed, lo, T > 0.f};
+        int rc = run_pass(c, DEER_DRAFTER, B * tps, maxlim, lm, keys, &pr);
         if (rc) return rc;
         hipLaunchKernelGGL(k_draft_finish, dim3(B), dim3(32), 0, c->stream, w.st, w.res[DEER_DRAFTER], draft_dev, k, lo);
         LAUNCHCHK(c, "k_draft_finish");
@@ -815,12 +824,13 @@ int deer_verify_block(deer_ctx *c, int32_t k, float T, const int32_t *draft_dev)
     int maxlim = 0;
     for (int b = 0; b < B; ++b) maxlim = std::max(maxlim, c->h_len[b] - 1 + nrows);
     Work &w = c->wk;
-    hipLaunchKernelGGL(k_rows_verify, dim3(B), dim3(32), 0, c->stream, w.st, w.rm, draft_dev, k, nrows, c->p.target.vocab);
-    LAUNCHCHK(c, "k_rows_verify");
+    PassRows pr{};
+    pr.draft_pass = 0; pr.st = w.st; pr.tokens = draft_dev; pr.k = k; pr.nrows = nrows; pr.vocab = c->p.target.vocab;
+    pr.tiles_per_seq = 1;
     LmPlan lm{true, 0, 1, B, nrows, T, 0};
     double keys = 0;
     for (int b = 0; b < B; ++b) keys += c->h_len[b] - 1 + nrows;
-    int rc = run_pass(c, DEER_TARGET, B, maxlim, lm, keys);
+    int rc = run_pass(c, DEER_TARGET, B, maxlim, lm, keys, &pr);
     if (rc) return rc;
     c->wk_draft = draft_dev;
     c->state = ST_VERIFIED;

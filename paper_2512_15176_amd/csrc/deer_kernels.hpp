@@ -8,9 +8,8 @@
 //     (hi, lo) with x ~= hi + lo in bf16, so that products against bf16 weights are exact to
 //     ~2^-17 and accumulate in fp32.
 //   * residual stream h: fp32 row-major [rows][d_model].
-//   * K cache [layer][seq][kv_head][slot][head_dim] bf16;  V cache transposed
-//     [layer][seq][kv_head][head_dim][slot] bf16, so that both attention contractions read
-//     contraction-contiguous 16-byte vectors.
+//   * K and V caches [layer][seq][kv_head] in blocks of 32 slots, each block in the fragment order of the
+//     attention contractions (see k_cache_off / v_cache_off), bf16.
 //   * a pass works on row tiles of 32; every tile belongs to one sequence; unused rows have
 //     limit 0 and slot -1.
 #pragma once
@@ -304,44 +303,44 @@ struct RowMeta {        // device arrays over the rows of a pass
 // token ids that reach the embedding gather are forced into [0, vocab): drafts come from caller memory
 __device__ __forceinline__ int safe_tok(int t, int vocab) { return (t < 0 || t >= vocab) ? 0 : t; }
 
-__global__ void k_rows_verify(SeqState st, RowMeta rm, const int *__restrict__ draft, int k, int nrows, int vocab) {
-    int b = blockIdx.x, i = threadIdx.x;
-    int row = b * 32 + i;
-    int j = st.len[b];
-    if (i == 0) rm.tile_seq[b] = b;
-    if (i < nrows) {
-        int p = j - 1 + i;
-        rm.tok[row] = safe_tok((i == 0) ? st.pending[b] : draft[b * k + i - 1], vocab);
-        rm.pos[row] = p;
-        rm.slot[row] = p;
-        rm.limit[row] = p + 1;
-    } else {
-        rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
-    }
-}
+// Rows of a verify or draft pass (Alg. 1: one pass per model and iteration).
+//   verify: tile b = sequence b, nrows rows [x_j, y^_1 .. ]: row i at position j - 1 + i, causal over the cache.
+//   draft: sequence b has tiles_per_seq tiles; tile 0 = k MASK rows at positions j..j+k-1 (they see the cache, the
+//   ingested rows and every MASK row; their K,V land in slots past the cached length and are never kept); tile 1 = the
+//   m not-yet-cached committed tokens, causal.  The first n_fixed block rows hold the tokens fixed[b][0 .. n_fixed)
+//   instead of the MASK id (a partially filled block: a later pass of a multi-pass draft).
+struct PassRows {
+    int draft_pass;                  // 0: verify, 1: draft
+    SeqState st;
+    const int *tokens;               // verify: the draft tokens [B][k]; draft: the fixed tokens [B][k] (n_fixed > 0)
+    int k, nrows, vocab;             // nrows: verify rows per sequence
+    int mask_id, tiles_per_seq, n_fixed;
+};
+struct RowDesc { int tok, pos, slot, limit; };
 
-// draft rows of sequence b: tile 2b = k MASK rows at positions j..j+k-1 (see cache + ingested rows +
-// every MASK row; their K,V land in slots past the cached length and are never kept); tile 2b+1 =
-// the m not-yet-cached committed tokens, causal.  With tiles_per_seq == 1 only the MASK tile exists.
-// The first n_fixed block rows hold the tokens fixed[b][0 .. n_fixed) instead of the MASK id (a partially filled
-// block: a later pass of a multi-pass draft).
-__global__ void k_rows_draft(SeqState st, RowMeta rm, int k, int mask_id, int tiles_per_seq, int vocab,
-                             const int *__restrict__ fixed, int n_fixed) {
-    int b = blockIdx.x, i = threadIdx.x;   // 64 threads
-    int t = i >> 5, r = i & 31;
-    if (t >= tiles_per_seq) return;
-    int tile = b * tiles_per_seq + t;
-    int row = tile * 32 + r;
-    int j = st.len[b], dl = st.dr_len[b], m = st.ing_n[b];
-    if (r == 0) rm.tile_seq[tile] = b;
-    if (t == 0 && r < k) {
-        rm.tok[row] = r < n_fixed ? safe_tok(fixed[b * k + r], vocab) : mask_id;
-        rm.pos[row] = j + r; rm.slot[row] = j + r; rm.limit[row] = j + k;
-    } else if (t == 1 && r < m) {
-        rm.tok[row] = safe_tok(st.ing_tok[b * 32 + r], vocab); rm.pos[row] = dl + r; rm.slot[row] = dl + r; rm.limit[row] = dl + r + 1;
+__device__ __forceinline__ RowDesc pass_row(const PassRows &p, int tile, int r, int &b) {
+    RowDesc d{0, 0, -1, 0};
+    if (!p.draft_pass) {
+        b = tile;
+        if (r < p.nrows) {
+            const int pos = p.st.len[b] - 1 + r;
+            d.tok = safe_tok(r == 0 ? p.st.pending[b] : p.tokens[b * p.k + r - 1], p.vocab);
+            d.pos = pos; d.slot = pos; d.limit = pos + 1;
+        }
     } else {
-        rm.tok[row] = 0; rm.pos[row] = 0; rm.slot[row] = -1; rm.limit[row] = 0;
+        b = tile / p.tiles_per_seq;
+        const int t = tile - b * p.tiles_per_seq;
+        if (t == 0 && r < p.k) {
+            const int j = p.st.len[b];
+            d.tok = r < p.n_fixed ? safe_tok(p.tokens[b * p.k + r], p.vocab) : p.mask_id;
+            d.pos = j + r; d.slot = j + r; d.limit = j + p.k;
+        } else if (t == 1 && r < p.st.ing_n[b]) {
+            const int dl = p.st.dr_len[b];
+            d.tok = safe_tok(p.st.ing_tok[b * 32 + r], p.vocab);
+            d.pos = dl + r; d.slot = dl + r; d.limit = dl + r + 1;
+        }
     }
+    return d;
 }
 
 // prefill pass: tile t holds desc[t].z rows of sequence desc[t].x, causal, at positions desc[t].y + r, whose token
@@ -383,16 +382,15 @@ __device__ __forceinline__ void tile_to_frag(const float *tile, uint4 *xhi, uint
     }
 }
 
-// embedding gather: h[row] = E[tok[row]] (bf16 table), plus fragment planes and sum of squares
-__global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ tok,
-                                               float *__restrict__ h, uint4 *__restrict__ xhi, uint4 *__restrict__ xlo,
-                                               float *__restrict__ ssq, int d, int ncg, int ssq_sub) {
-    __shared__ float tile[32 * RED_STRIDE];
-    int cg = blockIdx.x, t = blockIdx.y;
+// embedding gather of one (column group, tile): h[row] = E[tok[row]] (bf16 table), plus fragment planes and sums of
+// squares; tok: the tile's 32 token ids (global memory or LDS); 256 threads
+__device__ __forceinline__ void embed_tile(float *tile, const uint16_t *__restrict__ E, const int *tok, float *__restrict__ h,
+                                           uint4 *__restrict__ xhi, uint4 *__restrict__ xlo, float *__restrict__ ssq, int d,
+                                           int ncg, int ssq_sub, int cg, int t) {
     for (int e = threadIdx.x; e < 32 * CG; e += 256) {
         int row = e >> 7, col = e & 127;
         int grow = t * 32 + row;
-        float v = bf2f(E[(size_t)tok[grow] * d + cg * CG + col]);
+        float v = bf2f(E[(size_t)tok[row] * d + cg * CG + col]);
         tile[row * RED_STRIDE + col] = v;
         h[(size_t)grow * d + cg * CG + col] = v;
     }
@@ -404,6 +402,46 @@ __global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, c
         float s = 0.f;
         for (int c = 0; c < wdt; ++c) { float v = tile[row * RED_STRIDE + blk * wdt + c]; s += v * v; }
         ssq[(size_t)(t * 32 + row) * (ncg * ssq_sub) + cg * ssq_sub + blk] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_embed(const uint16_t *__restrict__ E, const int *__restrict__ tok,
+                                               float *__restrict__ h, uint4 *__restrict__ xhi, uint4 *__restrict__ xlo,
+                                               float *__restrict__ ssq, int d, int ncg, int ssq_sub) {
+    __shared__ float tile[32 * RED_STRIDE];
+    embed_tile(tile, E, tok + blockIdx.y * 32, h, xhi, xlo, ssq, d, ncg, ssq_sub, blockIdx.x, blockIdx.y);
+}
+
+// The start of a draft or verify pass in one launch: every block works out its tile's rows (pass_row), then blocks
+// x < ncg gather the embeddings of column group x, block x == ncg writes the row metadata and the tile's RoPE table.
+// (Three launches of a few microseconds each left the GPU waiting for the host at the start of every pass.)
+__global__ __launch_bounds__(256) void k_pass_begin(PassRows p, RowMeta rm, const uint16_t *__restrict__ E, float *__restrict__ h,
+                                                    uint4 *__restrict__ xhi, uint4 *__restrict__ xlo, float *__restrict__ ssq,
+                                                    int d, int ncg, int ssq_sub, const double *__restrict__ theta,
+                                                    float2 *__restrict__ cs, int half) {
+    __shared__ float tile[32 * RED_STRIDE];
+    __shared__ int s_tok[32], s_pos[32];
+    const int t = blockIdx.y;
+    if (threadIdx.x < 32) {
+        int b;
+        const RowDesc r = pass_row(p, t, threadIdx.x, b);
+        s_tok[threadIdx.x] = r.tok; s_pos[threadIdx.x] = r.pos;
+        if (blockIdx.x == ncg) {
+            const int row = t * 32 + threadIdx.x;
+            rm.tok[row] = r.tok; rm.pos[row] = r.pos; rm.slot[row] = r.slot; rm.limit[row] = r.limit;
+            if (threadIdx.x == 0) rm.tile_seq[t] = b;
+        }
+    }
+    __syncthreads();
+    if (blockIdx.x < ncg) {
+        embed_tile(tile, E, s_tok, h, xhi, xlo, ssq, d, ncg, ssq_sub, blockIdx.x, t);
+    } else {
+        for (int idx = threadIdx.x; idx < 32 * half; idx += 256) {
+            const int row = idx / half, i = idx - row * half;
+            double sn, c;
+            sincos((double)s_pos[row] * theta[i], &sn, &c);
+            cs[(size_t)(t * 32 + row) * half + i] = make_float2((float)c, (float)sn);
+        }
     }
 }
 
@@ -466,6 +504,7 @@ struct GemmArgs {
     uint4 *ahi, *alo; int F;
     // LMHEAD: logits, per-group row statistics
     int k; float *logits; float T; uint64_t seed; RowStat *stat; int ncg_v;
+    int draw;   // T > 0: also the Gumbel-max of the perturbed logits (a pass that samples its rows' tokens)
     unsigned long long *stamps;   // debugging: [workgroup][8] device-clock stamps of this launch, or null
     int k_lo;   // rows below k_lo keep the logits and statistics of an earlier pass (multi-pass draft)
     // ROUTER: top-k of softmax over n_experts (<= 128), renormalised
@@ -643,12 +682,13 @@ __device__ __forceinline__ void epi_lmhead(const GemmArgs &a, const float *tile,
             for (int e = 0; e < 16; e += 4) *(float4 *)(q + e) = make_float4(z[e], z[e + 1], z[e + 2], z[e + 3]);
         }
         uint64_t key = 0;
-        if (T > 0.f) key = row_key(a.seed, TAG_DRAFT, (uint64_t)a.rm.tile_seq[t], (uint64_t)a.rm.pos[t * 32 + row]);
+        const bool draw = T > 0.f && a.draw;
+        if (draw) key = row_key(a.seed, TAG_DRAFT, (uint64_t)a.rm.tile_seq[t], (uint64_t)a.rm.pos[t * 32 + row]);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             int v = cg * CG + sub * 16 + e;
             argmax_merge(m, idx, z[e], v);
-            if (T > 0.f) argmax_merge(gm, gidx, z[e] * invT + gumbel(key, (uint64_t)v), v);
+            if (draw) argmax_merge(gm, gidx, z[e] * invT + gumbel(key, (uint64_t)v), v);
         }
     }
 #pragma unroll
@@ -1493,7 +1533,7 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
 }
 
 // ------------------------------------------------------------------------------------------
-// Block attention item for a whole workgroup of 8 waves (both launch modes use it).
+// Block attention item for a whole workgroup of 8 waves: passes of many row tiles or long key ranges (k_attn).
 //  - one (row tile, kv head, key-range split) item per workgroup; wave w serves query head (w & 3) of the
 //    GQA group on the key tiles of parity (w >> 2) of each staged chunk, so two waves per SIMD overlap;
 //  - the K and V fragments of a chunk of ATT_CH 32-key tiles are requested by the eight waves together (every
@@ -1503,9 +1543,7 @@ __device__ __forceinline__ void attn_write_frag(const f32x16 *o, float inv, int 
 //  - Q fragments stay in registers, loaded by every wave for its own head;
 //  - the two key parities of a head are combined through LDS, then the result goes to the output
 //    projection's input (NS == 1) or to an un-normalised partial (M, L, O) for the merge.
-// Partials and outputs are written with agent-scope stores, so the item serves the persistent kernel
-// (consumers in the same kernel) and the per-operation path alike.  b: the tile's sequence; lim: the key
-// limit of this lane's query row.
+// b: the tile's sequence; lim: the key limit of this lane's query row.
 // ------------------------------------------------------------------------------------------
 #ifndef DEER_ATT_P_LO
 #define DEER_ATT_P_LO 1
@@ -1518,9 +1556,8 @@ struct AttnSmem {
     float2 ml[4 * 64];                       // parked (m, l) of the odd-parity waves
 };
 
-// FRAGS_EARLY (the attention kernel; the pass kernel has no registers to spare for it): all K fragments of a tile
-// are requested from LDS before the first product and the V fragments before the softmax, so the matrix pipe
-// does not wait for one LDS read per two products.
+// FRAGS_EARLY: all K fragments of a tile are requested from LDS before the first product and the V fragments
+// before the softmax, so the matrix pipe does not wait for one LDS read per two products.
 template <int HD, bool FRAGS_EARLY = false>
 __device__ __forceinline__ void attn_item(const uint4 *Qhi, const uint4 *Qlo, const uint16_t *__restrict__ Kc,
                                           const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
