@@ -42,6 +42,8 @@ int prefill_tiles(const deer_init_params &p) { return (p.target.n_experts || p.d
 constexpr int PART_TILES_MIN = 16;   // split-K partials exist for passes of up to max(2 * batch, 16) row tiles
 constexpr int MAX_NS = 32;          // key-range splits of block attention
 constexpr int NARROW_MAX_D = 1024;  // residual width up to which a dense model's O projection runs in 32-column workgroups
+constexpr int NEXT_SPAN_BYTES = 16 << 10;      // fetched ahead per 32-column block of a next-launch workgroup (4 blocks: 8 loads per thread)
+constexpr int KV_FETCH_MAX_BYTES = 1 << 20;    // fetched ahead per kv head of K and of V^T: a share of one XCD's 4 MB L2
 constexpr int ATT_HEAD_MAX_TILES = 12;   // per-head attention: most key tiles one wave may have to go through (equal or better up to 9, measured)
 constexpr size_t PART_COLS = 131072; // fp32 columns of split-K partials per row (S * N <= PART_COLS)
 
@@ -395,7 +397,8 @@ int launch_gemm(deer_ctx *c, GemmArgs &a, int K, int ntiles, int force_S) {
 struct LmPlan { bool on; int mt0, mt_stride, n_tiles, k; float T; uint64_t seed; int k_lo = 0; bool draw = false; };
 
 template <int HD>
-int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_head, float scale_log2e, double kv_bytes) {
+int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_head, float scale_log2e, double kv_bytes,
+                const NextWeights &nx) {
     Work &w = c->wk;
     const deer_model_cfg &mc = m.c;
     const uint16_t *K = m.kv + m.kv_k_base + (size_t)layer * m.kv_layer_stride;
@@ -404,7 +407,7 @@ int launch_attn(deer_ctx *c, ModelRT &m, int layer, int ntiles, int NS, int NS_h
     if (NS_head > 0) {   // few tiles: one workgroup per (tile, query head, key range), merged by the last to arrive
         hipLaunchKernelGGL(k_attn_head<HD>, dim3(mc.n_q_heads * NS_head, ntiles), dim3(512), 0, c->stream, w.q_hi, w.q_lo, K, Vt,
                            m.kv_seq_stride, m.kv_head_stride, w.rm.tile_seq, w.rm.limit, w.opart, w.attn_cnt,
-                           mc.n_q_heads, mc.n_kv_heads, NS_head, scale_log2e, w.xb_hi, w.xb_lo);
+                           mc.n_q_heads, mc.n_kv_heads, NS_head, scale_log2e, w.xb_hi, w.xb_lo, nx);
         LAUNCHCHK(c, "k_attn_head");
         return DEER_OK;
     }
@@ -471,17 +474,39 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     base.Hq = mc.n_q_heads; base.Hkv = mc.n_kv_heads; base.hd = hd;
     base.h = w.h; base.xhi_out = w.xa_hi; base.xlo_out = w.xa_lo; base.ssq_out = w.ssq;
     base.ahi = w.xb_hi; base.alo = w.xb_lo; base.F = m.F;
+    // What the idle workgroups of a split launch pull into their XCD's L2 for the launch after it (passes of one row
+    // tile, wide workgroups): the first k-steps of every workgroup of the next GEMM — attention fetches for the output
+    // projection, the down projection for the next layer's QKV projection — and, from the QKV projection, the old K,V
+    // blocks of the kv head its XCD serves in the per-head attention launch.  Measured (8B target, prefix 4096): verify
+    // pass 4.29 -> 4.21 ms; more than 16 KB per 32-column block, or fetching from unsplit launches (after their
+    // epilogue) or for gate/up, costs more than it saves.
+    const bool fetch_ahead = ntiles == 1 && m.ssq_sub == 1;
+    auto next_plan = [&](const char *W, int N, int K) {
+        NextWeights nx{};
+        if (!fetch_ahead) return nx;
+        const int KS = K / 16;
+        int S = choose_split(N, KS, 1);
+        while (S > 1 && (size_t)S * 32 * N > c->wk.part_floats) --S;
+        const int per = (KS + S * 8 - 1) / (S * 8);
+        nx.base = W; nx.ncg = N / CG; nx.nwg = nx.ncg * S; nx.span = NEXT_SPAN_BYTES;
+        nx.block_bytes = (long long)KS * 1024; nx.split_bytes = (long long)8 * per * 1024;
+        return nx;
+    };
     for (int l = 0; l < mc.n_layers; ++l) {
         const char *lw = m.w + m.off_layers + (size_t)l * m.layer_bytes;
         GemmArgs a = base;
         a.W = (const uint4 *)(lw + m.lo_qkv); a.Xhi = w.xa_hi; a.Xlo = w.xa_lo; a.N = m.n_qkv;
         a.kv = KvView{m.kv + m.kv_k_base + (size_t)l * m.kv_layer_stride, m.kv + m.kv_v_base + (size_t)l * m.kv_layer_stride,
                       m.kv_seq_stride, m.kv_head_stride, c->p.max_seq};
+        // whole key tiles that no row of this pass writes (a pass of one tile appends at most 32 rows)
+        if (fetch_ahead && NS_head > 0 && c->batch == 1 && 8 % mc.n_kv_heads == 0)
+            a.kv_fetch_bytes = std::min(KV_FETCH_MAX_BYTES, std::max(0, (max_limit - 32) / 32) * 32 * hd * 2);
         int rc = launch_gemm<EPI_QKV>(c, a, d, ntiles, 0);
         if (rc) return rc;
-        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
-        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
-        else rc = launch_attn<32>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes);
+        const NextWeights nx_o = next_plan(lw + m.lo_o, d, m.kattn);
+        if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
+        else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
+        else rc = launch_attn<32>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
         if (rc) return rc;
         a = base;
         a.W = (const uint4 *)(lw + m.lo_o); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
@@ -494,6 +519,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             if (rc) return rc;
             a = base;
             a.W = (const uint4 *)(lw + m.lo_d); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
+            if (l + 1 < mc.n_layers) a.nx = next_plan(lw + m.layer_bytes + m.lo_qkv, m.n_qkv, d);
             rc = launch_gemm<EPI_RESID>(c, a, m.F, ntiles, 0);
             if (rc) return rc;
         } else {

@@ -99,6 +99,13 @@ __device__ __forceinline__ void load4_async(float &dst, const void *p) {
     asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
 }
 __device__ __forceinline__ void tie(float &r) { asm volatile("" : "+v"(r)); }
+// A load whose data nobody wants (it pulls a line into the L2).  `sink` is read and written by every such statement,
+// so the register stays reserved from its initialisation to the tie() behind the final wait: a write-only
+// destination is dead in the compiler's eyes right after the statement, and the register would be handed to the next
+// address computation while the load is still on its way.
+__device__ __forceinline__ void load16_discard(u32x4 &sink, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
+}
 // at most `steps` x PER loads may still be outstanding (steps <= 4)
 template <int PER>
 __device__ __forceinline__ void wait_steps(int steps);
@@ -489,7 +496,62 @@ struct RowStat {   // per (row, column group) partial over 128 vocabulary entrie
     float gm; int gidx;      // max of z/T + Gumbel, its index (T > 0)
 };
 
+// What the NEXT launch of the stream will read first, for workgroups of this launch that have nothing left to do:
+// they pull it into their XCD's L2 while the launch's last workgroups finish (memory is idle then), so that the next
+// launch's first k-steps hit there.  Workgroup ids 8 apart share an XCD in both launches; next-launch workgroup j works
+// on column group j % ncg and K split j / ncg (k_gemm's grid order).
+struct NextWeights {
+    const char *base;          // the next launch's weight matrix, fragment layout; null: nothing to fetch
+    int nwg, ncg;              // its workgroups and column groups
+    int span;                  // bytes fetched per 32-column block, from the start of the split's K range
+    long long block_bytes;     // one 32-column block: KS * 1024
+    long long split_bytes;     // a split's K range within a block
+};
+
+__device__ __forceinline__ void prefetch_next(const NextWeights &nx) {
+    if (!nx.base) return;
+    // one next-launch workgroup per workgroup and no more: what is fetched must be back before this launch can end
+    const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int tid = opaque_tid();
+    u32x4 sink = {0u, 0u, 0u, 0u};
+    tie(sink);
+    if (lin < nx.nwg) {
+        const int j = lin;
+        const int cg = j % nx.ncg, sp = j / nx.ncg;
+        const long long s_off = sp * nx.split_bytes;
+        const int len = (int)min((long long)nx.span, nx.block_bytes - s_off);   // stays inside the block
+        const char *p0 = nx.base + (long long)cg * 4 * nx.block_bytes + s_off + tid * 16;
+        for (int nb = 0; nb < 4; ++nb)
+            for (int o = tid * 16; o < len; o += 512 * 16) load16_discard(sink, p0 + nb * nx.block_bytes + (o - tid * 16));
+    }
+    wait_loads<0>();
+    tie(sink);
+}
+
+// The same for the per-head attention launch that follows a QKV projection: its workgroups on XCD x work on kv head
+// x % Hkv (Hkv divides 8; one sequence), so this launch's idle workgroups on XCD x pull that head's old K and V^T blocks
+// — whole key tiles that this launch does not write — into its L2.
+__device__ __forceinline__ void prefetch_kv(const uint16_t *k, const uint16_t *vt, size_t head_stride, int Hkv, int bytes) {
+    if (bytes <= 0) return;
+    const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int nlin = gridDim.x * gridDim.y * gridDim.z;
+    const int per_x = (nlin - (lin & 7) + 7) >> 3;
+    const int tid = opaque_tid();
+    const size_t head = (size_t)((lin & 7) % Hkv) * head_stride;
+    const char *kb = (const char *)(k + head), *vb = (const char *)(vt + head);
+    u32x4 sink = {0u, 0u, 0u, 0u};
+    tie(sink);
+    for (int o = ((lin >> 3) * 512 + tid) * 16; o < bytes; o += per_x * 8192) {   // the host bounds `bytes`: a few trips
+        load16_discard(sink, kb + o);
+        load16_discard(sink, vb + o);
+    }
+    wait_loads<0>();
+    tie(sink);
+}
+
 struct GemmArgs {
+    NextWeights nx;
+    int kv_fetch_bytes;   // QKV launch before a per-head attention launch over one sequence: bytes of each kv head's K (and V^T) blocks to pull in, or 0
     const uint4 *W, *Xhi, *Xlo;
     float *part; int *counters;
     int N, KS, S, mt0, mt_stride, rows_total;
@@ -529,12 +591,15 @@ __device__ __forceinline__ void tile_rstd(const float *ssq, float *rstd, int gro
 // QKV epilogue: RMSNorm scale, RoPE, Q -> fragment planes per head, K -> cache, V -> transposed cache
 // The tile holds columns cg * WIDTH .. + WIDTH - 1 with row stride STRIDE.  WIDTH is a multiple of head_dim, so that
 // a head, and with it every rotation pair, lies inside one tile.
-template <bool COH, int WIDTH = CG, int STRIDE = RED_STRIDE>
-__device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t) {
+// pre (optional): what qkv_prefetch loaded for this thread's item while the tile was still being summed.
+constexpr int QKV_PRE = 18;   // 8 (cos, sin) pairs, the row's cache slot, the tile's sequence
+template <bool COH, int WIDTH = CG, int STRIDE = RED_STRIDE, bool PRE = false>
+__device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, const float *rstd, int cg, int t,
+                                        const float (&pre)[QKV_PRE]) {
     const int tidx = opaque_tid();
     const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv;
     const int half_hd = hd >> 1;
-    const int b = a.rm.tile_seq[t];
+    const int b = PRE ? __float_as_int(pre[17]) : a.rm.tile_seq[t];
     constexpr int RED_STRIDE = STRIDE;   // the row stride of this tile
     for (int item = tidx; item < 4 * WIDTH; item += 512) {   // GEMM workgroups have 512 threads
         const int row = item & 31, oct = item >> 5;
@@ -551,7 +616,7 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
             for (int e = 0; e < 8; ++e) {
                 float x = tile[row * RED_STRIDE + oct * 8 + e] * sc;
                 float xp = tile[row * RED_STRIDE + oct * 8 + e + poff] * sc;
-                float2 c = a.cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
+                const float2 c = PRE ? make_float2(pre[2 * e], pre[2 * e + 1]) : a.cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
                 v[e] = (i0 < half_hd) ? x * c.x - xp * c.y : x * c.x + xp * c.y;
             }
         } else {
@@ -565,7 +630,7 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
             st16<COH>(a.qhi + vec, hi);
             st16<COH>(a.qlo + vec, lo);
         } else {
-            const int slot = a.rm.slot[grow];
+            const int slot = PRE ? __float_as_int(pre[16]) : a.rm.slot[grow];
             if (slot >= 0) {
                 size_t base = (size_t)b * a.kv.seq_stride + (size_t)head * a.kv.head_stride;
                 if (kind == 1) {
@@ -578,6 +643,31 @@ __device__ __forceinline__ void epi_qkv(const GemmArgs &a, const float *tile, co
             }
         }
     }
+}
+
+// The QKV epilogue's own inputs (RoPE factors, cache slot, sequence) of this thread's item, requested before the
+// tile is ready so that they are not one more round trip behind it.  One item per thread: WIDTH <= 128.
+template <int WIDTH = CG>
+__device__ __forceinline__ void qkv_prefetch(const GemmArgs &a, float (&pre)[QKV_PRE], int cg, int t) {
+    const int item = opaque_tid();
+#pragma unroll
+    for (int i = 0; i < QKV_PRE; ++i) pre[i] = 0.f;
+    if (item >= 4 * WIDTH) return;
+    const int hd = a.hd, Hq = a.Hq, Hkv = a.Hkv, half_hd = hd >> 1;
+    const int row = item & 31, oct = item >> 5, grow = t * 32 + row;
+    const int col0 = cg * WIDTH + oct * 8;
+    const int kind = col0 < Hq * hd ? 0 : (col0 < (Hq + Hkv) * hd ? 1 : 2);
+    const int hc = col0 - (kind == 0 ? 0 : (kind == 1 ? Hq * hd : (Hq + Hkv) * hd));
+    const int i0 = hc % hd;
+    if (kind < 2) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float2 c = a.cs[(size_t)grow * half_hd + ((i0 + e) % half_hd)];
+            pre[2 * e] = c.x; pre[2 * e + 1] = c.y;
+        }
+    }
+    if (kind >= 1) pre[16] = __int_as_float(a.rm.slot[grow]);
+    pre[17] = __int_as_float(a.rm.tile_seq[t]);
 }
 
 // O-proj / down-proj epilogue: h += y; new fragment planes of h; per-group sum of squares.
@@ -777,7 +867,11 @@ __device__ __forceinline__ void run_epilogue(const GemmArgs &a, float *tile, flo
         tile_rstd<COH>(a.ssq_in, rstd, t * 32, a.ncg_in, a.d_in, a.eps);
         __syncthreads();
     }
-    if (EPI == EPI_QKV) epi_qkv<COH>(a, tile, rstd, cg, t);
+    if (EPI == EPI_QKV) {
+        // the wide workgroups load the epilogue's inputs here: requesting them ahead of the tile measured slower
+        const float none[QKV_PRE] = {};
+        epi_qkv<COH>(a, tile, rstd, cg, t, none);
+    }
     else if (EPI == EPI_RESID) epi_resid<COH>(a, tile, scratch, hreg, cg, t);
     else if (EPI == EPI_SWIGLU) epi_swiglu<COH>(a, tile, rstd, cg, t);
     else if (EPI == EPI_ROUTER) epi_router(a, tile, rstd, t);
@@ -1041,7 +1135,11 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     // the block that arrives last at this column group's counter sums all partials and finishes
     const bool last = arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last);
     gemm_stamp(a, lin, 3);
-    if (!last) return;
+    if (!last) {
+        if (EPI == EPI_QKV) prefetch_kv(a.kv.k, a.kv.vt, a.kv.head_stride, a.Hkv, a.kv_fetch_bytes);
+        else prefetch_next(a.nx);
+        return;
+    }
     gemm_finish<MT, EPI, COH, RSTD_EARLY>(a, sm, cg, z);
     gemm_stamp(a, lin, 4);
 }
@@ -1149,6 +1247,8 @@ __global__ __launch_bounds__(512) void k_gemm_narrow(const GemmArgs a, int ngrp,
             }
         }
     }
+    float qpre[QKV_PRE];
+    if (EPI == EPI_QKV) qkv_prefetch<32 * NB>(a, qpre, p, t);
     gemm_stamp(a, slin, 1);
     // sum of the 8 waves in the order w = 0..7: wave s < 4 NB sums register quad s & 3 of block s >> 2 and writes
     // its rows 8 q + 4 half + 0..3
@@ -1171,7 +1271,7 @@ __global__ __launch_bounds__(512) void k_gemm_narrow(const GemmArgs a, int ngrp,
     }
     __syncthreads();
     if (EPI == EPI_QKV) {
-        epi_qkv<false, 32 * NB, TS>(a, sm.tile, sm.rstd, p, t);
+        epi_qkv<false, 32 * NB, TS, true>(a, sm.tile, sm.rstd, p, t, qpre);
     } else {
         // h += y; new fragment planes of h; sums of squares of the block's 32 columns
 #pragma unroll
@@ -1945,7 +2045,7 @@ __device__ __forceinline__ void attn_head_item(const uint4 *Qhi, const uint4 *Ql
                                                const uint16_t *__restrict__ Vt, size_t seq_stride, size_t head_stride,
                                                int b, int lim, float *part, int *counters, int Hq, int Hkv, int NS,
                                                float scale_log2e, uint4 *xhi, uint4 *xlo, AttnHeadSmem<HD> &as, int head,
-                                               int split, int t) {
+                                               int split, int t, const NextWeights &nx) {
     constexpr int HT = HD / 32, KSQ = HD / 16, FPT = KSQ + 2 * HT;   // fragments (1 KB each) per key tile
     constexpr int PF = AttnPartial<HD>::FLOATS;
     const int tidx = opaque_tid();
@@ -2140,7 +2240,7 @@ __device__ __forceinline__ void attn_head_item(const uint4 *Qhi, const uint4 *Ql
     }
     if (NS == 1) return;
     // the key range that arrives last at the head's counter merges all of them
-    if (!arrive_last(counters + t * Hq + head, NS, &as.last)) return;
+    if (!arrive_last(counters + t * Hq + head, NS, &as.last)) { prefetch_next(nx); return; }
     if (w < 2 * HT) attn_head_merge<HD>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, w >> 1, w & 1, lane);
 }
 
@@ -2152,12 +2252,12 @@ __global__ __launch_bounds__(512) void k_attn_head(const uint4 *__restrict__ Qhi
                                                    const int *__restrict__ tile_seq, const int *__restrict__ row_limit,
                                                    float *__restrict__ part, int *__restrict__ counters, int Hq, int Hkv,
                                                    int NS, float scale_log2e, uint4 *__restrict__ xhi,
-                                                   uint4 *__restrict__ xlo) {
+                                                   uint4 *__restrict__ xlo, const NextWeights nx) {
     __shared__ __attribute__((aligned(16))) AttnHeadSmem<HD> as;
     const int t = blockIdx.y;
     const int G = Hq / Hkv, kvh = blockIdx.x % Hkv, r = blockIdx.x / Hkv;
     attn_head_item<HD>(Qhi, Qlo, Kc, Vt, seq_stride, head_stride, tile_seq[t], row_limit[t * 32 + (threadIdx.x & 31)], part,
-                       counters, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, kvh * G + r % G, r / G, t);
+                       counters, Hq, Hkv, NS, scale_log2e, xhi, xlo, as, kvh * G + r % G, r / G, t, nx);
 }
 
 // ------------------------------------------------------------------------------------------
