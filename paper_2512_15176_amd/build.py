@@ -37,5 +37,19 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def device_assembly(out_path: str) -> str:
+    """The gfx950 assembly of the device code, as text (same flags as the library): for checks on the generated code."""
+    cmd = [
+        hipcc_path(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG_DIR, "csrc"),
+        "--cuda-device-only", "-S", "-o", out_path, *SOURCES,
+    ]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
+    return out_path
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

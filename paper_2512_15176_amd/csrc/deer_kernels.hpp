@@ -104,7 +104,7 @@ __device__ __forceinline__ void tie(float &r) { asm volatile("" : "+v"(r)); }
 // destination is dead in the compiler's eyes right after the statement, and the register would be handed to the next
 // address computation while the load is still on its way.
 __device__ __forceinline__ void load16_discard(u32x4 &sink, const void *p) {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "+v"(sink) : "v"(p) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, off ; discard" : "+v"(sink) : "v"(p) : "memory");
 }
 // at most `steps` x PER loads may still be outstanding (steps <= 4)
 template <int PER>
