@@ -480,7 +480,19 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     // blocks of the kv head its XCD serves in the per-head attention launch.  Measured (8B target, prefix 4096): verify
     // pass 4.29 -> 4.21 ms; more than 16 KB per 32-column block, or fetching from unsplit launches (after their
     // epilogue) or for gate/up, costs more than it saves.
+    // A small dense model (narrow workgroups for its unsplit O and QKV projections, one or two row tiles): attention
+    // fetches the output projection's 32-column blocks whole, the split down projection the next layer's QKV blocks.
     const bool fetch_ahead = ntiles == 1 && m.ssq_sub == 1;
+    const bool fetch_ahead_narrow = ntiles <= 2 && m.ssq_sub == 4 && !mc.n_experts;
+    auto next_plan_narrow = [&](const char *W, int N, int K, int NB) {   // NB: 1 residual GEMM, 2 QKV (whole heads)
+        NextWeights nx{};
+        const int KS = K / 16;
+        if (!fetch_ahead_narrow || KS > 64 || N % (32 * NB)) return nx;
+        if (NB == 2 && !(hd <= 64 && 64 % hd == 0)) return nx;
+        nx.base = W; nx.ncg = N / (32 * NB); nx.nwg = ((nx.ncg + 7) / 8) * 8 * ntiles;
+        nx.block_bytes = (long long)KS * 1024; nx.narrow_nb = NB; nx.Z = ntiles;
+        return nx;
+    };
     auto next_plan = [&](const char *W, int N, int K) {
         NextWeights nx{};
         if (!fetch_ahead) return nx;
@@ -503,7 +515,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             a.kv_fetch_bytes = std::min(KV_FETCH_MAX_BYTES, std::max(0, (max_limit - 32) / 32) * 32 * hd * 2);
         int rc = launch_gemm<EPI_QKV>(c, a, d, ntiles, 0);
         if (rc) return rc;
-        const NextWeights nx_o = next_plan(lw + m.lo_o, d, m.kattn);
+        const NextWeights nx_o = fetch_ahead_narrow ? next_plan_narrow(lw + m.lo_o, d, m.kattn, 1) : next_plan(lw + m.lo_o, d, m.kattn);
         if (hd == 128) rc = launch_attn<128>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
         else if (hd == 64) rc = launch_attn<64>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
         else rc = launch_attn<32>(c, m, l, ntiles, NS, NS_head, scale_log2e, kv_bytes, nx_o);
@@ -519,7 +531,9 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             if (rc) return rc;
             a = base;
             a.W = (const uint4 *)(lw + m.lo_d); a.Xhi = w.xb_hi; a.Xlo = w.xb_lo; a.N = d;
-            if (l + 1 < mc.n_layers) a.nx = next_plan(lw + m.layer_bytes + m.lo_qkv, m.n_qkv, d);
+            if (l + 1 < mc.n_layers)
+                a.nx = fetch_ahead_narrow ? next_plan_narrow(lw + m.layer_bytes + m.lo_qkv, m.n_qkv, d, 2)
+                                          : next_plan(lw + m.layer_bytes + m.lo_qkv, m.n_qkv, d);
             rc = launch_gemm<EPI_RESID>(c, a, m.F, ntiles, 0);
             if (rc) return rc;
         } else {

@@ -99,13 +99,6 @@ __device__ __forceinline__ void load4_async(float &dst, const void *p) {
     asm volatile("global_load_dword %0, %1, off" : "=&v"(dst) : "v"(p) : "memory");
 }
 __device__ __forceinline__ void tie(float &r) { asm volatile("" : "+v"(r)); }
-// A load whose data nobody wants (it pulls a line into the L2).  `sink` is read and written by every such statement,
-// so the register stays reserved from its initialisation to the tie() behind the final wait: a write-only
-// destination is dead in the compiler's eyes right after the statement, and the register would be handed to the next
-// address computation while the load is still on its way.
-__device__ __forceinline__ void load16_discard(u32x4 &sink, const void *p) {
-    asm volatile("global_load_dwordx4 %0, %1, off ; discard" : "+v"(sink) : "v"(p) : "memory");
-}
 // at most `steps` x PER loads may still be outstanding (steps <= 4)
 template <int PER>
 __device__ __forceinline__ void wait_steps(int steps);
@@ -496,26 +489,51 @@ struct RowStat {   // per (row, column group) partial over 128 vocabulary entrie
     float gm; int gidx;      // max of z/T + Gumbel, its index (T > 0)
 };
 
+// A load whose data nobody wants: it pulls a line into the L2.  The data goes to LDS (lane l's 16 bytes land at
+// sink + 16 l: 1 KB per wave that the workgroup no longer needs), not to registers: a register that waits for a load
+// has to be kept away from the compiler's allocator until the data is back, and nothing in the language does that
+// across branches and loops.  The caller ends with wait_loads<0>(): the LDS must still be the workgroup's when the data
+// arrives.
+__device__ __forceinline__ void load16_discard(void *sink, const void *p) {
+    asm volatile("; fetch ahead");
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1))) *)p,
+                                     (void __attribute__((address_space(3))) *)sink, 16, 0, 0);
+}
+
 // What the NEXT launch of the stream will read first, for workgroups of this launch that have nothing left to do:
 // they pull it into their XCD's L2 while the launch's last workgroups finish (memory is idle then), so that the next
-// launch's first k-steps hit there.  Workgroup ids 8 apart share an XCD in both launches; next-launch workgroup j works
-// on column group j % ncg and K split j / ncg (k_gemm's grid order).
+// launch's first k-steps hit there.  Workgroup ids 8 apart share an XCD in both launches; workgroup j of this launch
+// fetches for workgroup j of the next.
+//   narrow_nb == 0 (k_gemm's grid order): next-launch workgroup j works on column group j % ncg and K split j / ncg;
+//     fetched: the first `span` bytes of the split's K range in each of the group's four 32-column blocks.
+//   narrow_nb = NB > 0 (k_gemm_narrow's order): j = 8 * ((p / 8) * Z + z) + p % 8 is row tile z of the group p of NB
+//     blocks, all of K; the Z workgroups of a group read the same (contiguous) NB * block_bytes: part z of Z is fetched.
 struct NextWeights {
     const char *base;          // the next launch's weight matrix, fragment layout; null: nothing to fetch
-    int nwg, ncg;              // its workgroups and column groups
+    int nwg, ncg;              // its workgroups and column groups (narrow: groups of NB blocks)
     int span;                  // bytes fetched per 32-column block, from the start of the split's K range
     long long block_bytes;     // one 32-column block: KS * 1024
     long long split_bytes;     // a split's K range within a block
+    int narrow_nb, Z;
 };
 
-__device__ __forceinline__ void prefetch_next(const NextWeights &nx) {
+// lds: 8 KB of LDS the workgroup is done with
+__device__ __forceinline__ void prefetch_next(const NextWeights &nx, void *lds) {
     if (!nx.base) return;
     // one next-launch workgroup per workgroup and no more: what is fetched must be back before this launch can end
     const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     const int tid = opaque_tid();
-    u32x4 sink = {0u, 0u, 0u, 0u};
-    tie(sink);
-    if (lin < nx.nwg) {
+    char *sink = (char *)lds + (__builtin_amdgcn_readfirstlane(tid >> 6) << 10);
+    if (lin < nx.nwg && nx.narrow_nb > 0) {
+        const int q8 = lin >> 3, z = q8 % nx.Z, grp = 8 * (q8 / nx.Z) + (lin & 7);
+        if (grp < nx.ncg) {
+            const int total = nx.narrow_nb * (int)nx.block_bytes;             // the group's blocks are adjacent
+            const int part = ((total / 16 + nx.Z - 1) / nx.Z) * 16;
+            const int end = min(total, (z + 1) * part);
+            const char *p0 = nx.base + (long long)grp * total;
+            for (int o = z * part + tid * 16; o < end; o += 512 * 16) load16_discard(sink, p0 + o);
+        }
+    } else if (lin < nx.nwg) {
         const int j = lin;
         const int cg = j % nx.ncg, sp = j / nx.ncg;
         const long long s_off = sp * nx.split_bytes;
@@ -525,13 +543,12 @@ __device__ __forceinline__ void prefetch_next(const NextWeights &nx) {
             for (int o = tid * 16; o < len; o += 512 * 16) load16_discard(sink, p0 + nb * nx.block_bytes + (o - tid * 16));
     }
     wait_loads<0>();
-    tie(sink);
 }
 
 // The same for the per-head attention launch that follows a QKV projection: its workgroups on XCD x work on kv head
 // x % Hkv (Hkv divides 8; one sequence), so this launch's idle workgroups on XCD x pull that head's old K and V^T blocks
 // — whole key tiles that this launch does not write — into its L2.
-__device__ __forceinline__ void prefetch_kv(const uint16_t *k, const uint16_t *vt, size_t head_stride, int Hkv, int bytes) {
+__device__ __forceinline__ void prefetch_kv(const uint16_t *k, const uint16_t *vt, size_t head_stride, int Hkv, int bytes, void *lds) {
     if (bytes <= 0) return;
     const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     const int nlin = gridDim.x * gridDim.y * gridDim.z;
@@ -539,14 +556,12 @@ __device__ __forceinline__ void prefetch_kv(const uint16_t *k, const uint16_t *v
     const int tid = opaque_tid();
     const size_t head = (size_t)((lin & 7) % Hkv) * head_stride;
     const char *kb = (const char *)(k + head), *vb = (const char *)(vt + head);
-    u32x4 sink = {0u, 0u, 0u, 0u};
-    tie(sink);
+    char *sink = (char *)lds + (__builtin_amdgcn_readfirstlane(tid >> 6) << 10);
     for (int o = ((lin >> 3) * 512 + tid) * 16; o < bytes; o += per_x * 8192) {   // the host bounds `bytes`: a few trips
         load16_discard(sink, kb + o);
         load16_discard(sink, vb + o);
     }
     wait_loads<0>();
-    tie(sink);
 }
 
 struct GemmArgs {
@@ -1136,8 +1151,9 @@ __device__ __forceinline__ void gemm_block(const GemmArgs &a, GemmSmem &sm, int 
     const bool last = arrive_last(a.counters + (size_t)z * ncg + cg, S, &sm.last);
     gemm_stamp(a, lin, 3);
     if (!last) {
-        if (EPI == EPI_QKV) prefetch_kv(a.kv.k, a.kv.vt, a.kv.head_stride, a.Hkv, a.kv_fetch_bytes);
-        else prefetch_next(a.nx);
+        // (sm.red is free: every wave has passed the barrier behind the wave sum)
+        if (EPI == EPI_QKV) prefetch_kv(a.kv.k, a.kv.vt, a.kv.head_stride, a.Hkv, a.kv_fetch_bytes, sm.red);
+        else prefetch_next(a.nx, sm.red);
         return;
     }
     gemm_finish<MT, EPI, COH, RSTD_EARLY>(a, sm, cg, z);
@@ -2240,7 +2256,7 @@ __device__ __forceinline__ void attn_head_item(const uint4 *Qhi, const uint4 *Ql
     }
     if (NS == 1) return;
     // the key range that arrives last at the head's counter merges all of them
-    if (!arrive_last(counters + t * Hq + head, NS, &as.last)) { prefetch_next(nx); return; }
+    if (!arrive_last(counters + t * Hq + head, NS, &as.last)) { prefetch_next(nx, as.slot); return; }
     if (w < 2 * HT) attn_head_merge<HD>(part, NS, Hq, scale_log2e, xhi, xlo, head, t, w >> 1, w & 1, lane);
 }
 
