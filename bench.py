@@ -484,7 +484,8 @@ def main():
     tv = np.median([e[1].elapsed_time(e[2]) for e in evs])
     ta = np.median([e[2].elapsed_time(e[3]) for e in evs])
 
-    # per-launch timing of the dominant kernel (weight-streaming GEMM) inside verify passes
+    # timing of the dominant kernel's launches (weight-streaming GEMM) inside verify passes: HIP events on the
+    # library's stream, one pair around each run of consecutive GEMM launches
     eng.debug_profile(True)
     n_prof = 3
     g_ms = g_bytes = a_ms = a_bytes = 0.0
@@ -540,7 +541,7 @@ def main():
                      "launches": int(g_n), "avg_launch_us": g_ms / max(g_n, 1) * 1e3,
                      "bytes_per_launch": g_bytes / max(g_n, 1),
                      # the same fraction from the kernel durations of the rocprofv3 trace summarised under profiles/
-                     # (HIP-event brackets around single launches read a few microseconds long)
+                     # (the event pair around each run of consecutive GEMM launches still reads somewhat long)
                      "frac_from_kernel_trace": (rec["algorithmic_bytes_per_launch"] / (rec["trace_avg_launch_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
                      if rec and rec.get("trace_avg_launch_us") else None,
                      "traffic_record": (rec.get("commit") if rec else None)},

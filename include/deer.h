@@ -191,9 +191,11 @@ const char *deer_last_error(const deer_ctx *c); /* c may be NULL: last init-time
  * or T > 0 in that pass.  Waits for the stream. */
 int deer_debug_get_logits(deer_ctx *c, int model, float *logits_host, size_t n_floats);
 
-/* Per-launch timing for the benchmark.  While enabled, every launch of the weight-streaming GEMM
- * (kernel_class 0) and of the block-attention kernel (kernel_class 1) is bracketed by HIP events
- * on the context's stream.  deer_debug_profile(c, on) waits for the stream, switches recording and forgets earlier
+/* Launch timing for the benchmark.  While enabled, the launches of the weight-streaming GEMM
+ * (kernel_class 0) and of the block-attention kernel (kernel_class 1) are bracketed by HIP events
+ * on the context's stream; launches of one class that follow each other directly share one pair of
+ * events (an event between two of them costs more than the gap it would measure), so the summed time
+ * includes the gaps inside such a run.  deer_debug_profile(c, on) waits for the stream, switches recording and forgets earlier
  * records; deer_debug_profile_read waits for the stream and returns, for one class, the summed event
  * time (ms), the number of launches, and their algorithmic bytes (weight bytes of each GEMM; K and V
  * rows visible to each attention launch). */

@@ -121,8 +121,12 @@ struct deer_ctx {
     std::string err;
     // optional per-launch timing (deer_debug_profile)
     bool prof_on = false;
-    struct ProfRec { int cls; hipEvent_t a, b; double bytes; };
+    struct ProfRec { int cls; hipEvent_t a, b; double bytes; int launches; };
     std::vector<ProfRec> prof;
+    int prof_open_cls = -1;          // a run of consecutive launches of one class is being timed
+    hipEvent_t prof_open_a = nullptr;
+    double prof_open_bytes = 0.0;
+    int prof_open_launches = 0;
     std::vector<hipEvent_t> ev_pool;
     size_t ev_used = 0;
 };
@@ -148,18 +152,31 @@ hipEvent_t prof_event(deer_ctx *c) {
     return c->ev_pool[c->ev_used++];
 }
 
-// brackets one launch with events when profiling is on
-struct ProfScope {
-    deer_ctx *c; int cls; double bytes; hipEvent_t a = nullptr;
-    ProfScope(deer_ctx *c_, int cls_, double bytes_) : c(c_), cls(cls_), bytes(bytes_) {
-        if (c->prof_on && (a = prof_event(c))) (void)hipEventRecord(a, c->stream);
-    }
-    ~ProfScope() {
-        if (!a) return;
-        hipEvent_t b = prof_event(c);
-        if (!b) return;
+// Timing of launches when profiling is on.  Launches of one class that follow each other directly on the stream (the
+// O, gate/up and down projections and the next layer's QKV projection) share one pair of events: an event between
+// two of them costs more than the gap it would measure.  prof_close() ends the run that is open; it is called before
+// a launch of another class, before every launch that is not timed, and before the records are read.
+void prof_close(deer_ctx *c) {
+    if (c->prof_open_cls < 0) return;
+    hipEvent_t b = prof_event(c);
+    if (b) {
         (void)hipEventRecord(b, c->stream);
-        c->prof.push_back({cls, a, b, bytes});
+        c->prof.push_back({c->prof_open_cls, c->prof_open_a, b, c->prof_open_bytes, c->prof_open_launches});
+    }
+    c->prof_open_cls = -1;
+}
+struct ProfScope {
+    ProfScope(deer_ctx *c, int cls, double bytes) {
+        if (!c->prof_on) return;
+        if (c->prof_open_cls != cls) {
+            prof_close(c);
+            hipEvent_t a = prof_event(c);
+            if (!a) return;
+            (void)hipEventRecord(a, c->stream);
+            c->prof_open_cls = cls; c->prof_open_a = a; c->prof_open_bytes = 0.0; c->prof_open_launches = 0;
+        }
+        c->prof_open_bytes += bytes;
+        c->prof_open_launches += 1;
     }
 };
 
@@ -437,6 +454,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
     c->cur_pass_model = model;
     hipStream_t s = c->stream;
     if (c->stamp_launch >= 0 && model == c->stamp_model) (void)hipMemsetAsync(w.stamps, 0, (size_t)STAMP_MAX_BLOCKS * 64, s);
+    prof_close(c);
     if (rows_desc) {
         hipLaunchKernelGGL(k_pass_begin, dim3(ncg_d + 1, ntiles), dim3(256), 0, s, *rows_desc, w.rm, (const uint16_t *)(m.w + m.off_embed),
                            w.h, w.xa_hi, w.xa_lo, w.ssq, d, ncg_d, m.ssq_sub, m.theta, w.cs, hd / 2);
@@ -545,6 +563,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
             rc = launch_gemm<EPI_ROUTER>(c, a, d, ntiles, 0);
             if (rc) return rc;
             const int cap = rows, chunks = ntiles;
+            prof_close(c);
             hipLaunchKernelGGL(k_moe_group, dim3(1), dim3(256), 0, s, w.route_e, w.rm.slot, rows, mc.top_k, mc.n_experts, cap,
                                w.exp_cnt, w.pair_row, w.pair_slot, w.moe_touched);
             LAUNCHCHK(c, "k_moe_group");
@@ -566,6 +585,7 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
                 hipLaunchKernelGGL(k_gemm_moe<MOE_DOWN>, dim3((d / CG + MOE_CGS - 1) / MOE_CGS, mc.n_experts, chunks), dim3(512), 0, s, ma);
             }
             LAUNCHCHK(c, "k_gemm_moe down");
+            prof_close(c);
             hipLaunchKernelGGL(k_moe_combine, dim3(ncg_d, ntiles), dim3(256), 0, s, w.moe_out, w.rm.slot, mc.top_k, w.h, w.xa_hi,
                                w.xa_lo, w.ssq, d);
             LAUNCHCHK(c, "k_moe_combine");
@@ -580,9 +600,11 @@ int run_pass(deer_ctx *c, int model, int ntiles, int max_limit, const LmPlan &lm
         a.logits = (c->p.keep_logits || lm.T > 0.f) ? w.logits[model] : nullptr;
         int rc = launch_gemm<EPI_LMHEAD>(c, a, d, lm.n_tiles, 1);
         if (rc) return rc;
+        prof_close(c);
         hipLaunchKernelGGL(k_rowstat_final, dim3(lm.n_tiles * lm.k), dim3(256), 0, s, w.stat, V / CG, lm.T, w.res[model], lm.k, lm.k_lo);
         LAUNCHCHK(c, "k_rowstat_final");
     }
+    prof_close(c);
     return DEER_OK;
 }
 
@@ -972,6 +994,7 @@ int deer_debug_get_logits(deer_ctx *c, int model, float *out, size_t n_floats) {
 
 int deer_debug_profile(deer_ctx *c, int enable) {
     if (!c) return DEER_EINVAL;
+    prof_close(c);
     HIPCHK(c, hipStreamSynchronize(c->stream));
     c->prof_on = enable != 0;
     c->prof.clear();
@@ -981,13 +1004,14 @@ int deer_debug_profile(deer_ctx *c, int enable) {
 
 int deer_debug_profile_read(deer_ctx *c, int kernel_class, double *total_ms, int64_t *launches, double *bytes) {
     if (!c || !total_ms || !launches || !bytes) return DEER_EINVAL;
+    prof_close(c);
     HIPCHK(c, hipStreamSynchronize(c->stream));
     *total_ms = 0.0; *launches = 0; *bytes = 0.0;
     for (const auto &r : c->prof) {
         if (r.cls != kernel_class) continue;
         float ms = 0.f;
         HIPCHK(c, hipEventElapsedTime(&ms, r.a, r.b));
-        *total_ms += ms; *launches += 1; *bytes += r.bytes;
+        *total_ms += ms; *launches += r.launches; *bytes += r.bytes;
     }
     return DEER_OK;
 }
