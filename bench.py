@@ -338,6 +338,33 @@ def run_no_kv_cache(args):
                       "by_batch": rows}))
 
 
+def run_hbm_read_probe(args):
+    """What a plain read kernel achieves on this GPU by buffer size (deer_debug_stream_read): context for the
+    `roofline` fractions, which are quoted against the published 8 TB/s.  Buffers of up to 32 MB are served by the
+    L2s when read again, up to 256 MB by the memory-side cache; the weights of a pass (15 GB) fit neither."""
+    import torch
+    from paper_2512_15176_amd import DeerEngine
+    cfg = di.CONFIGS["tiny"]
+    t, d, k = cfg["target"], cfg["drafter"], cfg["k"]
+    eng = DeerEngine(t, d, 1, 256, k, di.mask_token_id(t.vocab), -1, False)
+    buf = torch.ones(2 << 30, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    rows = []
+    for nt in (0, 1):
+        for wgs in (2048, 8192):
+            for mb in (16, 32, 64, 128, 256, 512, 1024, 2048):
+                ms = eng.debug_stream_read(buf, mb << 20, wgs, nt, 20)
+                rows.append({"MB": mb, "workgroups": wgs, "nontemporal": nt, "us": ms * 1e3, "GBs": (mb << 20) / (ms * 1e-3) / 1e9})
+    eng.close()
+    best = {}
+    for r in rows:
+        if r["MB"] not in best or r["GBs"] > best[r["MB"]]["GBs"]:
+            best[r["MB"]] = r
+    print(json.dumps({"metric": "plain read kernel, GB/s by buffer size (20 launches back to back, launch gaps included)",
+                      "unit": "GB/s", "n_gpus": 1, "best_by_MB": {str(mb): round(best[mb]["GBs"], 1) for mb in sorted(best)},
+                      "rows": rows}))
+
+
 def run_gemm_stamps(args):
     """Where the weight-streaming GEMM launches of one layer spend their time (device-clock stamps recorded by the
     workgroups themselves, deer_debug_gemm_stamps): headline workload, layer 1 of the target and of the drafter."""
@@ -387,7 +414,7 @@ def main():
                     help="profiling aid: declare the prefix prefilled without running the models (zero caches)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="profiling aid: also run one plain 1 GiB device copy (scale factor for byte counters)")
-    ap.add_argument("--mode", default="step", choices=["step", "no_kv_cache", "gemm_stamps"],
+    ap.add_argument("--mode", default="step", choices=["step", "no_kv_cache", "gemm_stamps", "hbm_read_probe"],
                     help="step: the draft-verify step (default, the benchmark line); no_kv_cache: the paper's batch experiment "
                          "setting, every iteration recomputes the sequence (its own JSON line)")
     ap.add_argument("--steps-nokv", type=int, default=3)
@@ -399,6 +426,8 @@ def main():
 
     if args.mode == "no_kv_cache":
         return run_no_kv_cache(args)
+    if args.mode == "hbm_read_probe":
+        return run_hbm_read_probe(args)
     if args.mode == "gemm_stamps":
         return run_gemm_stamps(args)
 
@@ -503,6 +532,11 @@ def main():
         a_ms, a_n, a_bytes = a_ms + r1[0], a_n + r1[1], a_bytes + r1[2]
         _, com, _ = eng.accept_and_commit(k, T, di.SAMPLING_SEED)
     eng.debug_profile(False)
+    # what a plain read kernel sustains on this GPU for a buffer that fits no cache (1 GiB, non-temporal loads, 8192
+    # workgroups, 20 launches back to back): context for the fractions below, which are quoted against the published peak
+    probe = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+    plain_read_gbs = (1 << 30) / (eng.debug_stream_read(probe, 1 << 30, 8192, 1, 20) * 1e-3) / 1e9
+    del probe
     wbytes, kvbytes = verify_bytes(t, prefix, k, B)
     experts_per_layer = None
     if t.n_experts:   # the experts a verify pass really streamed (mean over the profiled passes) instead of the expectation
@@ -544,7 +578,8 @@ def main():
                      # (the event pair around each run of consecutive GEMM launches still reads somewhat long)
                      "frac_from_kernel_trace": (rec["algorithmic_bytes_per_launch"] / (rec["trace_avg_launch_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS)
                      if rec and rec.get("trace_avg_launch_us") else None,
-                     "traffic_record": (rec.get("commit") if rec else None)},
+                     "traffic_record": (rec.get("commit") if rec else None),
+                     "plain_read_kernel_GBs": plain_read_gbs},
         "attention_kernel": {"launches": int(a_n), "avg_launch_us": a_ms / max(a_n, 1) * 1e3,
                              "GBs": a_bytes / max(a_ms * 1e-3, 1e-12) / 1e9},
     }

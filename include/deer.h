@@ -229,6 +229,15 @@ int deer_debug_route_spread(deer_ctx *c, int enable);
  * count - the data-dependent part of a pass's algorithmic bytes.  0 for dense models.  Waits for the stream. */
 int deer_debug_experts_streamed(deer_ctx *c, int64_t *pairs);
 
+/* Measurement aid: the rate at which a plain kernel reads a buffer, i.e. what "streaming at memory speed" means for
+ * that size on this chip (buffers up to the 32 MB of L2 or the 256 MB memory-side cache are served from there when
+ * read again).  Reads `bytes` (a multiple of 16) of caller-owned device memory at buf_dev (16-byte aligned) with
+ * `workgroups` workgroups of 512 threads, plain or non-temporal loads, 3 untimed launches and then `reps` timed ones
+ * back to back on the context's stream (launch gaps included); *ms_per_read = mean time of one launch.  Must not
+ * run while launch timing (deer_debug_profile) is on.  Waits for the stream. */
+int deer_debug_stream_read(deer_ctx *c, const void *buf_dev, size_t bytes, int32_t workgroups, int32_t nontemporal,
+                           int32_t reps, float *ms_per_read);
+
 /* Debugging aid: where a weight-streaming GEMM launch spends its time.  Copies the stamps recorded so far
  * (2 x 2048 workgroup rows x 8 ticks of the 100 MHz device clock: the first 2048 rows belong to the chosen launch,
  * the second 2048 to the streaming GEMM launched after it, so that the hand-over between two kernels can be seen;

@@ -19,7 +19,8 @@ EXPORTS = ["deer_query_sizes", "deer_init_models", "deer_load_tensor", "deer_pre
            "deer_debug_get_logits", "deer_get_lengths", "deer_get_kv_layout", "deer_debug_profile",
            "deer_debug_profile_read", "deer_debug_force_commit", "deer_debug_load_kv", "deer_set_bonus_token",
            "deer_draft_block_multipass", "deer_debug_gemm_tiled",
-           "deer_debug_gemm_stamps", "deer_debug_experts_streamed", "deer_debug_route_spread"]
+           "deer_debug_gemm_stamps", "deer_debug_experts_streamed", "deer_debug_route_spread",
+           "deer_debug_stream_read"]
 
 
 class DeerError(RuntimeError):
@@ -81,6 +82,7 @@ def load_library(path: str = LIB_PATH):
     lib.deer_destroy.argtypes = [C.c_void_p]
     lib.deer_debug_route_spread.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_experts_streamed.argtypes = [C.c_void_p, C.c_void_p]
+    lib.deer_debug_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_float)]
     lib.deer_debug_gemm_stamps.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int32, C.c_void_p]
     lib.deer_set_bonus_token.argtypes = [C.c_void_p, C.c_int]
     lib.deer_debug_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]
@@ -270,6 +272,15 @@ class DeerEngine:
 
     def debug_route_spread(self, enable):
         self._check(self.lib.deer_debug_route_spread(self.ctx, int(bool(enable))))
+
+    def debug_stream_read(self, buf, nbytes, workgroups, nontemporal, reps):
+        """Mean milliseconds per launch of a plain read of the first nbytes of the device tensor buf."""
+        if not buf.is_cuda or not buf.is_contiguous() or nbytes > buf.numel() * buf.element_size():
+            raise ValueError("debug_stream_read needs a contiguous device tensor of at least nbytes")
+        ms = C.c_float(0.0)
+        self._check(self.lib.deer_debug_stream_read(self.ctx, C.c_void_p(buf.data_ptr()), nbytes, workgroups, int(bool(nontemporal)),
+                                                    reps, C.byref(ms)))
+        return ms.value
 
     def debug_experts_streamed(self):
         n = C.c_int64(0)

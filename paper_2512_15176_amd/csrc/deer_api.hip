@@ -1047,6 +1047,33 @@ int deer_debug_experts_streamed(deer_ctx *c, int64_t *pairs) {
     return DEER_OK;
 }
 
+int deer_debug_stream_read(deer_ctx *c, const void *buf_dev, size_t bytes, int32_t workgroups, int32_t nontemporal,
+                           int32_t reps, float *ms_per_read) {
+    if (!c || !ms_per_read) return DEER_EINVAL;
+    if (!buf_dev || bytes < 16 || bytes % 16 || ((uintptr_t)buf_dev & 15)) return fail(c, DEER_EINVAL, "buffer must be 16-byte aligned, a multiple of 16 bytes");
+    if (workgroups < 1 || workgroups > (1 << 20) || reps < 1 || reps > 10000) return fail(c, DEER_EINVAL, "bad workgroups / reps");
+    if (c->prof_on) return fail(c, DEER_ESTATE, "launch timing is on");
+    uint32_t *out = (uint32_t *)c->wk.stamps;   // a word of the debugging buffer
+    const size_t n = bytes / 16;
+    auto launch = [&]() {
+        if (nontemporal) hipLaunchKernelGGL(k_stream_read<true>, dim3((unsigned)workgroups), dim3(512), 0, c->stream, (const u32x4 *)buf_dev, n, out);
+        else hipLaunchKernelGGL(k_stream_read<false>, dim3((unsigned)workgroups), dim3(512), 0, c->stream, (const u32x4 *)buf_dev, n, out);
+    };
+    for (int i = 0; i < 3; ++i) launch();
+    LAUNCHCHK(c, "k_stream_read");
+    hipEvent_t e0 = prof_event(c), e1 = prof_event(c);
+    if (!e0 || !e1) return fail(c, DEER_EHIP, "hipEventCreate failed");
+    HIPCHK(c, hipEventRecord(e0, c->stream));
+    for (int i = 0; i < reps; ++i) launch();
+    HIPCHK(c, hipEventRecord(e1, c->stream));
+    HIPCHK(c, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+    c->ev_used -= 2;   // the two events go back to the pool
+    *ms_per_read = ms / (float)reps;
+    return DEER_OK;
+}
+
 int deer_debug_gemm_tiled(deer_ctx *c, int min_tiles) {
     if (!c) return DEER_EINVAL;
     if (min_tiles < 0) return fail(c, DEER_EINVAL, "min_tiles must not be negative");

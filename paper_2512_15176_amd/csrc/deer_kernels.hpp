@@ -276,6 +276,28 @@ __global__ void k_convert_rows(const SrcT *__restrict__ src, uint16_t *__restric
     if (i < n) dst[i] = (uint16_t)load_as_bf16<SrcT>(src + i);
 }
 
+// Measurement aid: a plain read of n 16-byte vectors (grid-stride, four loads in flight per thread and trip), the rate
+// of which is what "streaming at memory speed" means for a buffer of that size on this chip.  Nothing is written
+// unless the data has one particular checksum (so that the loads cannot be dropped).
+template <bool NT>
+__global__ __launch_bounds__(512) void k_stream_read(const u32x4 *__restrict__ p, size_t n, uint32_t *out) {
+    size_t i = (size_t)blockIdx.x * 512 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 512;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        u32x4 v0, v1, v2, v3;
+        if (NT) {
+            v0 = __builtin_nontemporal_load(p + i); v1 = __builtin_nontemporal_load(p + i + stride);
+            v2 = __builtin_nontemporal_load(p + i + 2 * stride); v3 = __builtin_nontemporal_load(p + i + 3 * stride);
+        } else {
+            v0 = p[i]; v1 = p[i + stride]; v2 = p[i + 2 * stride]; v3 = p[i + 3 * stride];
+        }
+        acc ^= v0 ^ v1 ^ v2 ^ v3;
+    }
+    for (; i < n; i += stride) acc ^= p[i];
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) out[0] = 1u;
+}
+
 __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
