@@ -174,3 +174,31 @@ def test_sequence_runs_up_to_the_cache_capacity(weights):
     got, want = _lockstep(eng, pair, 4, [list(truth[18:22])], torch)   # a shorter block still fits (58 + 4 <= 64)
     assert got == want == truth[18:22]
     eng.close()
+
+
+def test_read_rate_probe_runs_and_checks_its_arguments(weights):
+    """deer_debug_stream_read: a measurement aid that reads a caller's buffer; it must time something, refuse sizes
+    and alignments its kernel does not handle, and refuse to run while launch timing uses the same events."""
+    import torch
+    from paper_2512_15176_amd import DeerError
+    t, d = CFG["target"], CFG["drafter"]
+    wt, wd = weights
+    eng = make_engine(t, d, wt, wd, 1, 64, 4)
+    buf = torch.ones(8 << 20, dtype=torch.uint8, device="cuda")
+    for nt in (0, 1):
+        ms = eng.debug_stream_read(buf, 8 << 20, 256, nt, 3)
+        assert 0.0 < ms < 50.0
+    assert eng.debug_stream_read(buf, 16, 1, 0, 1) > 0.0            # one vector, ragged against the grid
+    with pytest.raises(DeerError):
+        eng.debug_stream_read(buf, (8 << 20) - 8, 256, 0, 3)        # not a multiple of 16
+    with pytest.raises(DeerError):
+        eng.debug_stream_read(buf[8:], 1 << 20, 256, 0, 3)          # not 16-byte aligned
+    with pytest.raises(ValueError):
+        eng.debug_stream_read(buf, (8 << 20) + 16, 256, 0, 3)       # beyond the tensor
+    with pytest.raises(DeerError):
+        eng.debug_stream_read(buf, 1 << 20, 0, 0, 3)
+    eng.debug_profile(True)
+    with pytest.raises(DeerError):
+        eng.debug_stream_read(buf, 1 << 20, 256, 0, 3)
+    eng.debug_profile(False)
+    eng.close()
